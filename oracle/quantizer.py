@@ -1,0 +1,94 @@
+"""Quantizer, packing and bit-width shrinking of the oracle (test infrastructure).
+
+Notation follows the paper: X the 16-bit tensor, Z the zero point, S the scaling factor,
+b the bit-width, X_b the b-bit integer tensor.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+LEVELS = {8: 255, 4: 15, 2: 3}
+
+
+def quantize(x: np.ndarray, b: int, group: int):
+    """Asymmetric uniform group-wise quantization (Sec. 2.2, Eq. 1 and Eq. 2).
+
+    x: fp16 [..., D]; a group is `group` consecutive channels of one token of one head.
+    Z = min(X) per group, S = (max(X) - Z) / (2^b - 1); both are stored as fp16.  The
+    subtraction and the division for S are single IEEE fp32 operations and S is rounded
+    to nearest-even into fp16; the codes are round-to-nearest-even of (X - Z) / S in fp32
+    with the *stored* S, clamped to [0, 2^b - 1].  A group with S == 0 has all codes 0.
+    Returns (codes uint8 [..., D], S fp16 [..., D/group], Z fp16 [..., D/group]).
+    """
+    assert x.dtype == np.float16 and b in LEVELS and x.shape[-1] % group == 0
+    assert np.all(np.isfinite(x))
+    g = x.reshape(x.shape[:-1] + (x.shape[-1] // group, group))
+    Z = g.min(axis=-1)
+    mx = g.max(axis=-1)
+    S32 = (mx.astype(np.float32) - Z.astype(np.float32)) / np.float32(LEVELS[b])
+    S = S32.astype(np.float16)
+    assert np.all(np.isfinite(S))
+    Sf = S.astype(np.float32)[..., None]
+    num = g.astype(np.float32) - Z.astype(np.float32)[..., None]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        r = np.rint(num / Sf)
+    r = np.where(Sf == 0, np.float32(0), r)
+    codes = np.clip(r, 0, LEVELS[b]).astype(np.uint8)
+    return codes.reshape(x.shape), S, Z
+
+
+def dequantize(codes: np.ndarray, S: np.ndarray, Z: np.ndarray, group: int) -> np.ndarray:
+    """X_hat = X_b * S + Z in fp64 (exact: <= 8-bit code times 11-bit significand)."""
+    ng = codes.shape[-1] // group
+    c = codes.reshape(codes.shape[:-1] + (ng, group)).astype(np.float64)
+    out = c * S.astype(np.float64)[..., None] + Z.astype(np.float64)[..., None]
+    return out.reshape(codes.shape)
+
+
+def shrink_codes(x2b: np.ndarray, b: int) -> np.ndarray:
+    """Equivalent Right Shift (Sec. 3.1, Eq. 3): X_b = ((2^{2b} - 2^b + 1)(X_{2b} + 2^{b-1})) >> 3b.
+
+    x2b holds 2b-bit codes; b is the target width.  Evaluated in unsigned 64-bit integers.
+    """
+    assert b in (8, 4, 2)
+    x = x2b.astype(np.uint64)
+    mult = np.uint64((1 << (2 * b)) - (1 << b) + 1)
+    y = (mult * (x + np.uint64(1 << (b - 1)))) >> np.uint64(3 * b)
+    return y.astype(x2b.dtype)
+
+
+def shrink_scale(S2b: np.ndarray, b: int) -> np.ndarray:
+    """S_b = (2^b + 1) S_{2b} (Sec. 3.1, below Eq. 3); the fp32 product is rounded to fp16.  Z is kept."""
+    out = (S2b.astype(np.float32) * np.float32((1 << b) + 1)).astype(np.float16)
+    assert np.all(np.isfinite(out))
+    return out
+
+
+def pack_codes(codes: np.ndarray, b: int) -> np.ndarray:
+    """Canonical packing: element i of a row sits at bit offset (i*b) mod 8 of byte (i*b)//8, low bits first."""
+    per = 8 // b
+    c = codes.reshape(codes.shape[:-1] + (codes.shape[-1] // per, per)).astype(np.uint16)
+    out = np.zeros(c.shape[:-1], np.uint16)
+    for j in range(per):
+        out |= c[..., j] << (j * b)
+    return out.astype(np.uint8)
+
+
+def unpack_codes(packed: np.ndarray, b: int) -> np.ndarray:
+    per = 8 // b
+    out = np.empty(packed.shape + (per,), np.uint8)
+    for j in range(per):
+        out[..., j] = (packed >> (j * b)) & ((1 << b) - 1)
+    return out.reshape(packed.shape[:-1] + (packed.shape[-1] * per,))
+
+
+def bytes_per_token_head(bits: int, head_dim: int, group: int, count_metadata: bool) -> int:
+    """Bytes one cached token of one KV head occupies, K and V together.
+
+    Codes: 2 * head_dim * bits / 8.  Quantized widths also carry one fp16 (S, Z) pair per
+    group for K and for V when metadata is counted.
+    """
+    n = 2 * head_dim * bits // 8
+    if count_metadata and bits < 16:
+        n += 2 * (head_dim // group) * 4
+    return n
