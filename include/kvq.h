@@ -1,0 +1,159 @@
+/*
+ * kvq.h -- C ABI of libkvq: decode attention over a progressively quantized KV cache on AMD MI355X (gfx950).
+ *
+ * The library implements the online half of PM-KVQ (arXiv 2505.18610): tokens enter a transformer block's
+ * KV cache at 16 bits; when the block's byte budget would be exceeded the bit-width of the existing cache
+ * is halved, 16 -> 8 -> 4 -> 2, never below the block's final bit-width "Fbit" (Sec. 3.1); single-token
+ * grouped-query attention reads the mixed-width cache directly.
+ *
+ * Conventions for every entry point
+ *   - Pointers named *_dev are device (HIP) pointers, *_host are host pointers.  No entry point takes or
+ *     returns a framework type.
+ *   - The caller owns the arena, the q/k/v/out buffers and the stream.  The library owns the kvq_cache_t
+ *     (host tables) and sub-allocates inside the arena; it never allocates or frees device memory.
+ *   - Every kernel is enqueued on the given HIP stream (hipStream_t passed as void*, NULL = default stream)
+ *     and no entry point synchronises, except kvq_cache_export_segment which copies to the host.
+ *   - All calls on one cache must be issued from one thread at a time and on one stream (the host tables
+ *     are updated at enqueue time, the device tables in stream order).
+ *   - Errors are reported as kvq_status_t; argument, state and budget errors are detected on the host before
+ *     anything is enqueued and leave the cache unchanged.  Nothing throws or aborts across this boundary.
+ *   - All sequences of a batch have the same length and share one page table per block.
+ *   - head_dim is 128, group is 32 channels, 1 <= n_q_heads / n_kv_heads <= 16.
+ */
+#ifndef KVQ_H
+#define KVQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvq_cache kvq_cache_t;
+
+typedef enum {
+    KVQ_OK = 0,
+    KVQ_E_INVALID = 1, /* null pointer, bad shape, bits not in {16,8,4,2}, unsupported config            */
+    KVQ_E_BUDGET = 2,  /* the append would exceed the block's byte budget (nothing was written), or a    */
+                       /* shrink was asked for but the policy has nothing left to lower above Fbit        */
+    KVQ_E_OOM = 3,     /* the arena has no free block of the needed size                                  */
+    KVQ_E_STATE = 4,   /* the call does not fit the cache state (width change inside a page, max_tokens   */
+                       /* exceeded, no such segment, compute call on an accounting-only cache)            */
+    KVQ_E_HIP = 5      /* a HIP runtime call or kernel launch failed                                      */
+} kvq_status_t;
+
+enum { KVQ_POLICY_PAPER = 0, KVQ_POLICY_OLDEST_FIRST = 1 };
+enum { KVQ_WHICH_K = 0, KVQ_WHICH_V = 1 };
+
+typedef struct {
+    int32_t n_layers;      /* transformer blocks sharing the arena                                        */
+    int32_t batch;         /* sequences (all of equal length)                                             */
+    int32_t n_q_heads;     /* query heads; query head h reads KV head h / (n_q_heads / n_kv_heads)        */
+    int32_t n_kv_heads;
+    int32_t head_dim;      /* must be 128                                                                 */
+    int32_t group;         /* quantization group: consecutive channels of one token of one head; 32       */
+    int32_t max_tokens;    /* maximum context length per sequence                                         */
+    int32_t window;        /* most recent tokens kept at 16 bits (Sec. 4.1.2); multiple of page_tokens    */
+    int32_t n_sink;        /* first tokens kept at 16 bits (Sec. 4.1.2); multiple of page_tokens          */
+    int32_t page_tokens;   /* bookkeeping and allocation granularity in tokens; multiple of 32            */
+    int32_t policy;        /* KVQ_POLICY_*                                                                */
+    int32_t count_metadata_in_budget; /* 1: scales and zero points count toward the byte budget           */
+} kvq_config_t;
+
+typedef struct {
+    int32_t token_begin;   /* first token of the run                                                      */
+    int32_t token_end;     /* one past its last token                                                     */
+    int32_t bits;          /* 16, 8, 4 or 2                                                               */
+} kvq_segment_info_t;
+
+/* Arena size (bytes) that holds the library's device tables plus `payload_bytes` of cache pages.
+ * payload_bytes is rounded up to whole allocation blocks.  Returns 0 on an invalid config. */
+uint64_t kvq_arena_bytes(const kvq_config_t* cfg, uint64_t payload_bytes);
+
+/* Bytes one cached token of one KV head occupies at `bits`, K and V together (codes, plus one fp16
+ * scale/zero pair per group for K and for V when count_metadata != 0).  This is the Mem(.) of Sec. 3.2
+ * as the library accounts it.  Returns 0 for bits outside {16,8,4,2}. */
+uint64_t kvq_bytes_per_token_head(int32_t bits, int32_t head_dim, int32_t group, int32_t count_metadata);
+
+/* Create a cache over a caller-owned device arena (Sec. 3.1: per-block Fbit and byte budget).
+ *   block_budget_bytes_host[n_layers], block_fbit_host[n_layers] (each 16, 8, 4 or 2): host arrays, copied.
+ *   arena_dev: device memory of arena_bytes bytes, 256-byte aligned; must outlive the cache.  The library
+ *   enqueues nothing here; device tables are initialised lazily in stream order.
+ *   arena_dev == NULL creates an accounting-only cache: append/requant update the host tables exactly as
+ *   they would, launch nothing, and kvq_decode_attention / export return KVQ_E_STATE (capacity planning).
+ * Returns KVQ_E_INVALID for an unsupported config, KVQ_E_OOM if the arena cannot hold the device tables. */
+kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_budget_bytes_host,
+                              const uint8_t* block_fbit_host, void* arena_dev, uint64_t arena_bytes,
+                              kvq_cache_t** out);
+
+/* Frees the host tables.  Work already enqueued keeps running; the arena is the caller's. */
+void kvq_cache_destroy(kvq_cache_t* cache);
+
+/* Quantize-on-append (Sec. 2.2 Eq. 1-2; Sec. 3.1).
+ *   k_dev, v_dev: fp16 [batch, n_kv_heads, n_new, head_dim], contiguous; keys already carry RoPE.
+ *   entry_bits: 0 = the policy's entry width (16 while a window is configured or under OLDEST_FIRST, else
+ *   the block's current width); 16/8/4/2 = store at exactly that width (state construction).  A width that
+ *   differs from the partially filled last page's width is KVQ_E_STATE.
+ *   Quantized widths use asymmetric min-max per group: Z = min, S = (max - Z)/(2^b - 1) in fp32 rounded to
+ *   fp16, code = rne((x - Z)/S) with the stored S, clamped; S == 0 gives code 0.
+ *   Under KVQ_POLICY_PAPER with a window, pages leaving the window are quantized to the block's current
+ *   width inside this call.  KVQ_E_BUDGET (cache unchanged) if bytes after the append exceed the budget. */
+kvq_status_t kvq_quantize_append(kvq_cache_t* cache, int32_t layer, const void* k_dev, const void* v_dev,
+                                 int32_t n_new, int32_t entry_bits, void* hip_stream);
+
+/* Progressive bit-width shrinking (Sec. 3.1 Eq. 3, appendix theorem):
+ *   X_b = ((2^2b - 2^b + 1)(X_2b + 2^(b-1))) >> 3b,  S_b = fp16((2^b + 1) S_2b),  Z_b = Z_2b;
+ *   pages still holding raw fp16 values are quantized directly to 8 bits (Eq. 1-2), which by the theorem
+ *   is what an integer 16-bit tier followed by Eq. 3 would give.
+ *   segment >= 0: lower every page of that run (kvq_cache_describe order) one step; KVQ_E_STATE if it is
+ *   already at 2 bits or does not exist.
+ *   segment == -1, KVQ_POLICY_PAPER: halve the block's current width: every page at that width outside the
+ *   sink and the window is lowered one step.  KVQ_E_BUDGET if the block is already at Fbit.
+ *   segment == -1, KVQ_POLICY_OLDEST_FIRST: while bytes_used + reserve_tokens 16-bit tokens exceed the
+ *   budget, lower the oldest complete page outside sink/window whose width is above Fbit by one step;
+ *   KVQ_E_BUDGET when none is left (steps already taken stay).
+ *   *n_pages_done (may be NULL) receives the number of page re-quantizations enqueued. */
+kvq_status_t kvq_progressive_requant(kvq_cache_t* cache, int32_t layer, int32_t segment,
+                                     int32_t reserve_tokens, void* hip_stream, int32_t* n_pages_done);
+
+/* Single-token GQA decode attention over the block's whole cache (no mask; append the current token first):
+ *   out[b, h, :] = softmax_t( q[b, h, :] . K_hat[b, h/g, t, :] * softmax_scale ) V_hat[b, h/g, t, :]
+ *   with X_hat = code * S + Z (or the raw fp16 value).  fp16 operands, fp32 accumulation.
+ *   q_dev: fp16 [batch, n_q_heads, head_dim]; out_dev: [batch, n_q_heads, head_dim], fp32 if out_is_fp32
+ *   else fp16; softmax_scale 0 means 1/sqrt(head_dim).  KVQ_E_STATE if the block is empty. */
+kvq_status_t kvq_decode_attention(kvq_cache_t* cache, int32_t layer, const void* q_dev, void* out_dev,
+                                  int32_t out_is_fp32, float softmax_scale, void* hip_stream);
+
+/* Bookkeeping read-out (host only): maximal runs of pages with equal width, oldest first.
+ *   segs_host[cap] receives min(cap, *n) entries; n, bytes_used, n_tokens, current_bits may each be NULL.
+ *   bytes_used = sum over tokens of batch * n_kv_heads * kvq_bytes_per_token_head(bits of that token). */
+kvq_status_t kvq_cache_describe(const kvq_cache_t* cache, int32_t layer, kvq_segment_info_t* segs_host,
+                                int32_t cap, int32_t* n, uint64_t* bytes_used, int32_t* n_tokens,
+                                int32_t* current_bits);
+
+/* Copies one run of K (which = KVQ_WHICH_K) or V to the host in the canonical format, synchronising the
+ * stream.  n = token_end - token_begin, D = head_dim, G = group:
+ *   16-bit run: codes_host receives fp16 [batch, n_kv_heads, n, D]; scales/zeros are not written.
+ *   b-bit run : codes_host uint8 [batch, n_kv_heads, n, D*b/8], element i of a row at bit (i*b)%8 of byte
+ *               (i*b)/8, low bits first; scales_host and zeros_host fp16 [batch, n_kv_heads, n, D/G]. */
+kvq_status_t kvq_cache_export_segment(kvq_cache_t* cache, int32_t layer, int32_t segment, int32_t which,
+                                      void* codes_host, void* scales_host, void* zeros_host,
+                                      void* hip_stream);
+
+/* Tuning options (the results do not depend on them beyond floating-point summation order).
+ *   KVQ_OPT_SPLITS: number of token-range splits kvq_decode_attention uses per (sequence, KV head),
+ *                   1..128; 0 restores the automatic choice.
+ *   KVQ_OPT_FUSED_MERGE: 1 = the last workgroup of a (sequence, KV head) merges the split partials inside
+ *                   the attention kernel; 0 = a second small kernel does. */
+enum { KVQ_OPT_SPLITS = 0, KVQ_OPT_FUSED_MERGE = 1 };
+kvq_status_t kvq_cache_set_option(kvq_cache_t* cache, int32_t option, int32_t value);
+
+/* Free bytes left in the arena's page area (host bookkeeping). */
+uint64_t kvq_cache_arena_free_bytes(const kvq_cache_t* cache);
+
+const char* kvq_status_string(kvq_status_t s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQ_H */

@@ -1,0 +1,678 @@
+// Host side of libkvq: configuration checks, byte-budget accounting, shrink policies (Sec. 3.1), the page
+// allocator over the caller's arena, device table maintenance and the C ABI declared in include/kvq.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <set>
+#include <vector>
+
+#include "../../include/kvq.h"
+#include "kvq_internal.h"
+
+namespace {
+
+constexpr int kMaxOrder = 4;  // allocation blocks of 1, 2, 4, 8, 16 units; a unit is one metadata block
+constexpr uint64_t kRingBytes = 4u << 20;
+
+int order_of_bits(int bits) { return bits == 16 ? 4 : bits == 8 ? 3 : bits == 4 ? 2 : 1; }
+bool valid_bits(int b) { return b == 16 || b == 8 || b == 4 || b == 2; }
+
+// Buddy allocator in units.  Code blocks need 2^order units (2-bit: 2, 4-bit: 4, 8-bit: 8, 16-bit: 16),
+// metadata blocks one unit, so every size is a power of two and freed space coalesces without compaction.
+class Buddy {
+public:
+    void init(uint32_t n_super) {
+        for (auto& f : free_) f.clear();
+        for (uint32_t i = 0; i < n_super; ++i) free_[kMaxOrder].insert(i << kMaxOrder);
+        total_ = (uint64_t)n_super << kMaxOrder;
+        free_units_ = total_;
+    }
+    bool alloc(int order, uint32_t* off) {
+        int o = order;
+        while (o <= kMaxOrder && free_[o].empty()) ++o;
+        if (o > kMaxOrder) return false;
+        uint32_t blk = *free_[o].begin();
+        free_[o].erase(free_[o].begin());
+        while (o > order) {
+            --o;
+            free_[o].insert(blk + (1u << o));
+        }
+        free_units_ -= 1u << order;
+        *off = blk;
+        return true;
+    }
+    void release(uint32_t off, int order) {
+        free_units_ += 1u << order;
+        while (order < kMaxOrder) {
+            uint32_t buddy = off ^ (1u << order);
+            auto it = free_[order].find(buddy);
+            if (it == free_[order].end()) break;
+            free_[order].erase(it);
+            off = std::min(off, buddy);
+            ++order;
+        }
+        free_[order].insert(off);
+    }
+    uint64_t free_units() const { return free_units_; }
+
+private:
+    std::set<uint32_t> free_[kMaxOrder + 1];
+    uint64_t total_ = 0, free_units_ = 0;
+};
+
+struct Page {
+    int bits = 16;
+    int n = 0;              // tokens stored
+    uint32_t code_unit = 0; // allocation offsets in units
+    uint32_t meta_unit = 0; // valid when bits < 16
+};
+
+struct Layer {
+    uint64_t budget = 0;
+    int fbit = 2;
+    int T = 0;
+    std::vector<Page> pages;
+    // split plan cache of kvq_decode_attention
+    int plan_tiles = -1, plan_splits = 0;
+    uint64_t version = 0, plan_version = ~0ull;
+    int32_t split_begin[KVQ_MAX_SPLITS + 1];
+};
+
+}  // namespace
+
+struct kvq_cache {
+    kvq_config_t cfg;
+    int units = 0, tpp = 0, gqa = 0, max_pages = 0;
+    bool dry = false;
+    uint8_t* arena = nullptr;
+    uint64_t arena_bytes = 0;
+    uint64_t unit_bytes = 0;
+    uint64_t table_off = 0, jobs_off = 0, part_o_off = 0, part_ml_off = 0, counters_off = 0, pages_off = 0;
+    Buddy buddy;
+    std::vector<Layer> layers;
+    uint8_t* ring = nullptr;
+    uint64_t ring_pos = 0;
+    bool device_ready = false;
+    int splits_override = 0;
+    int fused_merge = 0;
+    int target_workgroups = 512;
+
+    uint64_t bpth(int bits) const {
+        return kvq_bytes_per_token_head(bits, cfg.head_dim, cfg.group, cfg.count_metadata_in_budget);
+    }
+    uint64_t unit_off_bytes(uint32_t unit) const { return pages_off + (uint64_t)unit * unit_bytes; }
+    KvqPageDesc desc(const Page& p) const {
+        KvqPageDesc d;
+        d.code_off256 = (uint32_t)(unit_off_bytes(p.code_unit) / 256);
+        d.meta_off256 = p.bits < 16 ? (uint32_t)(unit_off_bytes(p.meta_unit) / 256) : 0u;
+        d.bits = (uint32_t)p.bits;
+        d.pad = 0;
+        return d;
+    }
+    KvqPageDesc* table_dev(int layer) const {
+        return reinterpret_cast<KvqPageDesc*>(arena + table_off) + (size_t)layer * max_pages;
+    }
+};
+
+namespace {
+
+struct Regions {
+    uint64_t table_off, jobs_off, part_o_off, part_ml_off, counters_off, pages_off;
+};
+uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+bool check_config(const kvq_config_t* c) {
+    if (!c) return false;
+    if (c->n_layers < 1 || c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1) return false;
+    if (c->head_dim != KVQ_D || c->group != KVQ_G) return false;
+    if (c->n_q_heads % c->n_kv_heads != 0 || c->n_q_heads / c->n_kv_heads > KVQ_MAX_GQA) return false;
+    if (c->page_tokens < 32 || c->page_tokens % 32 != 0) return false;
+    if (c->max_tokens < 1) return false;
+    if (c->window < 0 || c->window % c->page_tokens != 0) return false;
+    if (c->n_sink < 0 || c->n_sink % c->page_tokens != 0) return false;
+    if (c->policy != KVQ_POLICY_PAPER && c->policy != KVQ_POLICY_OLDEST_FIRST) return false;
+    if ((int64_t)c->batch * c->n_kv_heads > 65535) return false;
+    return true;
+}
+
+Regions layout_regions(const kvq_config_t* c) {
+    Regions r;
+    uint64_t units = (uint64_t)c->batch * c->n_kv_heads;
+    uint64_t max_pages = ((uint64_t)c->max_tokens + c->page_tokens - 1) / c->page_tokens;
+    uint64_t off = 0;
+    r.table_off = off;     off = align_up(off + (uint64_t)c->n_layers * max_pages * sizeof(KvqPageDesc), 256);
+    r.jobs_off = off;      off = align_up(off + max_pages * sizeof(KvqRequantJob), 256);
+    r.part_o_off = off;    off = align_up(off + units * KVQ_MAX_SPLITS * 16 * KVQ_D * sizeof(float), 256);
+    r.part_ml_off = off;   off = align_up(off + units * KVQ_MAX_SPLITS * 32 * sizeof(float), 256);
+    r.counters_off = off;  off = align_up(off + units * sizeof(uint32_t), 256);
+    uint64_t unit_bytes = 32ull * c->page_tokens * units;
+    (void)unit_bytes;
+    r.pages_off = align_up(off, 4096);
+    return r;
+}
+
+hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
+
+// Copy `bytes` of host data to device memory in stream order through the pinned staging ring.
+kvq_status_t upload(kvq_cache* c, void* dst_dev, const void* src, uint64_t bytes, hipStream_t s) {
+    if (bytes == 0) return KVQ_OK;
+    if (bytes > kRingBytes) return KVQ_E_INVALID;
+    if (c->ring_pos + bytes > kRingBytes) {
+        // the ring wraps: wait until the copies enqueued from it have been consumed
+        if (hipStreamSynchronize(s) != hipSuccess) return KVQ_E_HIP;
+        c->ring_pos = 0;
+    }
+    std::memcpy(c->ring + c->ring_pos, src, bytes);
+    if (hipMemcpyAsync(dst_dev, c->ring + c->ring_pos, bytes, hipMemcpyHostToDevice, s) != hipSuccess)
+        return KVQ_E_HIP;
+    c->ring_pos = align_up(c->ring_pos + bytes, 64);
+    return KVQ_OK;
+}
+
+kvq_status_t ensure_device(kvq_cache* c, hipStream_t s) {
+    if (c->dry || c->device_ready) return KVQ_OK;
+    if (kvq_launch_fill_u32(reinterpret_cast<uint32_t*>(c->arena + c->counters_off), 0u, (size_t)c->units, s) !=
+        hipSuccess)
+        return KVQ_E_HIP;
+    c->device_ready = true;
+    return KVQ_OK;
+}
+
+kvq_status_t upload_table(kvq_cache* c, int layer, int first, int last, hipStream_t s) {
+    if (c->dry || last <= first) return KVQ_OK;
+    std::vector<KvqPageDesc> d((size_t)(last - first));
+    for (int i = first; i < last; ++i) d[(size_t)(i - first)] = c->desc(c->layers[(size_t)layer].pages[(size_t)i]);
+    return upload(c, c->table_dev(layer) + first, d.data(), d.size() * sizeof(KvqPageDesc), s);
+}
+
+uint64_t bytes_used(const kvq_cache* c, const Layer& L) {
+    uint64_t u = 0;
+    for (const Page& p : L.pages) u += (uint64_t)p.n * c->units * c->bpth(p.bits);
+    return u;
+}
+
+// Width of the block's bulk: smallest width among pages after the sink (16 if there is none).
+int current_bits(const kvq_cache* c, const std::vector<int>& bits) {
+    int first = c->cfg.n_sink / c->cfg.page_tokens, b = 16;
+    for (size_t i = (size_t)first; i < bits.size(); ++i) b = std::min(b, bits[i]);
+    return b;
+}
+int current_bits(const kvq_cache* c, const Layer& L) {
+    std::vector<int> bits(L.pages.size());
+    for (size_t i = 0; i < bits.size(); ++i) bits[i] = L.pages[i].bits;
+    return current_bits(c, bits);
+}
+
+// Sink pages and pages overlapping the most recent `window` tokens are never lowered.
+bool is_protected(const kvq_cache* c, int T, int page) {
+    const int P = c->cfg.page_tokens;
+    if (page < c->cfg.n_sink / P) return true;
+    return c->cfg.window > 0 && (int64_t)(page + 1) * P > (int64_t)T - c->cfg.window;
+}
+
+struct Lowering {  // one page to lower and the blocks allocated for it
+    int page, from, to;
+    uint32_t new_code = 0, new_meta = 0;
+};
+
+// Allocate destination blocks for a set of lowerings; on failure release what was taken.
+bool alloc_lowerings(kvq_cache* c, std::vector<Lowering>& low) {
+    for (size_t i = 0; i < low.size(); ++i) {
+        bool ok = c->buddy.alloc(order_of_bits(low[i].to), &low[i].new_code);
+        bool ok2 = true;
+        if (ok && low[i].from == 16) ok2 = c->buddy.alloc(0, &low[i].new_meta);
+        if (!ok || !ok2) {
+            if (ok) c->buddy.release(low[i].new_code, order_of_bits(low[i].to));
+            for (size_t k = 0; k < i; ++k) {
+                c->buddy.release(low[k].new_code, order_of_bits(low[k].to));
+                if (low[k].from == 16) c->buddy.release(low[k].new_meta, 0);
+            }
+            return false;
+        }
+    }
+    return true;
+}
+
+// Enqueue the kernels for lowerings that all share (from, to), then commit the host tables.
+kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, hipStream_t s) {
+    if (low.empty()) return KVQ_OK;
+    Layer& L = c->layers[(size_t)layer];
+    const int from = low[0].from, to = low[0].to;
+    if (!alloc_lowerings(c, low)) return KVQ_E_OOM;
+    if (!c->dry) {
+        std::vector<KvqRequantJob> jobs(low.size());
+        for (size_t i = 0; i < low.size(); ++i) {
+            const Page& p = L.pages[(size_t)low[i].page];
+            jobs[i].src_code_off256 = (uint32_t)(c->unit_off_bytes(p.code_unit) / 256);
+            jobs[i].dst_code_off256 = (uint32_t)(c->unit_off_bytes(low[i].new_code) / 256);
+            jobs[i].meta_off256 = (uint32_t)(c->unit_off_bytes(from == 16 ? low[i].new_meta : p.meta_unit) / 256);
+            jobs[i].pad = 0;
+        }
+        KvqRequantJob* jd = reinterpret_cast<KvqRequantJob*>(c->arena + c->jobs_off);
+        kvq_status_t st = upload(c, jd, jobs.data(), jobs.size() * sizeof(KvqRequantJob), s);
+        hipError_t e = hipSuccess;
+        if (st == KVQ_OK) {
+            e = (from == 16) ? kvq_launch_quant16(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, s)
+                             : kvq_launch_shrink(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, s);
+        }
+        if (st != KVQ_OK || e != hipSuccess) {
+            for (auto& w : low) {
+                c->buddy.release(w.new_code, order_of_bits(w.to));
+                if (w.from == 16) c->buddy.release(w.new_meta, 0);
+            }
+            return st != KVQ_OK ? st : KVQ_E_HIP;
+        }
+    }
+    int lo = (int)L.pages.size(), hi = 0;
+    for (auto& w : low) {
+        Page& p = L.pages[(size_t)w.page];
+        c->buddy.release(p.code_unit, order_of_bits(p.bits));  // reused only by work enqueued later
+        p.code_unit = w.new_code;
+        if (from == 16) p.meta_unit = w.new_meta;
+        p.bits = to;
+        lo = std::min(lo, w.page);
+        hi = std::max(hi, w.page + 1);
+    }
+    L.version++;
+    return upload_table(c, layer, lo, hi, s);
+}
+
+void build_segments(const kvq_cache* c, const Layer& L, std::vector<kvq_segment_info_t>& out) {
+    const int P = c->cfg.page_tokens;
+    out.clear();
+    for (size_t i = 0; i < L.pages.size(); ++i) {
+        int t0 = (int)i * P, t1 = t0 + L.pages[i].n;
+        if (!out.empty() && out.back().bits == L.pages[i].bits) out.back().token_end = t1;
+        else out.push_back(kvq_segment_info_t{t0, t1, L.pages[i].bits});
+    }
+}
+
+// Byte-balanced split of the tile range: a tile of width b costs b + 1 KiB (16 for raw fp16).
+void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
+    if (L.plan_tiles == n_tiles && L.plan_splits == n_splits && L.plan_version == L.version) return;
+    const int tpp = c->tpp;
+    uint64_t total = 0;
+    for (size_t i = 0; i < L.pages.size(); ++i) {
+        int nt = std::min(tpp, n_tiles - (int)i * tpp);
+        if (nt <= 0) break;
+        int b = L.pages[i].bits;
+        total += (uint64_t)nt * (b == 16 ? 16 : b + 1);
+    }
+    int sp = 1;
+    L.split_begin[0] = 0;
+    uint64_t cum = 0;
+    for (size_t i = 0; i < L.pages.size() && sp < n_splits; ++i) {
+        int nt = std::min(tpp, n_tiles - (int)i * tpp);
+        if (nt <= 0) break;
+        uint64_t cost = L.pages[i].bits == 16 ? 16 : (uint64_t)L.pages[i].bits + 1;
+        uint64_t page_end = cum + cost * nt;
+        while (sp < n_splits) {
+            uint64_t target = (total * sp + n_splits - 1) / n_splits;
+            if (target > page_end) break;
+            uint64_t k = target <= cum ? 0 : (target - cum + cost - 1) / cost;
+            L.split_begin[sp++] = (int)i * tpp + (int)k;
+        }
+        cum = page_end;
+    }
+    while (sp <= n_splits) L.split_begin[sp++] = n_tiles;
+    L.plan_tiles = n_tiles;
+    L.plan_splits = n_splits;
+    L.plan_version = L.version;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t kvq_bytes_per_token_head(int32_t bits, int32_t head_dim, int32_t group, int32_t count_metadata) {
+    if (!valid_bits(bits) || head_dim <= 0 || group <= 0) return 0;
+    uint64_t n = 2ull * head_dim * bits / 8;
+    if (count_metadata && bits < 16) n += 2ull * (head_dim / group) * 4;
+    return n;
+}
+
+uint64_t kvq_arena_bytes(const kvq_config_t* cfg, uint64_t payload_bytes) {
+    if (!check_config(cfg)) return 0;
+    Regions r = layout_regions(cfg);
+    uint64_t super = (32ull * cfg->page_tokens * cfg->batch * cfg->n_kv_heads) << kMaxOrder;
+    return r.pages_off + align_up(payload_bytes, super);
+}
+
+kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_budget_bytes_host,
+                              const uint8_t* block_fbit_host, void* arena_dev, uint64_t arena_bytes,
+                              kvq_cache_t** out) {
+    if (!out) return KVQ_E_INVALID;
+    *out = nullptr;
+    if (!check_config(cfg) || !block_budget_bytes_host || !block_fbit_host) return KVQ_E_INVALID;
+    for (int i = 0; i < cfg->n_layers; ++i)
+        if (!valid_bits(block_fbit_host[i])) return KVQ_E_INVALID;
+    if (arena_dev && (reinterpret_cast<uintptr_t>(arena_dev) & 255u)) return KVQ_E_INVALID;
+    kvq_cache* c = new (std::nothrow) kvq_cache();
+    if (!c) return KVQ_E_OOM;
+    c->cfg = *cfg;
+    c->units = cfg->batch * cfg->n_kv_heads;
+    c->tpp = cfg->page_tokens / KVQ_TILE_TOKENS;
+    c->gqa = cfg->n_q_heads / cfg->n_kv_heads;
+    c->max_pages = (cfg->max_tokens + cfg->page_tokens - 1) / cfg->page_tokens;
+    c->dry = (arena_dev == nullptr);
+    c->arena = static_cast<uint8_t*>(arena_dev);
+    c->arena_bytes = arena_bytes;
+    c->unit_bytes = 32ull * cfg->page_tokens * c->units;
+    Regions r = layout_regions(cfg);
+    c->table_off = r.table_off; c->jobs_off = r.jobs_off; c->part_o_off = r.part_o_off;
+    c->part_ml_off = r.part_ml_off; c->counters_off = r.counters_off; c->pages_off = r.pages_off;
+    uint64_t super = c->unit_bytes << kMaxOrder;
+    if (arena_bytes < c->pages_off + super) { delete c; return KVQ_E_OOM; }
+    uint64_t n_super = (arena_bytes - c->pages_off) / super;
+    if ((c->pages_off + n_super * super) / 256 > 0xffffffffull) { delete c; return KVQ_E_INVALID; }
+    c->buddy.init((uint32_t)n_super);
+    c->layers.resize((size_t)cfg->n_layers);
+    for (int i = 0; i < cfg->n_layers; ++i) {
+        c->layers[(size_t)i].budget = block_budget_bytes_host[i];
+        c->layers[(size_t)i].fbit = block_fbit_host[i];
+    }
+    if (!c->dry) {
+        if (hipHostMalloc(reinterpret_cast<void**>(&c->ring), kRingBytes, hipHostMallocDefault) != hipSuccess) {
+            delete c;
+            return KVQ_E_HIP;
+        }
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            prop.multiProcessorCount > 0)
+            c->target_workgroups = 2 * prop.multiProcessorCount;
+    }
+    *out = c;
+    return KVQ_OK;
+}
+
+void kvq_cache_destroy(kvq_cache_t* c) {
+    if (!c) return;
+    if (c->ring) (void)hipHostFree(c->ring);
+    delete c;
+}
+
+kvq_status_t kvq_quantize_append(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev,
+                                 int32_t n_new, int32_t entry_bits, void* hip_stream) {
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || n_new < 0) return KVQ_E_INVALID;
+    if (entry_bits != 0 && !valid_bits(entry_bits)) return KVQ_E_INVALID;
+    if (n_new == 0) return KVQ_OK;
+    if (!c->dry && (!k_dev || !v_dev)) return KVQ_E_INVALID;
+    Layer& L = c->layers[(size_t)layer];
+    const kvq_config_t& cfg = c->cfg;
+    const int P = cfg.page_tokens;
+    hipStream_t s = as_stream(hip_stream);
+    if ((int64_t)L.T + n_new > cfg.max_tokens) return KVQ_E_STATE;
+
+    // entry width
+    int e = entry_bits;
+    if (e == 0) e = (cfg.policy == KVQ_POLICY_OLDEST_FIRST || cfg.window > 0) ? 16 : current_bits(c, L);
+    if (L.T % P != 0 && L.pages.back().bits != e) return KVQ_E_STATE;
+    const bool evict = entry_bits == 0 && cfg.policy == KVQ_POLICY_PAPER && cfg.window > 0;
+
+    // simulate the bookkeeping: page widths and fill counts after the append and the evictions it causes
+    std::vector<int> bits(L.pages.size()), cnt(L.pages.size());
+    for (size_t i = 0; i < L.pages.size(); ++i) { bits[i] = L.pages[i].bits; cnt[i] = L.pages[i].n; }
+    int T = L.T, left = n_new;
+    while (left) {
+        if (T % P == 0) { bits.push_back(e); cnt.push_back(0); }
+        int take = std::min(left, P - cnt.back());
+        cnt.back() += take; T += take; left -= take;
+    }
+    std::vector<int> evicted;
+    int bcur = 16;
+    if (evict) {
+        bcur = current_bits(c, bits);
+        if (bcur < 16) {
+            for (;;) {
+                int i = (int)bits.size(), first = cfg.n_sink / P;
+                while (i > first && bits[(size_t)i - 1] == 16) --i;  // start of the trailing 16-bit run
+                if (i < (int)bits.size() && T - i * P >= cfg.window + P) { bits[(size_t)i] = bcur; evicted.push_back(i); }
+                else break;
+            }
+        }
+    }
+    uint64_t used = 0;
+    for (size_t i = 0; i < bits.size(); ++i) used += (uint64_t)cnt[i] * c->units * c->bpth(bits[i]);
+    if (used > L.budget) return KVQ_E_BUDGET;
+
+    // allocate the new pages
+    const size_t old_pages = L.pages.size();
+    std::vector<Page> fresh;
+    for (size_t i = old_pages; i < bits.size(); ++i) {
+        Page p;
+        p.bits = e;
+        bool ok = c->buddy.alloc(order_of_bits(e), &p.code_unit);
+        bool ok2 = true;
+        if (ok && e < 16) ok2 = c->buddy.alloc(0, &p.meta_unit);
+        if (!ok || !ok2) {
+            if (ok) c->buddy.release(p.code_unit, order_of_bits(e));
+            for (Page& q : fresh) {
+                c->buddy.release(q.code_unit, order_of_bits(e));
+                if (e < 16) c->buddy.release(q.meta_unit, 0);
+            }
+            return KVQ_E_OOM;
+        }
+        fresh.push_back(p);
+    }
+    kvq_status_t st = ensure_device(c, s);
+    if (st != KVQ_OK) return st;
+    const int t_old = L.T;
+    for (Page& p : fresh) L.pages.push_back(p);
+    for (size_t i = 0; i < L.pages.size(); ++i) L.pages[i].n = cnt[i];
+    L.T = T;
+    L.version++;
+    st = upload_table(c, layer, (int)old_pages, (int)L.pages.size(), s);
+    if (st != KVQ_OK) return st;
+    if (!c->dry) {
+        if (kvq_launch_append(e, c->arena, c->table_dev(layer), k_dev, v_dev, t_old, n_new, c->tpp, c->units, s) !=
+            hipSuccess)
+            return KVQ_E_HIP;
+    }
+    if (!evicted.empty()) {
+        std::vector<Lowering> low;
+        for (int i : evicted) low.push_back(Lowering{i, 16, bcur});
+        st = run_lowerings(c, layer, low, s);
+        if (st != KVQ_OK) return st;
+    }
+    return KVQ_OK;
+}
+
+kvq_status_t kvq_progressive_requant(kvq_cache_t* c, int32_t layer, int32_t segment, int32_t reserve_tokens,
+                                     void* hip_stream, int32_t* n_pages_done) {
+    if (n_pages_done) *n_pages_done = 0;
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || segment < -1 || reserve_tokens < 0) return KVQ_E_INVALID;
+    Layer& L = c->layers[(size_t)layer];
+    const kvq_config_t& cfg = c->cfg;
+    const int P = cfg.page_tokens;
+    hipStream_t s = as_stream(hip_stream);
+    kvq_status_t st = ensure_device(c, s);
+    if (st != KVQ_OK) return st;
+
+    if (segment >= 0) {
+        std::vector<kvq_segment_info_t> segs;
+        build_segments(c, L, segs);
+        if (segment >= (int)segs.size()) return KVQ_E_STATE;
+        const kvq_segment_info_t sg = segs[(size_t)segment];
+        if (sg.bits == 2) return KVQ_E_STATE;
+        std::vector<Lowering> low;
+        for (int i = sg.token_begin / P; i < (sg.token_end + P - 1) / P; ++i) low.push_back(Lowering{i, sg.bits, sg.bits / 2});
+        st = run_lowerings(c, layer, low, s);
+        if (st == KVQ_OK && n_pages_done) *n_pages_done = (int32_t)low.size();
+        return st;
+    }
+    if (cfg.policy == KVQ_POLICY_PAPER) {
+        const int bcur = current_bits(c, L);
+        if (bcur <= L.fbit) return KVQ_E_BUDGET;
+        std::vector<Lowering> low;
+        for (int i = 0; i < (int)L.pages.size(); ++i)
+            if (L.pages[(size_t)i].bits == bcur && !is_protected(c, L.T, i)) low.push_back(Lowering{i, bcur, bcur / 2});
+        if (low.empty()) return KVQ_E_BUDGET;
+        st = run_lowerings(c, layer, low, s);
+        if (st == KVQ_OK && n_pages_done) *n_pages_done = (int32_t)low.size();
+        return st;
+    }
+    // OLDEST_FIRST
+    const uint64_t need = (uint64_t)reserve_tokens * c->units * c->bpth(16);
+    int done = 0;
+    while (bytes_used(c, L) + need > L.budget) {
+        int pick = -1;
+        for (int i = cfg.n_sink / P; i < (int)L.pages.size(); ++i) {
+            const Page& p = L.pages[(size_t)i];
+            if (p.bits > L.fbit && p.n == P && (int64_t)(i + 1) * P <= (int64_t)L.T - cfg.window) { pick = i; break; }
+        }
+        if (pick < 0) { if (n_pages_done) *n_pages_done = done; return KVQ_E_BUDGET; }
+        std::vector<Lowering> low{Lowering{pick, L.pages[(size_t)pick].bits, L.pages[(size_t)pick].bits / 2}};
+        st = run_lowerings(c, layer, low, s);
+        if (st != KVQ_OK) { if (n_pages_done) *n_pages_done = done; return st; }
+        ++done;
+    }
+    if (n_pages_done) *n_pages_done = done;
+    return KVQ_OK;
+}
+
+kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_dev, void* out_dev,
+                                  int32_t out_is_fp32, float softmax_scale, void* hip_stream) {
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_dev || !out_dev) return KVQ_E_INVALID;
+    if (c->dry) return KVQ_E_STATE;
+    Layer& L = c->layers[(size_t)layer];
+    if (L.T == 0) return KVQ_E_STATE;
+    hipStream_t s = as_stream(hip_stream);
+    const int n_tiles = (L.T + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
+    int n_splits = c->splits_override;
+    if (n_splits <= 0) n_splits = std::min(c->target_workgroups / std::max(1, c->units), (n_tiles + 3) / 4);
+    n_splits = std::max(1, std::min(n_splits, std::min(KVQ_MAX_SPLITS, n_tiles)));
+    plan_splits(c, L, n_tiles, n_splits);
+
+    KvqAttnParams p;
+    p.arena = c->arena;
+    p.table = c->table_dev(layer);
+    p.q = q_dev;
+    p.out = out_dev;
+    p.part_o = reinterpret_cast<float*>(c->arena + c->part_o_off);
+    p.part_ml = reinterpret_cast<float*>(c->arena + c->part_ml_off);
+    p.counters = reinterpret_cast<uint32_t*>(c->arena + c->counters_off);
+    p.n_tokens = L.T;
+    p.tiles_per_page = c->tpp;
+    p.gqa = c->gqa;
+    p.n_q_heads = c->cfg.n_q_heads;
+    p.n_kv_heads = c->cfg.n_kv_heads;
+    p.n_splits = n_splits;
+    p.out_fp32 = out_is_fp32 ? 1 : 0;
+    p.fused_merge = c->fused_merge;
+    const float scale = softmax_scale != 0.f ? softmax_scale : 1.0f / std::sqrt((float)c->cfg.head_dim);
+    p.scale_log2 = scale * 1.44269504088896340736f;
+    std::memcpy(p.split_begin, L.split_begin, sizeof(int32_t) * (size_t)(n_splits + 1));
+    for (int i = n_splits + 1; i <= KVQ_MAX_SPLITS; ++i) p.split_begin[i] = n_tiles;
+    return kvq_launch_attention(p, c->units, s) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
+}
+
+kvq_status_t kvq_cache_describe(const kvq_cache_t* c, int32_t layer, kvq_segment_info_t* segs_host, int32_t cap,
+                                int32_t* n, uint64_t* bytes_used_out, int32_t* n_tokens, int32_t* current_bits_out) {
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || cap < 0 || (cap > 0 && !segs_host)) return KVQ_E_INVALID;
+    const Layer& L = c->layers[(size_t)layer];
+    std::vector<kvq_segment_info_t> segs;
+    build_segments(c, L, segs);
+    for (int i = 0; i < std::min<int>(cap, (int)segs.size()); ++i) segs_host[i] = segs[(size_t)i];
+    if (n) *n = (int32_t)segs.size();
+    if (bytes_used_out) *bytes_used_out = bytes_used(c, L);
+    if (n_tokens) *n_tokens = L.T;
+    if (current_bits_out) *current_bits_out = current_bits(c, L);
+    return KVQ_OK;
+}
+
+kvq_status_t kvq_cache_export_segment(kvq_cache_t* c, int32_t layer, int32_t segment, int32_t which,
+                                      void* codes_host, void* scales_host, void* zeros_host, void* hip_stream) {
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || segment < 0 || !codes_host) return KVQ_E_INVALID;
+    if (which != KVQ_WHICH_K && which != KVQ_WHICH_V) return KVQ_E_INVALID;
+    if (c->dry) return KVQ_E_STATE;
+    const Layer& L = c->layers[(size_t)layer];
+    std::vector<kvq_segment_info_t> segs;
+    build_segments(c, L, segs);
+    if (segment >= (int)segs.size()) return KVQ_E_STATE;
+    const kvq_segment_info_t sg = segs[(size_t)segment];
+    const int b = sg.bits, P = c->cfg.page_tokens, tpp = c->tpp;
+    if (b < 16 && (!scales_host || !zeros_host)) return KVQ_E_INVALID;
+    hipStream_t s = as_stream(hip_stream);
+    const int n_seg = sg.token_end - sg.token_begin;
+    const size_t row_bytes = (size_t)KVQ_D * b / 8;
+    const size_t code_block = (size_t)c->unit_bytes * b;
+    std::vector<uint8_t> code(code_block), meta(b < 16 ? (size_t)c->unit_bytes : 0);
+    uint8_t* oc = static_cast<uint8_t*>(codes_host);
+    uint16_t* os = static_cast<uint16_t*>(scales_host);
+    uint16_t* oz = static_cast<uint16_t*>(zeros_host);
+    for (int pg = sg.token_begin / P; pg < (sg.token_end + P - 1) / P; ++pg) {
+        const Page& p = L.pages[(size_t)pg];
+        if (hipMemcpyAsync(code.data(), c->arena + c->unit_off_bytes(p.code_unit), code_block, hipMemcpyDeviceToHost, s) != hipSuccess)
+            return KVQ_E_HIP;
+        if (b < 16 && hipMemcpyAsync(meta.data(), c->arena + c->unit_off_bytes(p.meta_unit), meta.size(), hipMemcpyDeviceToHost, s) != hipSuccess)
+            return KVQ_E_HIP;
+        if (hipStreamSynchronize(s) != hipSuccess) return KVQ_E_HIP;
+        for (int u = 0; u < c->units; ++u) {
+            for (int tl = 0; tl < p.n; ++tl) {
+                const int tip = tl / KVQ_TILE_TOKENS, t = tl % KVQ_TILE_TOKENS;
+                const size_t tslot = (size_t)u * tpp + tip;
+                const uint8_t* tile = code.data() + (tslot * 2 + (size_t)which) * kvq_tile_code_bytes(b);
+                const size_t tok_seg = (size_t)pg * P + tl - sg.token_begin;
+                uint8_t* row = oc + ((size_t)u * n_seg + tok_seg) * row_bytes;
+                std::memset(row, 0, row_bytes);
+                for (int d = 0; d < KVQ_D; ++d) {
+                    int lane, slot;
+                    if (which == KVQ_WHICH_K) kvq_k_slot(t, d, &lane, &slot);
+                    else kvq_v_slot(t, d, &lane, &slot);
+                    const uint32_t bit = (uint32_t)slot * b;
+                    if (b == 16) {
+                        const uint8_t* src = tile + kvq_tile_byte(lane, bit / 8);
+                        row[2 * d] = src[0];
+                        row[2 * d + 1] = src[1];
+                    } else {
+                        uint32_t v = (tile[kvq_tile_byte(lane, bit / 8)] >> (bit % 8)) & ((1u << b) - 1u);
+                        row[(size_t)d * b / 8] |= (uint8_t)(v << ((d * b) % 8));
+                    }
+                }
+                if (b < 16) {
+                    const uint16_t* m = reinterpret_cast<const uint16_t*>(meta.data() + tslot * KVQ_META_TILE_BYTES);
+                    for (int g = 0; g < KVQ_NGRP; ++g) {
+                        size_t oi = ((size_t)u * n_seg + tok_seg) * KVQ_NGRP + g;
+                        if (which == KVQ_WHICH_K) { os[oi] = m[t * 4 + g]; oz[oi] = m[128 + t * 4 + g]; }
+                        else { os[oi] = m[256 + kvq_vmeta_index(t, g)]; oz[oi] = m[384 + kvq_vmeta_index(t, g)]; }
+                    }
+                }
+            }
+        }
+    }
+    return KVQ_OK;
+}
+
+kvq_status_t kvq_cache_set_option(kvq_cache_t* c, int32_t option, int32_t value) {
+    if (!c) return KVQ_E_INVALID;
+    switch (option) {
+        case KVQ_OPT_SPLITS:
+            if (value < 0 || value > KVQ_MAX_SPLITS) return KVQ_E_INVALID;
+            c->splits_override = value;
+            return KVQ_OK;
+        case KVQ_OPT_FUSED_MERGE:
+            c->fused_merge = value ? 1 : 0;
+            return KVQ_OK;
+        default: return KVQ_E_INVALID;
+    }
+}
+
+uint64_t kvq_cache_arena_free_bytes(const kvq_cache_t* c) { return c ? c->buddy.free_units() * c->unit_bytes : 0; }
+
+const char* kvq_status_string(kvq_status_t s) {
+    switch (s) {
+        case KVQ_OK: return "ok";
+        case KVQ_E_INVALID: return "invalid argument or unsupported configuration";
+        case KVQ_E_BUDGET: return "block byte budget exceeded or nothing left to shrink";
+        case KVQ_E_OOM: return "arena out of memory";
+        case KVQ_E_STATE: return "call does not fit the cache state";
+        case KVQ_E_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

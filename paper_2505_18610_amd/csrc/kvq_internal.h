@@ -1,0 +1,49 @@
+// Internal interface between the host bookkeeping (kvq_host.cpp) and the kernel translation units.
+#ifndef KVQ_INTERNAL_H
+#define KVQ_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "kvq_layout.h"
+
+struct KvqRequantJob {        // one page to re-quantize
+    uint32_t src_code_off256; // source code block
+    uint32_t dst_code_off256; // destination code block
+    uint32_t meta_off256;     // metadata block (updated in place for 2b -> b, written for 16 -> b)
+    uint32_t pad;
+};
+
+struct KvqAttnParams {
+    const uint8_t* arena;
+    const KvqPageDesc* table;  // this block's page table
+    const void* q;             // fp16 [batch, n_q_heads, 128]
+    void* out;                 // [batch, n_q_heads, 128] fp16 or fp32
+    float* part_o;             // [unit][split][16][128] un-normalised partial outputs
+    float* part_ml;            // [unit][split][2][16] running max (log2 units) and sum
+    uint32_t* counters;        // [unit] arrival counters of the fused merge (kept at zero between launches)
+    int32_t n_tokens;
+    int32_t tiles_per_page;
+    int32_t gqa;               // query heads per KV head
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t n_splits;
+    int32_t out_fp32;
+    int32_t fused_merge;
+    float scale_log2;          // softmax scale * log2(e)
+    int32_t split_begin[KVQ_MAX_SPLITS + 1];  // tile index where each split starts
+};
+
+// kvq_quant.hip
+hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
+                             const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
+                             hipStream_t s);
+hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
+                             int tiles_per_page, int units, hipStream_t s);
+hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
+                              int tiles_per_page, int units, hipStream_t s);
+hipError_t kvq_launch_fill_u32(uint32_t* dst, uint32_t value, size_t n, hipStream_t s);
+
+// kvq_attention.hip
+hipError_t kvq_launch_attention(const KvqAttnParams& p, int units, hipStream_t s);
+
+#endif

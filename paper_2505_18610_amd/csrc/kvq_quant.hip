@@ -1,0 +1,391 @@
+// Quantize-on-append, fp16 -> b-bit page quantization and the Equivalent Right Shift kernels (gfx950).
+//
+// Quantizer: Sec. 2.2 Eq. 1-2 (asymmetric min-max per group of 32 channels of one token of one KV head).
+// Shrinking: Sec. 3.1 Eq. 3 with S_b = (2^b + 1) S_2b and Z kept.
+// All kernels work directly in the tile layout described in kvq_layout.h: one wavefront owns one tile and
+// every lane quantizes the 64 slots it will later feed to the matrix cores.
+#include "kvq_internal.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+__device__ inline uint16_t f2h_rn(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }  // RNE
+
+// (S, Z) of one group from its min and max (both exact fp16 values held as float), Eq. 2.
+__device__ inline void group_params(float mn, float mx, int levels, uint16_t* S, uint16_t* Z, float* Sf) {
+    float s32 = (mx - mn) / (float)levels;  // one fp32 subtract, one correctly rounded fp32 divide
+    *S = f2h_rn(s32);
+    *Z = f2h_rn(mn);
+    *Sf = h2f(*S);
+}
+// Eq. 1 with the stored scale; a zero scale maps the whole group to code 0.
+__device__ inline uint32_t code_of(float x, float mn, float Sf, int levels) {
+    if (Sf == 0.0f) return 0u;
+    float r = rintf((x - mn) / Sf);
+    r = fminf(fmaxf(r, 0.0f), (float)levels);
+    return (uint32_t)r;
+}
+
+// K tile: slot s = p*8 + i with p = sub*4 + grp; a group = the 8 slots of p in the 4 lanes that differ in j.
+template <int B>
+__device__ inline void quantize_k(const float (&x)[64], uint32_t (&str)[2 * B], uint16_t (&S)[8],
+                                  uint16_t (&Z)[8]) {
+    constexpr int levels = (1 << B) - 1;
+#pragma unroll
+    for (int d = 0; d < 2 * B; ++d) str[d] = 0u;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        float mn = x[p * 8], mx = x[p * 8];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) {
+            mn = fminf(mn, x[p * 8 + i]);
+            mx = fmaxf(mx, x[p * 8 + i]);
+        }
+        mn = fminf(mn, __shfl_xor(mn, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mn = fminf(mn, __shfl_xor(mn, 32));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float Sf;
+        group_params(mn, mx, levels, &S[p], &Z[p], &Sf);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint32_t c = code_of(x[p * 8 + i], mn, Sf, levels);
+            int bit = (p * 8 + i) * B;
+            str[bit >> 5] |= c << (bit & 31);
+        }
+    }
+}
+
+// V tile: slot s = nt*8 + i (token 8j+i, channel 16nt+n); group (i, g) = slots (2g, i), (2g+1, i) in the 16
+// lanes of one quarter.  S/Z index = i*4 + g.
+template <int B>
+__device__ inline void quantize_v(const float (&x)[64], uint32_t (&str)[2 * B], uint16_t (&S)[32],
+                                  uint16_t (&Z)[32]) {
+    constexpr int levels = (1 << B) - 1;
+#pragma unroll
+    for (int d = 0; d < 2 * B; ++d) str[d] = 0u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float a = x[(2 * g) * 8 + i], b = x[(2 * g + 1) * 8 + i];
+            float mn = fminf(a, b), mx = fmaxf(a, b);
+#pragma unroll
+            for (int m = 1; m < 16; m <<= 1) {
+                mn = fminf(mn, __shfl_xor(mn, m));
+                mx = fmaxf(mx, __shfl_xor(mx, m));
+            }
+            float Sf;
+            group_params(mn, mx, levels, &S[i * 4 + g], &Z[i * 4 + g], &Sf);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                int nt = 2 * g + h;
+                uint32_t c = code_of(h ? b : a, mn, Sf, levels);
+                int bit = (nt * 8 + i) * B;
+                str[bit >> 5] |= c << (bit & 31);
+            }
+        }
+    }
+}
+
+// Mask of the bits of string dword `dw` of a V lane that belong to tokens flagged in kb (bit i = token 8j+i).
+template <int B>
+__device__ inline uint32_t v_token_mask(uint32_t kb, int dw) {
+    constexpr int per = 32 / B;  // slots per dword
+    constexpr uint32_t field = (B == 32) ? 0xffffffffu : ((1u << B) - 1u);
+    uint32_t m = 0;
+#pragma unroll
+    for (int e = 0; e < per; ++e) {
+        int slot = dw * per + e;
+        int tok = slot & 7;
+        if ((kb >> tok) & 1u) m |= field << (e * B);
+    }
+    return m;
+}
+
+template <int B>
+__device__ inline void store_chunks(uint8_t* tile, int lane, const uint32_t (&str)[2 * B]) {
+#pragma unroll
+    for (int c = 0; c < B / 2; ++c) {
+        u32x4 v = {str[4 * c], str[4 * c + 1], str[4 * c + 2], str[4 * c + 3]};
+        *reinterpret_cast<u32x4*>(tile + (c * 64 + lane) * 16) = v;
+    }
+}
+template <int B>
+__device__ inline void load_chunks(const uint8_t* tile, int lane, uint32_t (&str)[2 * B]) {
+#pragma unroll
+    for (int c = 0; c < B / 2; ++c) {
+        u32x4 v = *reinterpret_cast<const u32x4*>(tile + (c * 64 + lane) * 16);
+        str[4 * c] = v.x; str[4 * c + 1] = v.y; str[4 * c + 2] = v.z; str[4 * c + 3] = v.w;
+    }
+}
+
+// keep_k: bit sub set = the token of sub-tile `sub` of this lane must keep its stored value
+__device__ inline void store_meta_k(uint8_t* meta, int lane, const uint16_t (&S)[8], const uint16_t (&Z)[8],
+                                    uint32_t keep_k) {
+    int j = lane >> 4, n = lane & 15;
+    uint16_t* ms = reinterpret_cast<uint16_t*>(meta);
+    uint16_t* mz = reinterpret_cast<uint16_t*>(meta + 256);
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+        if ((keep_k >> sub) & 1u) continue;
+        int t = 8 * (n >> 2) + 4 * sub + (n & 3);
+        uint16_t s = 0, z = 0;
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp)
+            if (grp == j) { s = S[sub * 4 + grp]; z = Z[sub * 4 + grp]; }
+        ms[t * 4 + j] = s;
+        mz[t * 4 + j] = z;
+    }
+}
+// keep_v: bit i set = token 8j+i keeps its stored value
+__device__ inline void store_meta_v(uint8_t* meta, int lane, const uint16_t (&S)[32], const uint16_t (&Z)[32],
+                                    uint32_t keep_v) {
+    int j = lane >> 4, n = lane & 15;
+    uint16_t* ms = reinterpret_cast<uint16_t*>(meta + 512);
+    uint16_t* mz = reinterpret_cast<uint16_t*>(meta + 768);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (n != i || ((keep_v >> i) & 1u)) continue;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            int idx = kvq_vmeta_index(8 * j + i, g);
+            ms[idx] = S[i * 4 + g];
+            mz[idx] = Z[i * 4 + g];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ append
+// grid.x = 2 * (tiles touched) (even: K tile, odd: V tile), grid.y = (sequence, KV head) unit, 64 threads.
+// Writes every slot of every touched tile: stored tokens keep their bits, new tokens are quantized (or
+// copied for B = 16), slots past the new end are zeroed so that partially filled tiles stay well defined.
+template <int B>
+__global__ __launch_bounds__(64) void kvq_append_kernel(uint8_t* __restrict__ arena,
+                                                        const KvqPageDesc* __restrict__ table,
+                                                        const uint16_t* __restrict__ k_in,
+                                                        const uint16_t* __restrict__ v_in, int t_old,
+                                                        int n_new, int tpp, int tile0) {
+    const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
+    const int which = blockIdx.x & 1;
+    const int tile = tile0 + (blockIdx.x >> 1);
+    const int unit = blockIdx.y;
+    const int page = tile / tpp, tip = tile - page * tpp;
+    const KvqPageDesc pd = table[page];
+    const uint64_t tslot = (uint64_t)unit * tpp + tip;
+    uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * B);
+    uint8_t* meta = arena + (uint64_t)pd.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
+    const int t_new = t_old + n_new, tok0 = tile * KVQ_TILE_TOKENS;
+    const uint16_t* in = (which ? v_in : k_in) + (uint64_t)unit * n_new * KVQ_D;
+    const bool has_old = tok0 < t_old;
+
+    uint16_t raw[64];
+    uint32_t keep = 0;  // K: per sub; V: per token of the quarter
+    if (!which) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            int tok = tok0 + 8 * (n >> 2) + 4 * sub + (n & 3);
+            bool isnew = tok >= t_old && tok < t_new;
+            if (tok < t_old) keep |= 1u << sub;
+#pragma unroll
+            for (int grp = 0; grp < 4; ++grp) {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (isnew)
+                    v = *reinterpret_cast<const u32x4*>(in + (uint64_t)(tok - t_old) * KVQ_D + 32 * grp + 8 * j);
+                int s0 = (sub * 4 + grp) * 8;
+                raw[s0 + 0] = v.x & 0xffff; raw[s0 + 1] = v.x >> 16;
+                raw[s0 + 2] = v.y & 0xffff; raw[s0 + 3] = v.y >> 16;
+                raw[s0 + 4] = v.z & 0xffff; raw[s0 + 5] = v.z >> 16;
+                raw[s0 + 6] = v.w & 0xffff; raw[s0 + 7] = v.w >> 16;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int tok = tok0 + 8 * j + i;
+            bool isnew = tok >= t_old && tok < t_new;
+            if (tok < t_old) keep |= 1u << i;
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt)
+                raw[nt * 8 + i] = isnew ? in[(uint64_t)(tok - t_old) * KVQ_D + 16 * nt + n] : (uint16_t)0;
+        }
+    }
+
+    uint32_t str[2 * B];
+    if constexpr (B == 16) {
+#pragma unroll
+        for (int d = 0; d < 32; ++d) str[d] = (uint32_t)raw[2 * d] | ((uint32_t)raw[2 * d + 1] << 16);
+    } else {
+        float x[64];
+#pragma unroll
+        for (int s = 0; s < 64; ++s) x[s] = h2f(raw[s]);
+        if (!which) {
+            uint16_t S[8], Z[8];
+            quantize_k<B>(x, str, S, Z);
+            store_meta_k(meta, lane, S, Z, keep);
+        } else {
+            uint16_t S[32], Z[32];
+            quantize_v<B>(x, str, S, Z);
+            store_meta_v(meta, lane, S, Z, keep);
+        }
+    }
+    if (has_old && keep) {
+        uint32_t old[2 * B];
+        load_chunks<B>(code, lane, old);
+#pragma unroll
+        for (int d = 0; d < 2 * B; ++d) {
+            uint32_t m = which ? v_token_mask<B>(keep, d) : (((keep >> (d / B)) & 1u) ? 0xffffffffu : 0u);
+            str[d] = (old[d] & m) | (str[d] & ~m);
+        }
+    }
+    store_chunks<B>(code, lane, str);
+}
+
+// ------------------------------------------------------------------------------------- fp16 page -> b bits
+// grid.x = 2 * n_jobs * tiles_per_page, grid.y = unit, 64 threads.  Direct quantization (Eq. 1-2) of a page
+// that still holds raw fp16 values.
+template <int B>
+__global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ arena,
+                                                         const KvqRequantJob* __restrict__ jobs, int tpp) {
+    const int lane = threadIdx.x;
+    const int which = blockIdx.x & 1;
+    const int idx = blockIdx.x >> 1;
+    const int job = idx / tpp, tip = idx - job * tpp;
+    const int unit = blockIdx.y;
+    const KvqRequantJob jb = jobs[job];
+    const uint64_t tslot = (uint64_t)unit * tpp + tip;
+    const uint8_t* src = arena + (uint64_t)jb.src_code_off256 * 256u + (tslot * 2 + which) * (512u * 16);
+    uint8_t* dst = arena + (uint64_t)jb.dst_code_off256 * 256u + (tslot * 2 + which) * (512u * B);
+    uint8_t* meta = arena + (uint64_t)jb.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
+    uint32_t in[32];
+    load_chunks<16>(src, lane, in);
+    float x[64];
+#pragma unroll
+    for (int d = 0; d < 32; ++d) {
+        x[2 * d] = h2f((uint16_t)(in[d] & 0xffff));
+        x[2 * d + 1] = h2f((uint16_t)(in[d] >> 16));
+    }
+    uint32_t str[2 * B];
+    if (!which) {
+        uint16_t S[8], Z[8];
+        quantize_k<B>(x, str, S, Z);
+        store_meta_k(meta, lane, S, Z, 0u);
+    } else {
+        uint16_t S[32], Z[32];
+        quantize_v<B>(x, str, S, Z);
+        store_meta_v(meta, lane, S, Z, 0u);
+    }
+    store_chunks<B>(dst, lane, str);
+}
+
+// ------------------------------------------------------------------------------- Equivalent Right Shift
+// Eq. 3 on packed codes, slot order preserved, several codes per 32-bit multiply (no carry can cross a field:
+// 13*(15+2) < 2^8 and 241*(255+8) < 2^16).
+__device__ inline uint32_t shrink_4_to_2(uint32_t w) {  // 8 nibbles -> 8 two-bit codes (16 bits)
+    uint32_t e = w & 0x0f0f0f0fu, o = (w >> 4) & 0x0f0f0f0fu;
+    e = (((e + 0x02020202u) * 13u) >> 6) & 0x03030303u;
+    o = (((o + 0x02020202u) * 13u) >> 6) & 0x03030303u;
+    uint32_t c = e | (o << 2);
+    c = (c | (c >> 4)) & 0x00ff00ffu;
+    return (c | (c >> 8)) & 0xffffu;
+}
+__device__ inline uint32_t shrink_8_to_4(uint32_t w) {  // 4 bytes -> 4 nibbles (16 bits)
+    uint32_t e = w & 0x00ff00ffu, o = (w >> 8) & 0x00ff00ffu;
+    e = (((e + 0x00080008u) * 241u) >> 12) & 0x000f000fu;
+    o = (((o + 0x00080008u) * 241u) >> 12) & 0x000f000fu;
+    uint32_t c = e | (o << 4);
+    return (c | (c >> 8)) & 0xffffu;
+}
+
+// grid.x = n_jobs * tiles_per_page, grid.y = unit, 64 threads; one wavefront shrinks the K and the V tile of
+// one (page, unit, tile) from 2B to B bits and multiplies its 256 scales by 2^B + 1 in place.
+template <int B>
+__global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ arena,
+                                                        const KvqRequantJob* __restrict__ jobs, int tpp) {
+    const int lane = threadIdx.x;
+    const int job = blockIdx.x / tpp, tip = blockIdx.x - job * tpp;
+    const int unit = blockIdx.y;
+    const KvqRequantJob jb = jobs[job];
+    const uint64_t tslot = (uint64_t)unit * tpp + tip;
+    const uint8_t* src = arena + (uint64_t)jb.src_code_off256 * 256u + tslot * 2 * (512u * 2 * B);
+    uint8_t* dst = arena + (uint64_t)jb.dst_code_off256 * 256u + tslot * 2 * (512u * B);
+    uint8_t* meta = arena + (uint64_t)jb.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
+    // scales: K block at +0 and V block at +512, 64 dwords each, one dword (two fp16) per lane
+    uint32_t sk = reinterpret_cast<const uint32_t*>(meta)[lane];
+    uint32_t sv = reinterpret_cast<const uint32_t*>(meta + 512)[lane];
+#pragma unroll
+    for (int kv = 0; kv < 2; ++kv) {
+        uint32_t in[4 * B];
+        load_chunks<2 * B>(src + kv * (512u * 2 * B), lane, in);
+        uint32_t out[2 * B];
+#pragma unroll
+        for (int d = 0; d < 2 * B; ++d) {
+            if constexpr (B == 2)
+                out[d] = shrink_4_to_2(in[2 * d]) | (shrink_4_to_2(in[2 * d + 1]) << 16);
+            else
+                out[d] = shrink_8_to_4(in[2 * d]) | (shrink_8_to_4(in[2 * d + 1]) << 16);
+        }
+        store_chunks<B>(dst + kv * (512u * B), lane, out);
+    }
+    const float f = (float)((1 << B) + 1);
+    uint32_t nk = (uint32_t)f2h_rn(h2f((uint16_t)(sk & 0xffff)) * f) | ((uint32_t)f2h_rn(h2f((uint16_t)(sk >> 16)) * f) << 16);
+    uint32_t nv = (uint32_t)f2h_rn(h2f((uint16_t)(sv & 0xffff)) * f) | ((uint32_t)f2h_rn(h2f((uint16_t)(sv >> 16)) * f) << 16);
+    reinterpret_cast<uint32_t*>(meta)[lane] = nk;
+    reinterpret_cast<uint32_t*>(meta + 512)[lane] = nv;
+}
+
+__global__ void kvq_fill_u32_kernel(uint32_t* dst, uint32_t value, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = value;
+}
+
+}  // namespace
+
+hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
+                             const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
+                             hipStream_t s) {
+    int tile0 = t_old / KVQ_TILE_TOKENS;
+    int tile1 = (t_old + n_new + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
+    dim3 grid(2 * (tile1 - tile0), units), block(64);
+    const uint16_t* k = static_cast<const uint16_t*>(k_in);
+    const uint16_t* v = static_cast<const uint16_t*>(v_in);
+    switch (bits) {
+        case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
+        case 8: hipLaunchKernelGGL(kvq_append_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
+        case 4: hipLaunchKernelGGL(kvq_append_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
+        case 2: hipLaunchKernelGGL(kvq_append_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
+                             int tiles_per_page, int units, hipStream_t s) {
+    dim3 grid(n_jobs * tiles_per_page, units), block(64);
+    switch (dst_bits) {
+        case 4: hipLaunchKernelGGL(kvq_shrink_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
+        case 2: hipLaunchKernelGGL(kvq_shrink_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
+                              int tiles_per_page, int units, hipStream_t s) {
+    dim3 grid(2 * n_jobs * tiles_per_page, units), block(64);
+    switch (dst_bits) {
+        case 8: hipLaunchKernelGGL(kvq_quant16_kernel<8>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
+        case 4: hipLaunchKernelGGL(kvq_quant16_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
+        case 2: hipLaunchKernelGGL(kvq_quant16_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t kvq_launch_fill_u32(uint32_t* dst, uint32_t value, size_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(kvq_fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, value, n);
+    return hipGetLastError();
+}

@@ -1,0 +1,254 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI (run with -m gpu on an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import kvq_synth
+import paper_2505_18610_amd as kq
+from oracle import OracleCache, CacheConfig, BudgetError, POLICY_PAPER, POLICY_OLDEST_FIRST, bytes_per_token_head
+from gpu_util import (dev, make_pair, append_both, assert_same_cache, check_attention, attention_errors,
+                      MAX_ABS, REL_L2)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("bits", [16, 8, 4, 2])
+def test_append_bit_exact_ragged_chunks(bits):
+    B, H, T, P = 2, 2, 427, 128
+    K, V = kvq_synth.make_kv(101, 0, B, H, 0, T)
+    oc, gc = make_pair(1, B, 2 * H, H, 1024, P)
+    t = 0
+    for n in (1, 31, 32, 100, 7, 129, 64, 63):
+        append_both(oc, gc, 0, K[:, :, t:t + n], V[:, :, t:t + n], bits)
+        t += n
+    assert t == T
+    assert_same_cache(oc, gc, 0)
+
+
+def test_append_one_shot_equals_token_by_token():
+    B, H, T, P = 1, 2, 200, 64
+    K, V = kvq_synth.make_kv(102, 0, B, H, 0, T)
+    for bits in (4, 2):
+        oc, gc = make_pair(1, B, 2 * H, H, 256, P)
+        append_both(oc, gc, 0, K, V, bits)
+        _, gc2 = make_pair(1, B, 2 * H, H, 256, P)
+        for t in range(T):
+            gc2.kvq_quantize_append(0, dev(K[:, :, t:t + 1]), dev(V[:, :, t:t + 1]), bits)
+        assert_same_cache(oc, gc, 0)
+        assert_same_cache(oc, gc2, 0)
+
+
+def test_quantizer_special_groups():
+    """Constant groups (S = 0), a group at the fp16 extremes' scale, tiny ranges, exact ties."""
+    B, H, T, P = 1, 1, 64, 32
+    rng = np.random.default_rng(3)
+    K = rng.standard_normal((B, H, T, 128)).astype(np.float16)
+    V = rng.standard_normal((B, H, T, 128)).astype(np.float16)
+    K[0, 0, 0, :32] = 0.75            # constant group
+    K[0, 0, 1, :] = 0.0               # all-zero token
+    K[0, 0, 2, 32:64] = np.linspace(0, 3, 32).astype(np.float16)   # ties at b = 2
+    K[0, 0, 3, :32] = (rng.standard_normal(32) * 1e-4).astype(np.float16)   # tiny range
+    K[0, 0, 4, 64:96] = (rng.standard_normal(32) * 2000).astype(np.float16)  # large range
+    V[0, 0, 5, :] = -2.5
+    for bits in (8, 4, 2):
+        oc, gc = make_pair(1, B, H, H, 64, P)
+        append_both(oc, gc, 0, K, V, bits)
+        assert_same_cache(oc, gc, 0)
+
+
+def test_requant_chain_bit_exact():
+    B, H, T, P = 2, 2, 512, 128
+    K, V = kvq_synth.make_kv(103, 0, B, H, 0, T)
+    oc, gc = make_pair(1, B, 2 * H, H, T, P)
+    append_both(oc, gc, 0, K, V, 16)
+    q = kvq_synth.make_q(103, 0, B, 2 * H, T - 1)
+    for want_bits in (8, 4, 2):
+        assert gc.kvq_progressive_requant(0, segment=0) == oc.requant(0, segment=0) == T // P
+        assert gc.kvq_cache_describe(0)[0] == [(0, T, want_bits)]
+        assert_same_cache(oc, gc, 0)
+        check_attention(oc, gc, 0, q)
+    with pytest.raises(kq.KvqError) as e:
+        gc.kvq_progressive_requant(0, segment=0)
+    assert e.value.status == kq.KVQ_E_STATE
+
+
+def test_shrink_of_directly_quantized_tiers():
+    """8 -> 4 and 4 -> 2 starting from tokens that entered at 8 / 4 bits, with a partly filled last page."""
+    B, H, P = 1, 2, 64
+    K, V = kvq_synth.make_kv(104, 0, B, H, 0, 300)
+    oc, gc = make_pair(1, B, 2 * H, H, 512, P)
+    append_both(oc, gc, 0, K[:, :, :128], V[:, :, :128], 4)
+    append_both(oc, gc, 0, K[:, :, 128:300], V[:, :, 128:300], 8)
+    assert gc.kvq_progressive_requant(0, segment=1) == oc.requant(0, segment=1)
+    assert gc.kvq_cache_describe(0)[0] == [(0, 300, 4)]
+    assert_same_cache(oc, gc, 0)
+    assert gc.kvq_progressive_requant(0, segment=0) == oc.requant(0, segment=0)
+    assert_same_cache(oc, gc, 0)
+    # the partly filled page keeps accepting tokens at the new width
+    K2, V2 = kvq_synth.make_kv(104, 0, B, H, 300, 340)
+    append_both(oc, gc, 0, K2, V2, 2)
+    assert_same_cache(oc, gc, 0)
+    check_attention(oc, gc, 0, kvq_synth.make_q(104, 0, B, 2 * H, 339))
+
+
+@pytest.mark.parametrize("policy,W,sink,fbit", [(POLICY_PAPER, 0, 0, 2), (POLICY_PAPER, 64, 32, 2),
+                                                (POLICY_OLDEST_FIRST, 32, 0, 2)])
+def test_progressive_decode_run_matches_oracle(policy, W, sink, fbit):
+    """A decode loop under a byte budget: append, shrink when the budget is hit, attend; state and outputs match."""
+    P, B, H, Tmax = 32, 1, 2, 640
+    budget = B * H * (420 * bytes_per_token_head(fbit, 128, 32, True) + (W + sink + 2 * P) * 512)
+    oc, gc = make_pair(1, B, 2 * H, H, Tmax, P, budgets=[budget], fbits=[fbit], window=W, n_sink=sink, policy=policy)
+    K, V = kvq_synth.make_kv(105, 0, B, H, 0, Tmax)
+    rng = np.random.default_rng(5)
+    t, events = 0, 0
+    while t < Tmax:
+        n = min(int(rng.integers(1, 24)), Tmax - t)
+        try:
+            oc.append(0, K[:, :, t:t + n], V[:, :, t:t + n])
+        except BudgetError:
+            with pytest.raises(kq.KvqError) as e:
+                gc.kvq_quantize_append(0, dev(K[:, :, t:t + n]), dev(V[:, :, t:t + n]))
+            assert e.value.status == kq.KVQ_E_BUDGET
+            try:
+                done = oc.requant(0, reserve_tokens=n)
+            except BudgetError:
+                break
+            assert gc.kvq_progressive_requant(0, reserve_tokens=n) == done
+            events += 1
+            assert_same_cache(oc, gc, 0)
+            check_attention(oc, gc, 0, kvq_synth.make_q(105, 0, B, 2 * H, t))
+            continue
+        gc.kvq_quantize_append(0, dev(K[:, :, t:t + n]), dev(V[:, :, t:t + n]))
+        t += n
+    assert events >= 2
+    assert_same_cache(oc, gc, 0)
+    check_attention(oc, gc, 0, kvq_synth.make_q(105, 0, B, 2 * H, t))
+
+
+def _build_workload(w, layer=0, B=None, rope=True):
+    B = B or w.batch
+    oc, gc = make_pair(1, B, w.n_q_heads, w.n_kv_heads, w.n_tokens, w.page_tokens)
+    t = 0
+    for n, bits in w.tiers_of_layer(layer):
+        K, V = kvq_synth.make_kv(w.seed, layer, B, w.n_kv_heads, t, t + n, rope_base=w.rope_base)
+        append_both(oc, gc, 0, K, V, bits)
+        t += n
+    return oc, gc
+
+
+def test_attention_tiny_config():
+    """BASELINE config 'Tiny': 8 q / 2 kv heads, 4 x 1,024 tokens at 2/4/8/16 bits, outlier channels x20, seed 0."""
+    w = kvq_synth.WORKLOADS["tiny"]
+    oc, gc = _build_workload(w)
+    assert_same_cache(oc, gc, 0)
+    q = kvq_synth.make_q(w.seed, 0, 1, 8, 4095, rope_base=None)
+    for dt in (torch.float32, torch.float16):
+        mx, rl = check_attention(oc, gc, 0, q, dt)
+        print("tiny", dt, mx, rl)
+
+
+@pytest.mark.parametrize("bits", [16, 8, 4, 2])
+@pytest.mark.parametrize("gqa", [1, 5, 8, 16])
+def test_attention_each_tier_and_group_size(bits, gqa):
+    B, H, T, P = 2, 2, 1000, 128
+    K, V = kvq_synth.make_kv(200 + bits, 0, B, H, 0, T)
+    oc, gc = make_pair(1, B, gqa * H, H, 1024, P)
+    append_both(oc, gc, 0, K, V, bits)
+    q = kvq_synth.make_q(200 + bits, 0, B, gqa * H, T - 1)
+    check_attention(oc, gc, 0, q)
+
+
+def test_attention_16bit_is_exact_attention():
+    B, H, T, P = 1, 2, 777, 64
+    K, V = kvq_synth.make_kv(300, 0, B, H, 0, T)
+    oc, gc = make_pair(1, B, 4 * H, H, 1024, P)
+    append_both(oc, gc, 0, K, V, 16)
+    q = kvq_synth.make_q(300, 0, B, 4 * H, T - 1)
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    gc.kvq_decode_attention(0, dev(q), out)
+    from oracle import decode_attention_fp64
+    want = decode_attention_fp64(q, K, V)
+    mx, rl = attention_errors(out.cpu().numpy(), want)
+    assert mx <= 1e-3 and rl <= 5e-4, (mx, rl)
+
+
+@pytest.mark.parametrize("T", [1, 2, 31, 32, 33, 127, 129])
+def test_attention_short_caches(T):
+    B, H, P = 1, 1, 32
+    K, V = kvq_synth.make_kv(400 + T, 0, B, H, 0, T)
+    for bits in (16, 4):
+        oc, gc = make_pair(1, B, 4, H, 256, P)
+        append_both(oc, gc, 0, K, V, bits)
+        check_attention(oc, gc, 0, kvq_synth.make_q(400, 0, B, 4, T - 1))
+
+
+def test_empty_cache_is_a_state_error():
+    _, gc = make_pair(1, 1, 4, 1, 256, 32)
+    out = torch.empty((1, 4, 128), dtype=torch.float32, device="cuda")
+    with pytest.raises(kq.KvqError) as e:
+        gc.kvq_decode_attention(0, out, out)
+    assert e.value.status == kq.KVQ_E_STATE
+
+
+def test_split_count_and_merge_variant_invariance():
+    w = kvq_synth.WORKLOADS["tiny"]
+    oc, gc = _build_workload(w)
+    q = kvq_synth.make_q(w.seed, 0, 1, 8, 4095, rope_base=None)
+    ref = None
+    for fused in (0, 1):
+        gc.kvq_cache_set_option(kq.KVQ_OPT_FUSED_MERGE, fused)
+        for n in (1, 2, 3, 7, 32, 128, 0):
+            gc.kvq_cache_set_option(kq.KVQ_OPT_SPLITS, n)
+            out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+            for _ in range(3):       # repeated launches reuse the arrival counters
+                out.zero_()
+                gc.kvq_decode_attention(0, dev(q), out)
+            torch.cuda.synchronize()
+            o = out.cpu().numpy()
+            if ref is None:
+                ref = o
+                check_attention(oc, gc, 0, q)
+            assert np.abs(o - ref).max() <= 2e-4, (fused, n, np.abs(o - ref).max())
+
+
+def test_softmax_scale_and_multi_layer():
+    B, H, T, P = 1, 2, 300, 64
+    oc, gc = make_pair(3, B, 2 * H, H, 512, P)
+    for layer, bits in enumerate((8, 2, 16)):
+        K, V = kvq_synth.make_kv(500, layer, B, H, 0, T)
+        append_both(oc, gc, layer, K, V, bits)
+    for layer in range(3):
+        q = kvq_synth.make_q(500, layer, B, 2 * H, T - 1)
+        check_attention(oc, gc, layer, q, scale=0.05)
+        assert_same_cache(oc, gc, layer)
+
+
+def test_full_size_32b_layer_sampled_units():
+    """One block of the 32B-shaped workload at full size, in the launch configuration the bench uses; the oracle
+    checks sampled (sequence, KV head) units one by one."""
+    w = kvq_synth.WORKLOADS["32b"]
+    B, Hkv, g = w.batch, w.n_kv_heads, w.n_q_heads // w.n_kv_heads
+    cfg = kq.KvqConfig(1, B, w.n_q_heads, Hkv, w.n_tokens, page_tokens=w.page_tokens)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, w.n_tokens * B * Hkv * 320), dtype=torch.uint8, device="cuda")
+    gc = kq.KvqCache(cfg, [1 << 50], [2], arena=arena)
+    t = 0
+    for n, bits in w.tiers:
+        K, V = kvq_synth.make_kv(w.seed, 0, B, Hkv, t, t + n)
+        gc.kvq_quantize_append(0, dev(K), dev(V), bits)
+        t += n
+    q = kvq_synth.make_q(w.seed, 0, B, w.n_q_heads, w.n_tokens - 1)
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    gc.kvq_decode_attention(0, dev(q), out)
+    got = out.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    for b, h in ((0, 0), (3, 7), (1, 4)):
+        oc = OracleCache(CacheConfig(1, 1, g, 1, page_tokens=w.page_tokens, max_tokens=w.n_tokens), [1 << 50], [2])
+        t = 0
+        for n, bits in w.tiers:
+            k, v = kvq_synth.make_kv_unit(w.seed, 0, b, h, t, t + n)
+            oc.append(0, k[None, None], v[None, None], bits)
+            t += n
+        want = oc.attention(0, q[b:b + 1, h * g:(h + 1) * g])
+        mx, rl = attention_errors(got[b:b + 1, h * g:(h + 1) * g], want)
+        print("32b unit", b, h, mx, rl)
+        assert mx <= MAX_ABS and rl <= REL_L2, (b, h, mx, rl)

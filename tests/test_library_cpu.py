@@ -1,0 +1,160 @@
+"""CPU checks of libkvq: exported symbols, argument errors, and the host bookkeeping (accounting-only caches)
+against the oracle's bookkeeping on the same operation sequences.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import kvq_synth
+import paper_2505_18610_amd as kq
+from oracle import (OracleCache, CacheConfig, BudgetError, StateError, POLICY_PAPER, POLICY_OLDEST_FIRST,
+                    bytes_per_token_head)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+pytestmark = pytest.mark.skipif(not os.path.exists(kq.library_path()), reason="libkvq.so not built")
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "kvq.h")).read()
+    declared = set(re.findall(r"\b(kvq_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(kq.exported_symbols())
+    lib = ctypes.CDLL(kq.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_bytes_per_token_head_matches_oracle_and_paper_shapes():
+    for b in (16, 8, 4, 2):
+        for G in (32, 64, 128):
+            for m in (0, 1):
+                assert kq.kvq_bytes_per_token_head(b, 128, G, m) == bytes_per_token_head(b, 128, G, bool(m))
+    assert kq.kvq_bytes_per_token_head(3) == 0
+
+
+def test_invalid_configs_and_arguments():
+    good = dict(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, max_tokens=1024, page_tokens=128)
+    for bad in (dict(head_dim=64), dict(group=128), dict(page_tokens=48), dict(n_q_heads=7), dict(window=100),
+                dict(n_sink=5), dict(policy=7), dict(n_q_heads=64, n_kv_heads=2)):
+        cfg = kq.KvqConfig(**{**good, **bad})
+        assert kq.kvq_arena_bytes(cfg, 0) == 0
+        with pytest.raises(kq.KvqError) as e:
+            kq.KvqCache(cfg, [1 << 30], [2], arena=None, arena_bytes=1 << 30)
+        assert e.value.status == kq.KVQ_E_INVALID
+    cfg = kq.KvqConfig(**good)
+    with pytest.raises(kq.KvqError):
+        kq.KvqCache(cfg, [1 << 30], [3], arena=None, arena_bytes=1 << 30)          # Fbit not a power of two
+    with pytest.raises(kq.KvqError) as e:
+        kq.KvqCache(cfg, [1 << 30], [2], arena=None, arena_bytes=1024)             # arena too small
+    assert e.value.status == kq.KVQ_E_OOM
+    c = kq.KvqCache(cfg, [1 << 30], [2], arena=None, arena_bytes=1 << 26)
+    for call, status in ((lambda: c.kvq_quantize_append(1, None, None, n_new=1), kq.KVQ_E_INVALID),
+                         (lambda: c.kvq_quantize_append(0, None, None, n_new=1, entry_bits=3), kq.KVQ_E_INVALID),
+                         (lambda: c.kvq_quantize_append(0, None, None, n_new=2000), kq.KVQ_E_STATE),
+                         (lambda: c.kvq_progressive_requant(0, segment=0), kq.KVQ_E_STATE)):
+        with pytest.raises(kq.KvqError) as e:
+            call()
+        assert e.value.status == status
+    c.kvq_quantize_append(0, None, None, n_new=40, entry_bits=8)
+    with pytest.raises(kq.KvqError) as e:
+        c.kvq_quantize_append(0, None, None, n_new=8, entry_bits=4)                # width change inside a page
+    assert e.value.status == kq.KVQ_E_STATE
+    assert c.kvq_cache_describe(0)[0] == [(0, 40, 8)]
+    assert kq.kvq_status_string(kq.KVQ_E_OOM) != kq.kvq_status_string(kq.KVQ_OK)
+
+
+def _pair(policy, P, W, sink, budget, fbit, meta=1, Tmax=4096, B=2, H=2):
+    ocfg = CacheConfig(1, B, 2 * H, H, page_tokens=P, max_tokens=Tmax, window=W, n_sink=sink, policy=policy,
+                       count_metadata_in_budget=meta)
+    oc = OracleCache(ocfg, [budget], [fbit])
+    cfg = kq.KvqConfig(1, B, 2 * H, H, Tmax, page_tokens=P, window=W, n_sink=sink, policy=policy,
+                       count_metadata_in_budget=meta)
+    gc = kq.KvqCache(cfg, [budget], [fbit], arena=None, arena_bytes=1 << 30)
+    return oc, gc
+
+
+def _same_state(oc, gc):
+    segs, used, T, cur = gc.kvq_cache_describe(0)
+    assert segs == oc.segments(0)
+    assert used == oc.bytes_used(0)
+    assert T == oc.layers[0].T
+    assert cur == oc.current_bits(0)
+
+
+@pytest.mark.parametrize("policy,W,sink,fbit", [(POLICY_PAPER, 0, 0, 2), (POLICY_PAPER, 64, 32, 2),
+                                                (POLICY_PAPER, 64, 0, 4), (POLICY_OLDEST_FIRST, 32, 0, 2),
+                                                (POLICY_OLDEST_FIRST, 0, 32, 4)])
+def test_bookkeeping_matches_oracle_on_random_decode_runs(policy, W, sink, fbit):
+    P, B, H = 32, 2, 2
+    rng = np.random.default_rng(hash((policy, W, sink, fbit)) % 2 ** 32)
+    budget = B * H * (500 * bytes_per_token_head(fbit, 128, 32, True) + (W + sink + 2 * P) * 512)
+    oc, gc = _pair(policy, P, W, sink, budget, fbit, Tmax=1024, B=B, H=H)
+    K, V = kvq_synth.make_kv(77, 0, B, H, 0, 1024, rope_base=None)
+    t = 0
+    exhausted = False
+    while t < 1024 and not exhausted:
+        n = int(rng.integers(1, 40))
+        n = min(n, 1024 - t)
+        try:
+            oc.append(0, K[:, :, t:t + n], V[:, :, t:t + n])
+            ok = True
+        except BudgetError:
+            ok = False
+        if ok:
+            gc.kvq_quantize_append(0, None, None, n_new=n)
+            t += n
+        else:
+            with pytest.raises(kq.KvqError) as e:
+                gc.kvq_quantize_append(0, None, None, n_new=n)
+            assert e.value.status == kq.KVQ_E_BUDGET
+            _same_state(oc, gc)
+            try:
+                done = oc.requant(0, reserve_tokens=n)
+            except BudgetError:
+                with pytest.raises(kq.KvqError) as e:
+                    gc.kvq_progressive_requant(0, reserve_tokens=n)
+                assert e.value.status == kq.KVQ_E_BUDGET
+                exhausted = True
+            else:
+                assert gc.kvq_progressive_requant(0, reserve_tokens=n) == done
+        _same_state(oc, gc)
+    assert exhausted and t > 400
+
+
+def test_explicit_construction_and_segment_requant_match_oracle():
+    oc, gc = _pair(POLICY_PAPER, 64, 0, 0, 1 << 40, 2, Tmax=2048, B=1, H=2)
+    K, V = kvq_synth.make_kv(78, 0, 1, 2, 0, 2048, rope_base=None)
+    t = 0
+    for n, b in ((256, 2), (320, 4), (448, 8), (100, 16)):
+        oc.append(0, K[:, :, t:t + n], V[:, :, t:t + n], b)
+        gc.kvq_quantize_append(0, None, None, n_new=n, entry_bits=b)
+        t += n
+    _same_state(oc, gc)
+    for seg in (3, 2, 1):
+        assert gc.kvq_progressive_requant(0, segment=seg) == oc.requant(0, segment=seg)
+        _same_state(oc, gc)
+    with pytest.raises(StateError):
+        oc.requant(0, segment=0)
+    with pytest.raises(kq.KvqError) as e:
+        gc.kvq_progressive_requant(0, segment=0)
+    assert e.value.status == kq.KVQ_E_STATE
+
+
+def test_arena_accounting_and_reuse():
+    cfg = kq.KvqConfig(2, 1, 2, 1, 4096, page_tokens=128)
+    need = kq.kvq_arena_bytes(cfg, 0)
+    unit = 32 * 128 * 1
+    c = kq.KvqCache(cfg, [1 << 40, 1 << 40], [2, 2], arena=None, arena_bytes=need + 3 * 16 * unit)
+    free0 = c.kvq_cache_arena_free_bytes()
+    assert free0 == 3 * 16 * unit
+    for _ in range(3):
+        c.kvq_quantize_append(0, None, None, n_new=128, entry_bits=16)
+    with pytest.raises(kq.KvqError) as e:
+        c.kvq_quantize_append(1, None, None, n_new=1, entry_bits=16)
+    assert e.value.status == kq.KVQ_E_OOM and c.kvq_cache_describe(1)[2] == 0
+    # shrinking needs room for the new block first: 16 -> 8 of one page cannot start with a full arena
+    with pytest.raises(kq.KvqError) as e:
+        c.kvq_progressive_requant(0, segment=0)
+    assert e.value.status == kq.KVQ_E_OOM and c.kvq_cache_describe(0)[0] == [(0, 384, 16)]
+    assert c.kvq_cache_arena_free_bytes() == 0
