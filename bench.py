@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the PM-KVQ hot path on one MI355X.
+
+A step is one decode step of the whole path over all transformer blocks: for every block, quantize-append
+one new token (K, V) and run single-token GQA attention over the block's mixed-width cache (the shrink step
+runs whenever the block's budget asks for it; in the steady state timed here it does not trigger, so its
+throughput is measured separately after the timed region and reported under "requant").
+
+Prints ONE JSON line.  value = KV tokens/s = batch * cached tokens * blocks / step time, inputs resident in HBM.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+
+def tier_bytes(tiers, units, bpth):
+    return sum(n * units * bpth(b) for n, b in tiers)
+
+
+def build_state(kq, torch, w, steps_total):
+    """All blocks of workload w resident in HBM, short of the final context by the tokens the steps will append."""
+    import kvq_synth
+    B, Hkv, L = w.batch, w.n_kv_heads, w.n_layers
+    units = B * Hkv
+    tiers0 = list(w.tiers)
+    assert steps_total < tiers0[-1][0], "timed steps must fit into the newest tier"
+    payload = 0
+    for layer in range(L):
+        payload += sum(n * units * kq.kvq_bytes_per_token_head(b) for n, b in w.tiers_of_layer(layer))
+    payload = int(payload * 1.02) + L * w.page_tokens * units * 512 + (256 << 20)
+    cfg = kq.KvqConfig(L, B, w.n_q_heads, Hkv, w.n_tokens, page_tokens=w.page_tokens,
+                       policy=kq.KVQ_POLICY_OLDEST_FIRST)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, payload), dtype=torch.uint8, device="cuda")
+    cache = kq.KvqCache(cfg, [1 << 60] * L, [2] * L, arena=arena)
+    t0 = time.time()
+    K, V = kvq_synth.make_kv(w.seed, 0, B, Hkv, 0, w.n_tokens, rope_base=w.rope_base)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    gen_s = time.time() - t0
+    append_stats = {}
+    for layer in range(L):
+        t = 0
+        tiers = list(w.tiers_of_layer(layer))
+        tiers[-1] = (tiers[-1][0] - steps_total, tiers[-1][1])
+        for n, bits in tiers:
+            k = Kd[:, :, t:t + n].contiguous()
+            v = Vd[:, :, t:t + n].contiguous()
+            if layer == 0:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            cache.kvq_quantize_append(layer, k, v, bits)
+            if layer == 0:
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1)
+                moved = n * units * (512 + kq.kvq_bytes_per_token_head(bits))
+                append_stats[f"bulk_{bits}bit_GBps"] = round(moved / ms / 1e6, 1)
+            t += n
+        del k, v
+    torch.cuda.synchronize()
+    tail = (Kd[:, :, -steps_total:].contiguous(), Vd[:, :, -steps_total:].contiguous())
+    del Kd, Vd
+    return cache, arena, tail, gen_s, append_stats, (K, V)
+
+
+def measure_requant(kq, torch):
+    """16 -> 8 -> 4 -> 2 on one 14B-shaped block of 16,384 tokens (64 units); GB/s = (read + written) / time."""
+    B, Hkv, T, P = 8, 8, 16384, 256
+    units = B * Hkv
+    cfg = kq.KvqConfig(1, B, 40, Hkv, T, page_tokens=P)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, int(T * units * 512 * 1.8)), dtype=torch.uint8, device="cuda")
+    cache = kq.KvqCache(cfg, [1 << 60], [2], arena=arena)
+    g = torch.Generator(device="cuda").manual_seed(14)
+    k = torch.randn((B, Hkv, T, 128), device="cuda", generator=g).half()
+    v = torch.randn((B, Hkv, T, 128), device="cuda", generator=g).half()
+    cache.kvq_quantize_append(0, k, v, 16)
+    del k, v
+    elems = T * units * 256
+    per_elem = {8: 3.125, 4: 1.75, 2: 1.0}      # algorithmic bytes per element, read + write, group 32
+    out = {}
+    for b in (8, 4, 2):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        cache.kvq_progressive_requant(0, segment=0)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        gbps = elems * per_elem[b] / ms / 1e6
+        out[f"{2 * b}to{b}"] = {"ms": round(ms, 4), "GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+    cache.close()
+    return out
+
+
+def cpu_baseline(w, KV, q_np, seconds_hint=20.0):
+    """The oracle's attention (de-quantize + fp64 attention) on one sequence of one block of the same workload."""
+    from oracle import OracleCache, CacheConfig
+    try:
+        from threadpoolctl import threadpool_info
+    except Exception:                                   # pragma: no cover
+        threadpool_info = None
+    K, V = KV
+    g = w.n_q_heads // w.n_kv_heads
+    oc = OracleCache(CacheConfig(1, 1, w.n_q_heads, w.n_kv_heads, page_tokens=w.page_tokens, max_tokens=w.n_tokens),
+                     [1 << 60], [2])
+    t = 0
+    for n, bits in w.tiers_of_layer(0):
+        oc.append(0, K[:1, :, t:t + n], V[:1, :, t:t + n], bits)
+        t += n
+    reps, t0 = 0, time.time()
+    while True:
+        oc.attention(0, q_np[:1])
+        reps += 1
+        if time.time() - t0 > seconds_hint or reps >= 3:
+            break
+    dt = (time.time() - t0) / reps
+    threads = 1
+    if threadpool_info is not None:
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": round(w.n_tokens / dt, 1), "unit": "KV tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"one sequence of one block ({w.n_kv_heads} KV heads x {w.n_tokens} tokens, {g} query heads each), "
+                      f"numpy fp64 de-quantize + attention, {reps} repetition(s), {dt:.2f} s each"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="32b", choices=["7b", "14b", "32b", "70b"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-requant", action="store_true")
+    ap.add_argument("--fused-merge", type=int, default=None)
+    ap.add_argument("--splits", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path needs no cross-GPU step); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import kvq_synth
+    import paper_2505_18610_amd as kq
+    kq.load_library()
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    w = kvq_synth.WORKLOADS[args.workload]
+    B, Hkv, Hq, L = w.batch, w.n_kv_heads, w.n_q_heads, w.n_layers
+    units = B * Hkv
+    steps_total = args.steps + args.warmup
+
+    cache, arena, (k_tail, v_tail), gen_s, append_stats, KV = build_state(kq, torch, w, steps_total)
+    if args.fused_merge is not None:
+        cache.kvq_cache_set_option(kq.KVQ_OPT_FUSED_MERGE, args.fused_merge)
+    if args.splits:
+        cache.kvq_cache_set_option(kq.KVQ_OPT_SPLITS, args.splits)
+    q_np = kvq_synth.make_q(w.seed, 0, B, Hq, w.n_tokens - 1, rope_base=w.rope_base)
+    q = torch.from_numpy(q_np).cuda()
+    outs = [torch.empty((B, Hq, 128), dtype=torch.float16, device="cuda") for _ in range(L)]
+    new_k = [k_tail[:, :, i:i + 1].contiguous() for i in range(steps_total)]
+    new_v = [v_tail[:, :, i:i + 1].contiguous() for i in range(steps_total)]
+    stream = torch.cuda.current_stream()
+
+    def step(i, events=None):
+        for layer in range(L):
+            cache.kvq_quantize_append(layer, new_k[i], new_v[i], 0, stream)
+            if events is not None:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+            cache.kvq_decode_attention(layer, q, outs[layer], 0.0, stream)
+            if events is not None:
+                e1.record(stream)
+                events.append((e0, e1))
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for i in range(args.warmup, steps_total):
+        step(i, events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    _, _, T_end, _ = cache.kvq_cache_describe(0)
+    T_mid = T_end - args.steps / 2.0
+    kv_tokens_per_s = B * T_mid * L / (ms_per_step * 1e-3)
+
+    # roofline of the dominant kernel (fused de-quantize + decode attention), one launch = one block
+    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+    bytes_per_launch = 0
+    for layer in range(L):
+        segs, _, _, _ = cache.kvq_cache_describe(layer)
+        bytes_per_launch += sum((t1_ - t0_) * units * kq.kvq_bytes_per_token_head(b) for t0_, t1_, b in segs)
+    bytes_per_launch /= L
+    achieved = bytes_per_launch / (attn_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "kernel": "kvq_attention_kernel", "avg_launch_ms": round(attn_ms, 5),
+                "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+
+    result = {
+        "metric": "decode-attention KV tokens/s per GPU", "value": round(kv_tokens_per_s, 1), "unit": "KV tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{w.name}-shaped: {L} blocks, {Hq}q/{Hkv}kv heads, head_dim 128, batch {B}, "
+                               f"{w.n_tokens} cached tokens, tiers (tokens,bits) {list(w.tiers_of_layer(0))}, group 32, "
+                               f"page {w.page_tokens} tokens",
+                   "step": "per block: append 1 token + decode attention", "layers_share_values": True},
+        "hbm_GBps_whole_step": round(bytes_per_launch * L / (ms_per_step * 1e-3) / 1e9, 1),
+        "hbm_frac_whole_step": round(bytes_per_launch * L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "roofline": roofline,
+        "append": append_stats,
+    }
+    del outs
+    if not args.no_requant:
+        result["requant"] = measure_requant(kq, torch)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, KV, q_np)
+    result["setup_seconds"] = {"generate_inputs": round(gen_s, 1)}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

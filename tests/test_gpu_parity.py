@@ -112,6 +112,9 @@ def test_progressive_decode_run_matches_oracle(policy, W, sink, fbit):
             try:
                 done = oc.requant(0, reserve_tokens=n)
             except BudgetError:
+                with pytest.raises(kq.KvqError) as e:       # steps taken before running out stay, on both sides
+                    gc.kvq_progressive_requant(0, reserve_tokens=n)
+                assert e.value.status == kq.KVQ_E_BUDGET
                 break
             assert gc.kvq_progressive_requant(0, reserve_tokens=n) == done
             events += 1
