@@ -50,11 +50,20 @@ __device__ inline float mixf(uint32_t packed, int hi) {  // fp16 half of a dword
     return (float)(hi ? h.y : h.x);
 }
 
+// (x & mask) | magic in one VALU op; gfx9 VOP3 takes no literals and one scalar operand, so the mask rides in
+// an SGPR and the magic constant in a VGPR.
+__device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(magic));
+    return r;
+}
+
 // Piece p (8 consecutive slots) of a lane's packed string -> 8 exact fp16 integers in MFMA operand order:
 // operand register v holds slots v (low half) and v+4 (high half).
 template <int B>
 __device__ inline half8 dq_piece(const uint32_t* w, int p) {
     uint32_t r0, r1, r2, r3;
+    const uint32_t magic = KVQ_MAGIC;
     if constexpr (B == 8) {
         uint32_t w0 = w[2 * p], w1 = w[2 * p + 1];
         r0 = pk_add(__builtin_amdgcn_perm(w1, w0, 0x0c040c00u) | KVQ_MAGIC, -1024.f);
@@ -63,17 +72,17 @@ __device__ inline half8 dq_piece(const uint32_t* w, int p) {
         r3 = pk_add(__builtin_amdgcn_perm(w1, w0, 0x0c070c03u) | KVQ_MAGIC, -1024.f);
     } else if constexpr (B == 4) {
         uint32_t x = w[p], y = x >> 8;
-        r0 = pk_add((x & 0x000f000fu) | KVQ_MAGIC, -1024.f);
-        r1 = pk_fma((x & 0x00f000f0u) | KVQ_MAGIC, 0.0625f, -64.f);
-        r2 = pk_add((y & 0x000f000fu) | KVQ_MAGIC, -1024.f);
-        r3 = pk_fma((y & 0x00f000f0u) | KVQ_MAGIC, 0.0625f, -64.f);
+        r0 = pk_add(and_or(x, 0x000f000fu, magic), -1024.f);
+        r1 = pk_fma(and_or(x, 0x00f000f0u, magic), 0.0625f, -64.f);
+        r2 = pk_add(and_or(y, 0x000f000fu, magic), -1024.f);
+        r3 = pk_fma(and_or(y, 0x00f000f0u, magic), 0.0625f, -64.f);
     } else {  // B == 2: 16 bits of dword p/2
         uint32_t x = w[p >> 1];
         uint32_t t = (p & 1) ? __builtin_amdgcn_perm(0u, x, 0x0c030c02u) : __builtin_amdgcn_perm(0u, x, 0x0c010c00u);
-        r0 = pk_add((t & 0x00030003u) | KVQ_MAGIC, -1024.f);
-        r1 = pk_fma((t & 0x000c000cu) | KVQ_MAGIC, 0.25f, -256.f);
-        r2 = pk_fma((t & 0x00300030u) | KVQ_MAGIC, 0.0625f, -64.f);
-        r3 = pk_fma((t & 0x00c000c0u) | KVQ_MAGIC, 0.015625f, -16.f);
+        r0 = pk_add(and_or(t, 0x00030003u, magic), -1024.f);
+        r1 = pk_fma(and_or(t, 0x000c000cu, magic), 0.25f, -256.f);
+        r2 = pk_fma(and_or(t, 0x00300030u, magic), 0.0625f, -64.f);
+        r3 = pk_fma(and_or(t, 0x00c000c0u, magic), 0.015625f, -16.f);
     }
     return as_half8(r0, r1, r2, r3);
 }
@@ -120,66 +129,86 @@ __device__ inline float4v mfma(half8 a, half8 b, float4v c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
-// One 32-token tile of width B.  `code` points at the K tile (the V tile follows), `meta` at the tile's
-// metadata.  tok0 = first token of the tile, n_tokens = cache length (tokens beyond it are masked).
+// Registers of one tile in flight: the lane's packed K and V strings and its 16-byte share of the metadata.
 template <int B>
-__device__ inline void process_tile(WaveState& st, const QOps& Q, const uint8_t* __restrict__ code,
-                                    const uint8_t* __restrict__ meta, int tok0, int n_tokens, float scale_log2,
-                                    int lane) {
+struct Stage {
+    uint32_t kw[2 * B];
+    uint32_t vw[2 * B];
+    u32x4 meta;
+};
+
+// Issue every global load of one tile (nothing waits here).
+template <int B>
+__device__ inline void issue_tile(Stage<B>& sg, const uint8_t* __restrict__ code, const uint8_t* __restrict__ meta,
+                                  int lane) {
+    load_string<2 * B>(code, lane, sg.kw);
+    load_string<2 * B>(code + 512u * B, lane, sg.vw);
+    if constexpr (B < 16) sg.meta = *reinterpret_cast<const u32x4*>(meta + lane * 16);
+}
+
+// One 32-token tile of width B from registers.  meta_lds: this wavefront's 1 KiB staging area, through which
+// the metadata is redistributed (each lane needs the scales of the 8 tokens of its quarter).
+// tok0 = first token of the tile, n_tokens = cache length (tokens beyond it are masked).
+template <int B>
+__device__ inline void compute_k(WaveState& st, const QOps& Q, const uint32_t (&kw)[2 * B], const u32x4& meta_regs,
+                                 uint8_t* meta_lds, int tok0, int n_tokens, float scale_log2, int lane,
+                                 uint32_t (&pop)[4]) {
     const int j = lane >> 4, n = lane & 15;
-    constexpr int NDW = 2 * B;
     const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
     float s[2][4];
 
+    if constexpr (B < 16) {
+        *reinterpret_cast<u32x4*>(meta_lds + lane * 16) = meta_regs;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+
     // ---- K: scores^T for the 32 tokens x 16 heads
-    {
-        uint32_t kw[NDW];
-        load_string<NDW>(code, lane, kw);
-        if constexpr (B == 16) {
+    if constexpr (B == 16) {
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                float4v acc = zero4;
+        for (int sub = 0; sub < 2; ++sub) {
+            float4v acc = zero4;
 #pragma unroll
-                for (int grp = 0; grp < 4; ++grp) {
-                    int p = sub * 4 + grp;
-                    half8 a = as_half8(kw[4 * p], kw[4 * p + 1], kw[4 * p + 2], kw[4 * p + 3]);
-                    half8 b = as_half8(Q.q[grp][0], Q.q[grp][1], Q.q[grp][2], Q.q[grp][3]);
-                    acc = mfma(a, b, acc);
+            for (int grp = 0; grp < 4; ++grp) {
+                int p = sub * 4 + grp;
+                half8 a = as_half8(kw[4 * p], kw[4 * p + 1], kw[4 * p + 2], kw[4 * p + 3]);
+                half8 b = as_half8(Q.q[grp][0], Q.q[grp][1], Q.q[grp][2], Q.q[grp][3]);
+                acc = mfma(a, b, acc);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[sub][i] = acc[i];
+        }
+    } else {
+        // scales of the 8 tokens whose scores this lane quarter receives: tokens 8j .. 8j+7, 4 groups each
+        uint32_t ks[16];
+        const u32x4* ksp = reinterpret_cast<const u32x4*>(meta_lds + j * 64);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            u32x4 v = ksp[c];
+            ks[4 * c] = v.x; ks[4 * c + 1] = v.y; ks[4 * c + 2] = v.z; ks[4 * c + 3] = v.w;
+        }
+        half8 qs = as_half8(Q.qsum[0], Q.qsum[1], Q.qsum[2], Q.qsum[3]);
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            // zero points of the token this lane supplies as an A row: token 8*(n/4) + 4*sub + n%4
+            int t = 8 * (n >> 2) + 4 * sub + (n & 3);
+            u32x2 kz = *reinterpret_cast<const u32x2*>(meta_lds + 256 + t * 8);
+            float4v acc = mfma(as_half8(kz.x, kz.y, kz.x, kz.y), qs, zero4);
+#pragma unroll
+            for (int grp = 0; grp < 4; ++grp) {
+                half8 a = dq_piece<B>(kw, sub * 4 + grp);
+                half8 b = as_half8(Q.q[grp][0], Q.q[grp][1], Q.q[grp][2], Q.q[grp][3]);
+                float4v part = mfma(a, b, zero4);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int tk = 4 * sub + i;  // token 8j + tk: dwords 2*tk, 2*tk+1 hold its four scales
+                    float sc = mixf(ks[2 * tk + (grp >> 1)], grp & 1);
+                    acc[i] = fmaf(sc, part[i], acc[i]);
                 }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) s[sub][i] = acc[i];
             }
-        } else {
-            // scales of the 8 tokens whose scores this lane quarter receives: tokens 8j .. 8j+7, 4 groups each
-            uint32_t ks[16];
-            const u32x4* ksp = reinterpret_cast<const u32x4*>(meta + j * 64);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                u32x4 v = ksp[c];
-                ks[4 * c] = v.x; ks[4 * c + 1] = v.y; ks[4 * c + 2] = v.z; ks[4 * c + 3] = v.w;
-            }
-            half8 qs = as_half8(Q.qsum[0], Q.qsum[1], Q.qsum[2], Q.qsum[3]);
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                // zero points of the token this lane supplies as an A row: token 8*(n/4) + 4*sub + n%4
-                int t = 8 * (n >> 2) + 4 * sub + (n & 3);
-                u32x2 kz = *reinterpret_cast<const u32x2*>(meta + 256 + t * 8);
-                float4v acc = mfma(as_half8(kz.x, kz.y, kz.x, kz.y), qs, zero4);
-#pragma unroll
-                for (int grp = 0; grp < 4; ++grp) {
-                    half8 a = dq_piece<B>(kw, sub * 4 + grp);
-                    half8 b = as_half8(Q.q[grp][0], Q.q[grp][1], Q.q[grp][2], Q.q[grp][3]);
-                    float4v part = mfma(a, b, zero4);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        int tk = 4 * sub + i;  // token 8j + tk: dwords 2*tk, 2*tk+1 hold its four scales
-                        float sc = mixf(ks[2 * tk + (grp >> 1)], grp & 1);
-                        acc[i] = fmaf(sc, part[i], acc[i]);
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) s[sub][i] = acc[i];
-            }
+            for (int i = 0; i < 4; ++i) s[sub][i] = acc[i];
         }
     }
 
@@ -189,11 +218,19 @@ __device__ inline void process_tile(WaveState& st, const QOps& Q, const uint8_t*
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float x = s[sub][i] * scale_log2;
-            if (tok0 + 8 * j + 4 * sub + i >= n_tokens) x = -INFINITY;
-            s[sub][i] = x;
-            tmax = fmaxf(tmax, x);
+            s[sub][i] *= scale_log2;
+            tmax = fmaxf(tmax, s[sub][i]);
         }
+    if (tok0 + KVQ_TILE_TOKENS > n_tokens) {  // ragged last tile only
+        tmax = -INFINITY;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (tok0 + 8 * j + 4 * sub + i >= n_tokens) s[sub][i] = -INFINITY;
+                tmax = fmaxf(tmax, s[sub][i]);
+            }
+    }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
     float m_new = fmaxf(st.m, tmax);
@@ -204,7 +241,6 @@ __device__ inline void process_tile(WaveState& st, const QOps& Q, const uint8_t*
         st.zl *= alpha;
         st.m = m_new;
     }
-    uint32_t pop[4];
     {
         float p[2][4];
 #pragma unroll
@@ -222,38 +258,123 @@ __device__ inline void process_tile(WaveState& st, const QOps& Q, const uint8_t*
                 pop[v] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p[0][v], p[1][v]));
         }
     }
-    const half8 pb = as_half8(pop[0], pop[1], pop[2], pop[3]);
+}
 
-    // ---- V: out^T += V^T p^T
-    {
-        const uint8_t* vcode = code + 512u * B;
-        uint32_t vw[NDW];
-        load_string<NDW>(vcode, lane, vw);
-        const uint32_t ones = (n == 4) ? 0x3c003c00u : 0u;  // row 4 of the extra MFMA sums p (denominator)
-        if constexpr (B == 16) {
-            st.zl = mfma(as_half8(ones, ones, ones, ones), pb, st.zl);
+// V half of a tile: out^T += V^T p^T with the probabilities `pop` compute_k produced for the same tile.
+template <int B>
+__device__ inline void compute_v(WaveState& st, const uint32_t (&vw)[2 * B], const uint8_t* meta_lds,
+                                 const uint32_t (&pop)[4], int lane) {
+    const int j = lane >> 4, n = lane & 15;
+    const half8 pb = as_half8(pop[0], pop[1], pop[2], pop[3]);
+    const uint32_t ones = (n == 4) ? 0x3c003c00u : 0u;  // row 4 of the extra MFMA sums p (denominator)
+    if constexpr (B == 16) {
+        st.zl = mfma(as_half8(ones, ones, ones, ones), pb, st.zl);
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt) {
-                half8 a = as_half8(vw[4 * nt], vw[4 * nt + 1], vw[4 * nt + 2], vw[4 * nt + 3]);
-                st.o[nt] = mfma(a, pb, st.o[nt]);
-            }
-        } else {
-            // rows 0..3 of the extra MFMA: zero points of V group n over the 8 tokens of this quarter
-            u32x4 zv = *reinterpret_cast<const u32x4*>(meta + 768 + (n & 3) * 64 + j * 16);
-            if (n >= 4) { zv.x = ones; zv.y = ones; zv.z = ones; zv.w = ones; }
-            st.zl = mfma(as_half8(zv.x, zv.y, zv.z, zv.w), pb, st.zl);
+        for (int nt = 0; nt < 8; ++nt) {
+            half8 a = as_half8(vw[4 * nt], vw[4 * nt + 1], vw[4 * nt + 2], vw[4 * nt + 3]);
+            st.o[nt] = mfma(a, pb, st.o[nt]);
+        }
+    } else {
+        // rows 0..3 of the extra MFMA: zero points of V group n over the 8 tokens of this quarter
+        u32x4 zv = *reinterpret_cast<const u32x4*>(meta_lds + 768 + (n & 3) * 64 + j * 16);
+        if (n >= 4) { zv.x = ones; zv.y = ones; zv.z = ones; zv.w = ones; }
+        st.zl = mfma(as_half8(zv.x, zv.y, zv.z, zv.w), pb, st.zl);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                u32x4 sv = *reinterpret_cast<const u32x4*>(meta + 512 + g * 64 + j * 16);
-                half8 pg = as_half8(pk_mul(pop[0], sv.x), pk_mul(pop[1], sv.y), pk_mul(pop[2], sv.z),
-                                    pk_mul(pop[3], sv.w));
+        for (int g = 0; g < 4; ++g) {
+            u32x4 sv = *reinterpret_cast<const u32x4*>(meta_lds + 512 + g * 64 + j * 16);
+            half8 pg = as_half8(pk_mul(pop[0], sv.x), pk_mul(pop[1], sv.y), pk_mul(pop[2], sv.z),
+                                pk_mul(pop[3], sv.w));
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    int nt = 2 * g + h;
-                    st.o[nt] = mfma(dq_piece<B>(vw, nt), pg, st.o[nt]);
-                }
+            for (int h = 0; h < 2; ++h) {
+                int nt = 2 * g + h;
+                st.o[nt] = mfma(dq_piece<B>(vw, nt), pg, st.o[nt]);
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+template <int B>
+__device__ inline void compute_tile(WaveState& st, const QOps& Q, const Stage<B>& sg, uint8_t* meta_lds, int tok0,
+                                    int n_tokens, float scale_log2, int lane) {
+    uint32_t pop[4];
+    compute_k<B>(st, Q, sg.kw, sg.meta, meta_lds, tok0, n_tokens, scale_log2, lane, pop);
+    compute_v<B>(st, sg.vw, meta_lds, pop, lane);
+}
+
+struct RunCtx {
+    const uint8_t* arena;
+    const u32x4* desc_lds;   // descriptors of pages page0 .. of the current chunk
+    int page0;
+    int tpp;
+    int unit;
+    int n_tokens;
+    float scale_log2;
+};
+
+template <int B>
+__device__ inline void tile_addr(const RunCtx& c, int tile, const uint8_t** code, const uint8_t** meta) {
+    const int page = tile / c.tpp, tip = tile - page * c.tpp;
+    const u32x4 d = c.desc_lds[page - c.page0];
+    const uint32_t code_off = __builtin_amdgcn_readfirstlane(d.x);
+    const uint32_t meta_off = __builtin_amdgcn_readfirstlane(d.y);
+    const uint64_t tslot = (uint64_t)c.unit * c.tpp + tip;
+    *code = c.arena + (uint64_t)code_off * 256u + tslot * 2 * (512u * B);
+    *meta = c.arena + (uint64_t)meta_off * 256u + tslot * KVQ_META_TILE_BYTES;
+}
+
+// This wavefront's tiles first, first+4, ... < end, all of width B, software-pipelined: the loads of the next
+// tile are in flight while the current one is computed (two register stages, ping-pong).
+template <int B>
+__device__ inline void run_tiles(WaveState& st, const QOps& Q, const RunCtx& c, int first, int end,
+                                 uint8_t* meta_lds, int lane) {
+    if (first >= end) return;
+    if constexpr (B == 16) {
+        // raw fp16 tiles are 16 KiB: one register stage, K and V staggered (V loads fly during the K product,
+        // the next tile's K loads during the V product)
+        uint32_t kw[32], vw[32];
+        const u32x4 nometa = {0u, 0u, 0u, 0u};
+        const uint8_t *code, *meta;
+        tile_addr<16>(c, first, &code, &meta);
+        load_string<32>(code, lane, kw);
+        load_string<32>(code + 512u * 16, lane, vw);
+        for (int t = first; t < end; t += 4) {
+            uint32_t pop[4];
+            compute_k<16>(st, Q, kw, nometa, meta_lds, t * KVQ_TILE_TOKENS, c.n_tokens, c.scale_log2, lane, pop);
+            const bool more = t + 4 < end;
+            if (more) {
+                tile_addr<16>(c, t + 4, &code, &meta);
+                load_string<32>(code, lane, kw);
+            }
+            compute_v<16>(st, vw, meta_lds, pop, lane);
+            if (more) load_string<32>(code + 512u * 16, lane, vw);
+        }
+        return;
+    }
+    Stage<B> s0, s1;
+    const uint8_t *code, *meta;
+    tile_addr<B>(c, first, &code, &meta);
+    issue_tile<B>(s0, code, meta, lane);
+    int t = first;
+    for (;;) {
+        const int t1 = t + 4;
+        const bool has1 = t1 < end;
+        if (has1) {
+            tile_addr<B>(c, t1, &code, &meta);
+            issue_tile<B>(s1, code, meta, lane);
+        }
+        compute_tile<B>(st, Q, s0, meta_lds, t * KVQ_TILE_TOKENS, c.n_tokens, c.scale_log2, lane);
+        if (!has1) break;
+        const int t2 = t1 + 4;
+        const bool has2 = t2 < end;
+        if (has2) {
+            tile_addr<B>(c, t2, &code, &meta);
+            issue_tile<B>(s0, code, meta, lane);
+        }
+        compute_tile<B>(st, Q, s1, meta_lds, t1 * KVQ_TILE_TOKENS, c.n_tokens, c.scale_log2, lane);
+        if (!has2) break;
+        t = t2;
     }
 }
 
@@ -281,15 +402,18 @@ __device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, i
     }
 }
 
+#define KVQ_DESC_CACHE 256  // page descriptors staged in LDS per chunk of the split's range
 #define KVQ_OPAD 132  // padded row of the LDS reduction slab (floats)
 
-__global__ __launch_bounds__(256) void kvq_attention_kernel(const KvqAttnParams P) {
+__global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnParams P) {
     __shared__ _Float16 q_lds[16 * KVQ_D];
     __shared__ float qsum_lds[16 * 4];
     __shared__ float red_o[4][16 * KVQ_OPAD];
     __shared__ float red_m[4][16];
     __shared__ float red_l[4][16];
     __shared__ int is_last;
+    __shared__ u32x4 desc_lds[KVQ_DESC_CACHE];
+    __shared__ __attribute__((aligned(16))) uint8_t meta_lds[4 * KVQ_META_TILE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane >> 4, n = lane & 15;
@@ -337,21 +461,35 @@ __global__ __launch_bounds__(256) void kvq_attention_kernel(const KvqAttnParams 
 
     const int tpp = P.tiles_per_page;
     const int t_begin = P.split_begin[split], t_end = P.split_begin[split + 1];
-    for (int tile = t_begin + wave; tile < t_end; tile += 4) {
-        const int page = tile / tpp, tip = tile - page * tpp;
-        const KvqPageDesc pd = P.table[page];
-        const int bits = __builtin_amdgcn_readfirstlane(pd.bits);
-        const uint64_t tslot = (uint64_t)unit * tpp + tip;
-        const uint8_t* code = P.arena + (uint64_t)pd.code_off256 * 256u + tslot * 2 * (512u * bits);
-        const uint8_t* meta = P.arena + (uint64_t)pd.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
-        const int natural = (bits == 16);
-        if (Q.natural != natural) load_q_ops(Q, q_lds, lane, natural);
-        const int tok0 = tile * KVQ_TILE_TOKENS;
-        switch (bits) {
-            case 16: process_tile<16>(st, Q, code, meta, tok0, P.n_tokens, P.scale_log2, lane); break;
-            case 8: process_tile<8>(st, Q, code, meta, tok0, P.n_tokens, P.scale_log2, lane); break;
-            case 4: process_tile<4>(st, Q, code, meta, tok0, P.n_tokens, P.scale_log2, lane); break;
-            default: process_tile<2>(st, Q, code, meta, tok0, P.n_tokens, P.scale_log2, lane); break;
+    RunCtx ctx;
+    ctx.arena = P.arena; ctx.desc_lds = desc_lds; ctx.tpp = tpp; ctx.unit = unit;
+    ctx.n_tokens = P.n_tokens; ctx.scale_log2 = P.scale_log2;
+    uint8_t* my_meta = meta_lds + wave * KVQ_META_TILE_BYTES;
+    const int p_first = t_begin / tpp, p_last = (t_end + tpp - 1) / tpp;  // pages touched: [p_first, p_last)
+    for (int pc = p_first; pc < p_last; pc += KVQ_DESC_CACHE) {
+        const int pn = min(KVQ_DESC_CACHE, p_last - pc);
+        __syncthreads();
+        for (int e = tid; e < pn; e += 256) desc_lds[e] = reinterpret_cast<const u32x4*>(P.table)[pc + e];
+        __syncthreads();
+        ctx.page0 = pc;
+        const int lo = max(t_begin, pc * tpp), hi = min(t_end, (pc + pn) * tpp);
+        // first tile of this wavefront in [lo, hi): tiles are dealt round-robin from t_begin
+        int t = lo + ((t_begin + wave - lo) % 4 + 4) % 4;
+        while (t < hi) {
+            const int page = t / tpp;
+            const int bits = __builtin_amdgcn_readfirstlane(desc_lds[page - pc].z);
+            int pe = page + 1;
+            while (pe < pc + pn && __builtin_amdgcn_readfirstlane(desc_lds[pe - pc].z) == bits) ++pe;
+            const int rend = min(pe * tpp, hi);
+            const int natural = (bits == 16);
+            if (Q.natural != natural) load_q_ops(Q, q_lds, lane, natural);
+            switch (bits) {
+                case 16: run_tiles<16>(st, Q, ctx, t, rend, my_meta, lane); break;
+                case 8: run_tiles<8>(st, Q, ctx, t, rend, my_meta, lane); break;
+                case 4: run_tiles<4>(st, Q, ctx, t, rend, my_meta, lane); break;
+                default: run_tiles<2>(st, Q, ctx, t, rend, my_meta, lane); break;
+            }
+            t += ((rend - t + 3) / 4) * 4;
         }
     }
 
