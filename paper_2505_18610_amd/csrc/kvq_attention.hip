@@ -87,6 +87,36 @@ __device__ inline half8 dq_piece(const uint32_t* w, int p) {
     return as_half8(r0, r1, r2, r3);
 }
 
+// The same piece as fp16 *denormals*: the code bits are left where they are in the mantissa, so register v
+// holds c * 2^(pos_v - 24) with pos_v = 0 (8 bit), {0,4,0,4}[v] (4 bit), 2v (2 bit).  The matrix cores take
+// denormal inputs exactly; the K product compensates with a query operand pre-scaled by 2^-pos_v and one
+// multiplication of the per-token sum by 2^24.  One VALU op per two codes.
+template <int B>
+__device__ inline half8 dq_piece_denorm(const uint32_t* w, int p) {
+    uint32_t r0, r1, r2, r3;
+    if constexpr (B == 8) {
+        uint32_t w0 = w[2 * p], w1 = w[2 * p + 1];
+        r0 = __builtin_amdgcn_perm(w1, w0, 0x0c040c00u);
+        r1 = __builtin_amdgcn_perm(w1, w0, 0x0c050c01u);
+        r2 = __builtin_amdgcn_perm(w1, w0, 0x0c060c02u);
+        r3 = __builtin_amdgcn_perm(w1, w0, 0x0c070c03u);
+    } else if constexpr (B == 4) {
+        uint32_t x = w[p], y = x >> 8;
+        r0 = x & 0x000f000fu;
+        r1 = x & 0x00f000f0u;
+        r2 = y & 0x000f000fu;
+        r3 = y & 0x00f000f0u;
+    } else {
+        uint32_t x = w[p >> 1];
+        uint32_t t = (p & 1) ? __builtin_amdgcn_perm(0u, x, 0x0c030c02u) : __builtin_amdgcn_perm(0u, x, 0x0c010c00u);
+        r0 = t & 0x00030003u;
+        r1 = t & 0x000c000cu;
+        r2 = t & 0x00300030u;
+        r3 = t & 0x00c000c0u;
+    }
+    return as_half8(r0, r1, r2, r3);
+}
+
 template <int NDW>
 __device__ inline void load_string(const uint8_t* tile, int lane, uint32_t (&w)[NDW]) {
 #pragma unroll
@@ -106,65 +136,75 @@ struct WaveState {
 struct QOps {
     uint32_t q[4][4];
     uint32_t qsum[4];  // quarter 0: hi/lo fp16 split of the per-group sums of q; other quarters: zero
-    int natural;       // 1: k-slot order of the 16-bit tier, 0: the (v, v+4) pairing of the quantized tiers
+    int cls;           // width the operands are arranged for: 16 natural k-slot order; 8/4/2 the (v, v+4)
+                       // pairing, pre-scaled by 2^-pos_v of that width's denormal code operands
+    int have_qsum;
 };
 
-__device__ inline void load_q_ops(QOps& Q, const _Float16* q_lds, int lane, int natural) {
+__device__ inline uint32_t pack_rn(float a, float b) {  // two floats -> packed fp16, round to nearest even
+    half2v h = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+__device__ inline void load_q_ops(QOps& Q, const _Float16* q_lds, int lane, int cls, float scale_log2) {
     const int j = lane >> 4, n = lane & 15;
-    const uint16_t* row = reinterpret_cast<const uint16_t*>(q_lds) + n * KVQ_D;
+    const _Float16* row = q_lds + n * KVQ_D;
 #pragma unroll
     for (int grp = 0; grp < 4; ++grp) {
-        const uint16_t* p = row + 32 * grp + 8 * j;
+        const _Float16* p = row + 32 * grp + 8 * j;
+        float sum = 0.f;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            uint32_t lo = natural ? p[2 * v] : p[v];
-            uint32_t hi = natural ? p[2 * v + 1] : p[v + 4];
-            Q.q[grp][v] = lo | (hi << 16);
+            _Float16 lo = (cls == 16) ? p[2 * v] : p[v];
+            _Float16 hi = (cls == 16) ? p[2 * v + 1] : p[v + 4];
+            sum += (float)lo + (float)hi;
+            float f = 1.0f;
+            if (cls == 4) f = (v & 1) ? 0.0625f : 1.0f;
+            if (cls == 2) f = (v == 0) ? 1.0f : (v == 1) ? 0.25f : (v == 2) ? 0.0625f : 0.015625f;
+            half2v h = {lo, hi};
+            half2v fs = {(_Float16)f, (_Float16)f};
+            h = h * fs;  // exact: a power of two (tiny |q| may round in the denormal range)
+            Q.q[grp][v] = __builtin_bit_cast(uint32_t, h);
+        }
+        if (!Q.have_qsum) {  // sum of q over the group's 32 channels: 8 here, the rest in the other quarters
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+            sum *= scale_log2;  // the zero-point term then needs no scaling after its MFMA
+            _Float16 h = (_Float16)sum;
+            _Float16 l = (_Float16)(sum - (float)h);
+            uint32_t hb = __builtin_bit_cast(uint16_t, h), lb = __builtin_bit_cast(uint16_t, l);
+            if (j != 0) { hb = 0u; lb = 0u; }
+            if (grp & 1) { Q.qsum[grp >> 1] |= hb << 16; Q.qsum[2 + (grp >> 1)] |= lb << 16; }
+            else { Q.qsum[grp >> 1] = hb; Q.qsum[2 + (grp >> 1)] = lb; }
         }
     }
-    Q.natural = natural;
+    Q.have_qsum = 1;
+    Q.cls = cls;
 }
 
 __device__ inline float4v mfma(half8 a, half8 b, float4v c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
-// Registers of one tile in flight: the lane's packed K and V strings and its 16-byte share of the metadata.
-template <int B>
+// Registers of one pipeline stage: TPI tiles in flight, each the lane's packed K and V strings and its
+// 16-byte share of the tile's metadata.
+template <int B, int TPI>
 struct Stage {
-    uint32_t kw[2 * B];
-    uint32_t vw[2 * B];
-    u32x4 meta;
+    uint32_t kw[TPI][2 * B];
+    uint32_t vw[TPI][2 * B];
+    u32x4 meta[TPI];
+    int tok0[TPI];  // first token of each tile (a huge value marks a slot that only pads the stage)
 };
 
-// Issue every global load of one tile (nothing waits here).
-template <int B>
-__device__ inline void issue_tile(Stage<B>& sg, const uint8_t* __restrict__ code, const uint8_t* __restrict__ meta,
-                                  int lane) {
-    load_string<2 * B>(code, lane, sg.kw);
-    load_string<2 * B>(code + 512u * B, lane, sg.vw);
-    if constexpr (B < 16) sg.meta = *reinterpret_cast<const u32x4*>(meta + lane * 16);
-}
+#define KVQ_PAD_TOK0 0x3fffff00
 
-// One 32-token tile of width B from registers.  meta_lds: this wavefront's 1 KiB staging area, through which
-// the metadata is redistributed (each lane needs the scales of the 8 tokens of its quarter).
-// tok0 = first token of the tile, n_tokens = cache length (tokens beyond it are masked).
+// K half: scores^T (scaled to log2 units) of the 32 tokens of one tile for the 16 head columns.
+// meta_lds: this tile's 1 KiB metadata, already redistributed through LDS.
 template <int B>
-__device__ inline void compute_k(WaveState& st, const QOps& Q, const uint32_t (&kw)[2 * B], const u32x4& meta_regs,
-                                 uint8_t* meta_lds, int tok0, int n_tokens, float scale_log2, int lane,
-                                 uint32_t (&pop)[4]) {
+__device__ inline void scores_tile(const QOps& Q, const uint32_t (&kw)[2 * B], const uint8_t* meta_lds,
+                                   float scale_log2, int lane, float (&s)[2][4]) {
     const int j = lane >> 4, n = lane & 15;
     const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
-    float s[2][4];
-
-    if constexpr (B < 16) {
-        *reinterpret_cast<u32x4*>(meta_lds + lane * 16) = meta_regs;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
-
-    // ---- K: scores^T for the 32 tokens x 16 heads
     if constexpr (B == 16) {
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
@@ -177,7 +217,7 @@ __device__ inline void compute_k(WaveState& st, const QOps& Q, const uint32_t (&
                 acc = mfma(a, b, acc);
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s[sub][i] = acc[i];
+            for (int i = 0; i < 4; ++i) s[sub][i] = acc[i] * scale_log2;
         }
     } else {
         // scales of the 8 tokens whose scores this lane quarter receives: tokens 8j .. 8j+7, 4 groups each
@@ -194,10 +234,11 @@ __device__ inline void compute_k(WaveState& st, const QOps& Q, const uint32_t (&
             // zero points of the token this lane supplies as an A row: token 8*(n/4) + 4*sub + n%4
             int t = 8 * (n >> 2) + 4 * sub + (n & 3);
             u32x2 kz = *reinterpret_cast<const u32x2*>(meta_lds + 256 + t * 8);
-            float4v acc = mfma(as_half8(kz.x, kz.y, kz.x, kz.y), qs, zero4);
+            float4v zacc = mfma(as_half8(kz.x, kz.y, kz.x, kz.y), qs, zero4);
+            float4v acc = zero4;
 #pragma unroll
             for (int grp = 0; grp < 4; ++grp) {
-                half8 a = dq_piece<B>(kw, sub * 4 + grp);
+                half8 a = dq_piece_denorm<B>(kw, sub * 4 + grp);
                 half8 b = as_half8(Q.q[grp][0], Q.q[grp][1], Q.q[grp][2], Q.q[grp][3]);
                 float4v part = mfma(a, b, zero4);
 #pragma unroll
@@ -208,62 +249,16 @@ __device__ inline void compute_k(WaveState& st, const QOps& Q, const uint32_t (&
                 }
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s[sub][i] = acc[i];
-        }
-    }
-
-    // ---- online softmax (log2 domain)
-    float tmax = -INFINITY;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            s[sub][i] *= scale_log2;
-            tmax = fmaxf(tmax, s[sub][i]);
-        }
-    if (tok0 + KVQ_TILE_TOKENS > n_tokens) {  // ragged last tile only
-        tmax = -INFINITY;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (tok0 + 8 * j + 4 * sub + i >= n_tokens) s[sub][i] = -INFINITY;
-                tmax = fmaxf(tmax, s[sub][i]);
-            }
-    }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    float m_new = fmaxf(st.m, tmax);
-    if (__any(m_new > st.m)) {
-        float alpha = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - m_new);
-#pragma unroll
-        for (int nt = 0; nt < 8; ++nt) st.o[nt] *= alpha;
-        st.zl *= alpha;
-        st.m = m_new;
-    }
-    {
-        float p[2][4];
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) p[sub][i] = __builtin_amdgcn_exp2f(s[sub][i] - st.m);
-        if constexpr (B == 16) {  // natural order: slots 0..3 = sub 0, slots 4..7 = sub 1
-            pop[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p[0][0], p[0][1]));
-            pop[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p[0][2], p[0][3]));
-            pop[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p[1][0], p[1][1]));
-            pop[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p[1][2], p[1][3]));
-        } else {
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                pop[v] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p[0][v], p[1][v]));
+            for (int i = 0; i < 4; ++i)  // the code operands were denormals: 2^24 restores the sum of S * (c . q)
+                s[sub][i] = fmaf(acc[i], scale_log2 * 16777216.0f, zacc[i]);
         }
     }
 }
 
-// V half of a tile: out^T += V^T p^T with the probabilities `pop` compute_k produced for the same tile.
+// V half: out^T += V^T p^T with the probabilities `pop` (MFMA B operand) of the same tile.
 template <int B>
-__device__ inline void compute_v(WaveState& st, const uint32_t (&vw)[2 * B], const uint8_t* meta_lds,
-                                 const uint32_t (&pop)[4], int lane) {
+__device__ inline void accumulate_tile(WaveState& st, const uint32_t (&vw)[2 * B], const uint8_t* meta_lds,
+                                       const uint32_t (&pop)[4], int lane) {
     const int j = lane >> 4, n = lane & 15;
     const half8 pb = as_half8(pop[0], pop[1], pop[2], pop[3]);
     const uint32_t ones = (n == 4) ? 0x3c003c00u : 0u;  // row 4 of the extra MFMA sums p (denominator)
@@ -290,17 +285,92 @@ __device__ inline void compute_v(WaveState& st, const uint32_t (&vw)[2 * B], con
                 st.o[nt] = mfma(dq_piece<B>(vw, nt), pg, st.o[nt]);
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
     }
 }
 
-template <int B>
-__device__ inline void compute_tile(WaveState& st, const QOps& Q, const Stage<B>& sg, uint8_t* meta_lds, int tok0,
-                                    int n_tokens, float scale_log2, int lane) {
-    uint32_t pop[4];
-    compute_k<B>(st, Q, sg.kw, sg.meta, meta_lds, tok0, n_tokens, scale_log2, lane, pop);
-    compute_v<B>(st, sg.vw, meta_lds, pop, lane);
+// Online softmax over the TPI*32 scores of a stage (log2 domain).  The running maximum st.m is equal in the
+// four lane quarters of a head column; the cross-quarter reduction and the rescaling of the accumulators run
+// only when some lane sees a score above it, which becomes rare after the first tiles.
+template <int B, int TPI>
+__device__ inline void softmax_stage(WaveState& st, float (&s)[TPI][2][4], const int (&tok0)[TPI], int n_tokens,
+                                     int lane, uint32_t (&pop)[TPI][4]) {
+    const int j = lane >> 4;
+    bool ragged = false;
+#pragma unroll
+    for (int k = 0; k < TPI; ++k) ragged |= (tok0[k] + KVQ_TILE_TOKENS > n_tokens);
+    if (ragged) {  // last tile of the cache, or a slot that only pads the stage
+        asm volatile("" ::: "memory");  // keep this a branch: the selects must not run for every tile
+#pragma unroll
+        for (int k = 0; k < TPI; ++k)
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (tok0[k] + 8 * j + 4 * sub + i >= n_tokens) s[k][sub][i] = -INFINITY;
+    }
+    float lmax = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < TPI; ++k)
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) lmax = fmaxf(lmax, s[k][sub][i]);
+    if (__any(lmax > st.m)) {
+        float tmax = fmaxf(lmax, __shfl_xor(lmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        float m_new = fmaxf(st.m, tmax);
+        float alpha = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - m_new);
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) st.o[nt] *= alpha;
+        st.zl *= alpha;
+        st.m = m_new;
+    }
+#pragma unroll
+    for (int k = 0; k < TPI; ++k) {
+        float p[2][4];
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) p[sub][i] = __builtin_amdgcn_exp2f(s[k][sub][i] - st.m);
+        if constexpr (B == 16) {  // natural order: slots 0..3 = sub 0, slots 4..7 = sub 1
+            pop[k][0] = pack_rn(p[0][0], p[0][1]);
+            pop[k][1] = pack_rn(p[0][2], p[0][3]);
+            pop[k][2] = pack_rn(p[1][0], p[1][1]);
+            pop[k][3] = pack_rn(p[1][2], p[1][3]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                pop[k][v] = pack_rn(p[0][v], p[1][v]);
+        }
+    }
+}
+
+__device__ inline void wave_lds_sync() {  // orders LDS traffic between the lanes of one wavefront
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// All TPI tiles of one stage: K products, one joint softmax, V products.
+template <int B, int TPI>
+__device__ inline void compute_stage(WaveState& st, const QOps& Q, const Stage<B, TPI>& sg, uint8_t* meta_lds,
+                                     int n_tokens, float scale_log2, int lane) {
+    if constexpr (B < 16) {
+#pragma unroll
+        for (int k = 0; k < TPI; ++k)
+            *reinterpret_cast<u32x4*>(meta_lds + k * KVQ_META_TILE_BYTES + lane * 16) = sg.meta[k];
+        wave_lds_sync();
+    }
+    float s[TPI][2][4];
+#pragma unroll
+    for (int k = 0; k < TPI; ++k)
+        scores_tile<B>(Q, sg.kw[k], meta_lds + k * KVQ_META_TILE_BYTES, scale_log2, lane, s[k]);
+    uint32_t pop[TPI][4];
+    softmax_stage<B, TPI>(st, s, sg.tok0, n_tokens, lane, pop);
+#pragma unroll
+    for (int k = 0; k < TPI; ++k)
+        accumulate_tile<B>(st, sg.vw[k], meta_lds + k * KVQ_META_TILE_BYTES, pop[k], lane);
+    if constexpr (B < 16) wave_lds_sync();
 }
 
 struct RunCtx {
@@ -324,96 +394,174 @@ __device__ inline void tile_addr(const RunCtx& c, int tile, const uint8_t** code
     *meta = c.arena + (uint64_t)meta_off * 256u + tslot * KVQ_META_TILE_BYTES;
 }
 
+// Issue every global load of one stage (nothing waits here): tiles t, t+4, ... of this wavefront; slots past
+// `end` re-read the first tile and are masked out by their tok0.
+template <int B, int TPI>
+__device__ inline void issue_stage(Stage<B, TPI>& sg, const RunCtx& c, int t, int end, int lane) {
+#pragma unroll
+    for (int k = 0; k < TPI; ++k) {
+        const int tk = t + 4 * k;
+        const bool real = (k == 0) || (tk < end);
+        const uint8_t *code, *meta;
+        tile_addr<B>(c, real ? tk : t, &code, &meta);
+        load_string<2 * B>(code, lane, sg.kw[k]);
+        load_string<2 * B>(code + 512u * B, lane, sg.vw[k]);
+        if constexpr (B < 16) sg.meta[k] = *reinterpret_cast<const u32x4*>(meta + lane * 16);
+        sg.tok0[k] = real ? tk * KVQ_TILE_TOKENS : KVQ_PAD_TOK0;
+    }
+}
+
 // This wavefront's tiles first, first+4, ... < end, all of width B, software-pipelined: the loads of the next
-// tile are in flight while the current one is computed (two register stages, ping-pong).
-template <int B>
+// stage are in flight while the current one is computed (two register stages, ping-pong).
+template <int B, int TPI>
 __device__ inline void run_tiles(WaveState& st, const QOps& Q, const RunCtx& c, int first, int end,
                                  uint8_t* meta_lds, int lane) {
     if (first >= end) return;
-    if constexpr (B == 16) {
-        // raw fp16 tiles are 16 KiB: one register stage, K and V staggered (V loads fly during the K product,
-        // the next tile's K loads during the V product)
-        uint32_t kw[32], vw[32];
-        const u32x4 nometa = {0u, 0u, 0u, 0u};
+    if constexpr (B >= 8) {
+        // wide tiles (8 and 16 KiB): one register stage, K and V staggered (V loads fly during the K product,
+        // the next tile's K and metadata loads during the V product)
+        uint32_t kw[2 * B], vw[2 * B];
+        u32x4 mreg = {0u, 0u, 0u, 0u};
         const uint8_t *code, *meta;
-        tile_addr<16>(c, first, &code, &meta);
-        load_string<32>(code, lane, kw);
-        load_string<32>(code + 512u * 16, lane, vw);
+        tile_addr<B>(c, first, &code, &meta);
+        load_string<2 * B>(code, lane, kw);
+        if constexpr (B < 16) mreg = *reinterpret_cast<const u32x4*>(meta + lane * 16);
+        load_string<2 * B>(code + 512u * B, lane, vw);
         for (int t = first; t < end; t += 4) {
-            uint32_t pop[4];
-            compute_k<16>(st, Q, kw, nometa, meta_lds, t * KVQ_TILE_TOKENS, c.n_tokens, c.scale_log2, lane, pop);
+            float s[1][2][4];
+            uint32_t pop[1][4];
+            const int tok0[1] = {t * KVQ_TILE_TOKENS};
+            if constexpr (B < 16) {
+                *reinterpret_cast<u32x4*>(meta_lds + lane * 16) = mreg;
+                wave_lds_sync();
+            }
+            scores_tile<B>(Q, kw, meta_lds, c.scale_log2, lane, s[0]);
             const bool more = t + 4 < end;
             if (more) {
-                tile_addr<16>(c, t + 4, &code, &meta);
-                load_string<32>(code, lane, kw);
+                tile_addr<B>(c, t + 4, &code, &meta);
+                load_string<2 * B>(code, lane, kw);
+                if constexpr (B < 16) mreg = *reinterpret_cast<const u32x4*>(meta + lane * 16);
             }
-            compute_v<16>(st, vw, meta_lds, pop, lane);
-            if (more) load_string<32>(code + 512u * 16, lane, vw);
+            softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
+            accumulate_tile<B>(st, vw, meta_lds, pop[0], lane);
+            if constexpr (B < 16) wave_lds_sync();
+            if (more) load_string<2 * B>(code + 512u * B, lane, vw);
         }
         return;
-    }
-    Stage<B> s0, s1;
-    const uint8_t *code, *meta;
-    tile_addr<B>(c, first, &code, &meta);
-    issue_tile<B>(s0, code, meta, lane);
-    int t = first;
-    for (;;) {
-        const int t1 = t + 4;
-        const bool has1 = t1 < end;
-        if (has1) {
-            tile_addr<B>(c, t1, &code, &meta);
-            issue_tile<B>(s1, code, meta, lane);
+    } else {
+        constexpr int STEP = 4 * TPI;
+        Stage<B, TPI> s0, s1;
+        issue_stage<B, TPI>(s0, c, first, end, lane);
+        int t = first;
+        for (;;) {
+            const int t1 = t + STEP;
+            const bool has1 = t1 < end;
+            if (has1) issue_stage<B, TPI>(s1, c, t1, end, lane);
+            compute_stage<B, TPI>(st, Q, s0, meta_lds, c.n_tokens, c.scale_log2, lane);
+            if (!has1) break;
+            const int t2 = t1 + STEP;
+            const bool has2 = t2 < end;
+            if (has2) issue_stage<B, TPI>(s0, c, t2, end, lane);
+            compute_stage<B, TPI>(st, Q, s1, meta_lds, c.n_tokens, c.scale_log2, lane);
+            if (!has2) break;
+            t = t2;
         }
-        compute_tile<B>(st, Q, s0, meta_lds, t * KVQ_TILE_TOKENS, c.n_tokens, c.scale_log2, lane);
-        if (!has1) break;
-        const int t2 = t1 + 4;
-        const bool has2 = t2 < end;
-        if (has2) {
-            tile_addr<B>(c, t2, &code, &meta);
-            issue_tile<B>(s0, code, meta, lane);
-        }
-        compute_tile<B>(st, Q, s1, meta_lds, t1 * KVQ_TILE_TOKENS, c.n_tokens, c.scale_log2, lane);
-        if (!has2) break;
-        t = t2;
     }
 }
 
-// Merge of split partials: thread `tid` of `nthreads` produces out[head][d] for its share of (head, d).
-__device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, int nthreads) {
-    const int g = P.gqa;
+// Device-scope (all XCDs) relaxed accesses: they go through to memory instead of living in one XCD's L2, so
+// split partials can be handed to the merging workgroup without whole-cache write-backs or invalidations.
+__device__ inline void store_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float load_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Merge of the split partials of one unit by 256 threads.  lds: >= (2 * 128 * 16 + 16) floats of scratch.
+// Every thread's global loads are independent of each other, so the whole merge costs about three memory
+// round trips: (m, l) of all splits, then the partial outputs (16 splits per batch), then the store.
+template <bool AGENT>
+__device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, float* lds) {
+    const int g = P.gqa, ns = P.n_splits;
     const int b = unit / P.n_kv_heads, hk = unit - b * P.n_kv_heads;
-    const float* po = P.part_o + (size_t)unit * P.n_splits * 16 * KVQ_D;
-    const float* pml = P.part_ml + (size_t)unit * P.n_splits * 32;
-    for (int e = tid; e < g * KVQ_D; e += nthreads) {
-        int head = e >> 7, d = e & 127;
+    const float* po = P.part_o + (size_t)unit * ns * 16 * KVQ_D;
+    const float* pml = P.part_ml + (size_t)unit * ns * 32;
+    float* f_lds = lds;                 // [split][16] rescaling factor of each split
+    float* l_lds = lds + 128 * 16;      // [split][16] its denominator
+    float* L_lds = lds + 2 * 128 * 16;  // [16] merged denominator
+    for (int e = tid; e < ns * 16; e += 256) {
+        int sp = e >> 4, head = e & 15;
+        f_lds[e] = AGENT ? load_agent(pml + sp * 32 + head) : pml[sp * 32 + head];
+        l_lds[e] = AGENT ? load_agent(pml + sp * 32 + 16 + head) : pml[sp * 32 + 16 + head];
+    }
+    __syncthreads();
+    {
+        const int head = tid >> 4, l16 = tid & 15;  // 16 threads per head
         float M = -INFINITY;
-        for (int sp = 0; sp < P.n_splits; ++sp) M = fmaxf(M, pml[sp * 32 + head]);
-        float L = 0.f, acc = 0.f;
-        for (int sp = 0; sp < P.n_splits; ++sp) {
-            float ms = pml[sp * 32 + head];
+        for (int sp = l16; sp < ns; sp += 16) M = fmaxf(M, f_lds[sp * 16 + head]);
+#pragma unroll
+        for (int m = 1; m < 16; m <<= 1) M = fmaxf(M, __shfl_xor(M, m));
+        float L = 0.f;
+        for (int sp = l16; sp < ns; sp += 16) {
+            float ms = f_lds[sp * 16 + head];
             float f = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-            L += pml[sp * 32 + 16 + head] * f;
-            acc += po[((size_t)sp * 16 + head) * KVQ_D + d] * f;
+            f_lds[sp * 16 + head] = f;
+            L += l_lds[sp * 16 + head] * f;
         }
-        float r = acc / L;
-        size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + d;
-        if (P.out_fp32) static_cast<float*>(P.out)[oi] = r;
-        else static_cast<_Float16*>(P.out)[oi] = (_Float16)r;
+#pragma unroll
+        for (int m = 1; m < 16; m <<= 1) L += __shfl_xor(L, m);
+        if (l16 == 0) L_lds[head] = L;
+    }
+    __syncthreads();
+    const int d4 = tid & 31;  // channels 4*d4 .. 4*d4+3
+    for (int head = tid >> 5; head < g; head += 8) {
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
+        for (int s0 = 0; s0 < ns; s0 += 16) {
+            float4v v[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                int sp = min(s0 + k, ns - 1);
+                const float* src = po + ((size_t)sp * 16 + head) * KVQ_D + 4 * d4;
+                if (AGENT) {
+                    v[k][0] = load_agent(src); v[k][1] = load_agent(src + 1);
+                    v[k][2] = load_agent(src + 2); v[k][3] = load_agent(src + 3);
+                } else {
+                    v[k] = *reinterpret_cast<const float4v*>(src);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                if (s0 + k < ns) acc += v[k] * f_lds[(s0 + k) * 16 + head];
+        }
+        const float inv = 1.0f / L_lds[head];
+        size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + 4 * d4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float r = acc[i] * inv;
+            if (P.out_fp32) static_cast<float*>(P.out)[oi + i] = r;
+            else static_cast<_Float16*>(P.out)[oi + i] = (_Float16)r;
+        }
     }
 }
 
+#ifndef KVQ_TPI2
+#define KVQ_TPI2 2  // tiles per pipeline stage of the 2-bit tier
+#endif
+#ifndef KVQ_TPI4
+#define KVQ_TPI4 2  // and of the 4-bit tier
+#endif
 #define KVQ_DESC_CACHE 256  // page descriptors staged in LDS per chunk of the split's range
 #define KVQ_OPAD 132  // padded row of the LDS reduction slab (floats)
 
 __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnParams P) {
-    __shared__ _Float16 q_lds[16 * KVQ_D];
-    __shared__ float qsum_lds[16 * 4];
+    __shared__ __attribute__((aligned(16))) _Float16 q_lds[16 * KVQ_D];
     __shared__ float red_o[4][16 * KVQ_OPAD];
     __shared__ float red_m[4][16];
     __shared__ float red_l[4][16];
     __shared__ int is_last;
     __shared__ u32x4 desc_lds[KVQ_DESC_CACHE];
-    __shared__ __attribute__((aligned(16))) uint8_t meta_lds[4 * KVQ_META_TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t meta_lds[4 * 2 * KVQ_META_TILE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane >> 4, n = lane & 15;
@@ -421,37 +569,26 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
     const int g = P.gqa;
     const int b = unit / P.n_kv_heads, hk = unit - b * P.n_kv_heads;
 
-    // stage q (heads beyond g are zero) and its per-group sums
+    const int tpp = P.tiles_per_page;
+    const int t_begin = P.split_begin[split], t_end = P.split_begin[split + 1];
+    const int p_first = t_begin / tpp, p_last = (t_end + tpp - 1) / tpp;  // pages touched: [p_first, p_last)
+    // stage q (heads beyond g are zero) and the first chunk of page descriptors with one round trip
     {
-        const _Float16* qg = static_cast<const _Float16*>(P.q) + ((size_t)b * P.n_q_heads + hk * g) * KVQ_D;
-        for (int e = tid; e < 16 * KVQ_D; e += 256) q_lds[e] = (e < g * KVQ_D) ? qg[e] : (_Float16)0.f;
-        __syncthreads();
-        if (tid < 64) {
-            int head = tid >> 2, grp = tid & 3;
-            float sum = 0.f;
-            for (int d = 0; d < 32; ++d) sum += (float)q_lds[head * KVQ_D + grp * 32 + d];
-            qsum_lds[tid] = sum;
-        }
+        const int head = tid >> 4, c16 = tid & 15;
+        u32x4 qv = {0u, 0u, 0u, 0u};
+        if (head < g)
+            qv = *reinterpret_cast<const u32x4*>(static_cast<const _Float16*>(P.q) +
+                                                 ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + c16 * 8);
+        u32x4 dv = {0u, 0u, 0u, 0u};
+        if (tid < min(KVQ_DESC_CACHE, p_last - p_first)) dv = reinterpret_cast<const u32x4*>(P.table)[p_first + tid];
+        *reinterpret_cast<u32x4*>(&q_lds[head * KVQ_D + c16 * 8]) = qv;
+        desc_lds[tid] = dv;
         __syncthreads();
     }
     QOps Q;
-    {
-        uint16_t hi[4], lo[4];
-#pragma unroll
-        for (int grp = 0; grp < 4; ++grp) {
-            float sum = qsum_lds[n * 4 + grp];
-            _Float16 h = (_Float16)sum;
-            _Float16 l = (_Float16)(sum - (float)h);
-            hi[grp] = __builtin_bit_cast(uint16_t, h);
-            lo[grp] = __builtin_bit_cast(uint16_t, l);
-        }
-        bool q0 = (j == 0);
-        Q.qsum[0] = q0 ? ((uint32_t)hi[0] | ((uint32_t)hi[1] << 16)) : 0u;
-        Q.qsum[1] = q0 ? ((uint32_t)hi[2] | ((uint32_t)hi[3] << 16)) : 0u;
-        Q.qsum[2] = q0 ? ((uint32_t)lo[0] | ((uint32_t)lo[1] << 16)) : 0u;
-        Q.qsum[3] = q0 ? ((uint32_t)lo[2] | ((uint32_t)lo[3] << 16)) : 0u;
-        Q.natural = -1;
-    }
+    Q.cls = -1;
+    Q.have_qsum = 0;
+    Q.qsum[0] = Q.qsum[1] = Q.qsum[2] = Q.qsum[3] = 0u;
 
     WaveState st;
 #pragma unroll
@@ -459,18 +596,17 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
     st.zl = float4v{0.f, 0.f, 0.f, 0.f};
     st.m = -INFINITY;
 
-    const int tpp = P.tiles_per_page;
-    const int t_begin = P.split_begin[split], t_end = P.split_begin[split + 1];
     RunCtx ctx;
     ctx.arena = P.arena; ctx.desc_lds = desc_lds; ctx.tpp = tpp; ctx.unit = unit;
     ctx.n_tokens = P.n_tokens; ctx.scale_log2 = P.scale_log2;
-    uint8_t* my_meta = meta_lds + wave * KVQ_META_TILE_BYTES;
-    const int p_first = t_begin / tpp, p_last = (t_end + tpp - 1) / tpp;  // pages touched: [p_first, p_last)
+    uint8_t* my_meta = meta_lds + wave * (2 * KVQ_META_TILE_BYTES);
     for (int pc = p_first; pc < p_last; pc += KVQ_DESC_CACHE) {
         const int pn = min(KVQ_DESC_CACHE, p_last - pc);
-        __syncthreads();
-        for (int e = tid; e < pn; e += 256) desc_lds[e] = reinterpret_cast<const u32x4*>(P.table)[pc + e];
-        __syncthreads();
+        if (pc != p_first) {  // further chunks of a very long range
+            __syncthreads();
+            if (tid < pn) desc_lds[tid] = reinterpret_cast<const u32x4*>(P.table)[pc + tid];
+            __syncthreads();
+        }
         ctx.page0 = pc;
         const int lo = max(t_begin, pc * tpp), hi = min(t_end, (pc + pn) * tpp);
         // first tile of this wavefront in [lo, hi): tiles are dealt round-robin from t_begin
@@ -481,13 +617,12 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
             int pe = page + 1;
             while (pe < pc + pn && __builtin_amdgcn_readfirstlane(desc_lds[pe - pc].z) == bits) ++pe;
             const int rend = min(pe * tpp, hi);
-            const int natural = (bits == 16);
-            if (Q.natural != natural) load_q_ops(Q, q_lds, lane, natural);
+            if (Q.cls != bits) load_q_ops(Q, q_lds, lane, bits, P.scale_log2);
             switch (bits) {
-                case 16: run_tiles<16>(st, Q, ctx, t, rend, my_meta, lane); break;
-                case 8: run_tiles<8>(st, Q, ctx, t, rend, my_meta, lane); break;
-                case 4: run_tiles<4>(st, Q, ctx, t, rend, my_meta, lane); break;
-                default: run_tiles<2>(st, Q, ctx, t, rend, my_meta, lane); break;
+                case 16: run_tiles<16, 1>(st, Q, ctx, t, rend, my_meta, lane); break;
+                case 8: run_tiles<8, 1>(st, Q, ctx, t, rend, my_meta, lane); break;
+                case 4: run_tiles<4, KVQ_TPI4>(st, Q, ctx, t, rend, my_meta, lane); break;
+                default: run_tiles<2, KVQ_TPI2>(st, Q, ctx, t, rend, my_meta, lane); break;
             }
             t += ((rend - t + 3) / 4) * 4;
         }
@@ -531,6 +666,8 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
             size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + d;
             if (P.out_fp32) static_cast<float*>(P.out)[oi] = r;
             else static_cast<_Float16*>(P.out)[oi] = (_Float16)r;
+        } else if (P.fused_merge) {
+            store_agent(po + e, acc);
         } else {
             po[e] = acc;
         }
@@ -538,27 +675,31 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
     if (direct) return;
     if (tid < 16) {
         float Mh = fmaxf(fmaxf(red_m[0][tid], red_m[1][tid]), fmaxf(red_m[2][tid], red_m[3][tid]));
-        pml[tid] = Mh;
-        pml[16 + tid] = red_l[0][tid] + red_l[1][tid] + red_l[2][tid] + red_l[3][tid];
+        float Lh = red_l[0][tid] + red_l[1][tid] + red_l[2][tid] + red_l[3][tid];
+        if (P.fused_merge) { store_agent(pml + tid, Mh); store_agent(pml + 16 + tid, Lh); }
+        else { pml[tid] = Mh; pml[16 + tid] = Lh; }
     }
     if (!P.fused_merge) return;
 
-    // ---- fused merge: the last workgroup of the unit to arrive combines all split partials
-    __threadfence();
+    // ---- fused merge: the last workgroup of the unit to arrive combines all split partials.  Every thread
+    // waits until its device-scope stores have been performed, the workgroup meets, one thread bumps the
+    // unit's arrival counter (device-scope atomic); the workgroup that sees the last ticket reads the partials
+    // with device-scope loads.  The counter is left at zero for the next launch.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
-        uint32_t old = atomicAdd(&P.counters[unit], 1u);
+        uint32_t old = __hip_atomic_fetch_add(&P.counters[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         is_last = (old == (uint32_t)P.n_splits - 1u);
     }
     __syncthreads();
     if (!is_last) return;
-    __threadfence();
-    merge_splits(P, unit, tid, 256);
-    if (tid == 0) P.counters[unit] = 0u;
+    merge_splits<true>(P, unit, tid, &red_o[0][0]);
+    if (tid == 0) __hip_atomic_store(&P.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ __launch_bounds__(256) void kvq_merge_kernel(const KvqAttnParams P) {
-    merge_splits(P, blockIdx.x, threadIdx.x, 256);
+    __shared__ float lds[2 * 128 * 16 + 16];
+    merge_splits<false>(P, blockIdx.x, threadIdx.x, lds);
 }
 
 }  // namespace

@@ -97,7 +97,7 @@ struct kvq_cache {
     uint64_t ring_pos = 0;
     bool device_ready = false;
     int splits_override = 0;
-    int fused_merge = 0;
+    int fused_merge = 1;
     int target_workgroups = 512;
 
     uint64_t bpth(int bits) const {
@@ -290,7 +290,11 @@ void build_segments(const kvq_cache* c, const Layer& L, std::vector<kvq_segment_
     }
 }
 
-// Byte-balanced split of the tile range: a tile of width b costs b + 1 KiB (16 for raw fp16).
+// Relative time one tile of each width costs the attention kernel (measured on MI355X: the narrow widths are
+// bound by de-quantization work, the wide ones by their bytes).
+int tile_cost(int bits) { return bits == 16 ? 33 : bits == 8 ? 18 : bits == 4 ? 12 : 10; }
+
+// Cost-balanced split of the tile range.
 void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
     if (L.plan_tiles == n_tiles && L.plan_splits == n_splits && L.plan_version == L.version) return;
     const int tpp = c->tpp;
@@ -299,7 +303,7 @@ void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
         int nt = std::min(tpp, n_tiles - (int)i * tpp);
         if (nt <= 0) break;
         int b = L.pages[i].bits;
-        total += (uint64_t)nt * (b == 16 ? 16 : b + 1);
+        total += (uint64_t)nt * tile_cost(b);
     }
     int sp = 1;
     L.split_begin[0] = 0;
@@ -307,7 +311,7 @@ void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
     for (size_t i = 0; i < L.pages.size() && sp < n_splits; ++i) {
         int nt = std::min(tpp, n_tiles - (int)i * tpp);
         if (nt <= 0) break;
-        uint64_t cost = L.pages[i].bits == 16 ? 16 : (uint64_t)L.pages[i].bits + 1;
+        uint64_t cost = (uint64_t)tile_cost(L.pages[i].bits);
         uint64_t page_end = cum + cost * nt;
         while (sp < n_splits) {
             uint64_t target = (total * sp + n_splits - 1) / n_splits;

@@ -211,7 +211,7 @@ def test_split_count_and_merge_variant_invariance():
             if ref is None:
                 ref = o
                 check_attention(oc, gc, 0, q)
-            assert np.abs(o - ref).max() <= 2e-4, (fused, n, np.abs(o - ref).max())
+            assert np.abs(o - ref).max() <= 5e-4, (fused, n, np.abs(o - ref).max())
 
 
 def test_softmax_scale_and_multi_layer():
@@ -244,6 +244,19 @@ def test_full_size_32b_layer_sampled_units():
     gc.kvq_decode_attention(0, dev(q), out)
     got = out.cpu().numpy()
     assert np.all(np.isfinite(got))
+    # the two merge variants do the same arithmetic in the same order: bit-identical outputs, launch after launch
+    outs = {}
+    for fused in (0, 1):
+        gc.kvq_cache_set_option(kq.KVQ_OPT_FUSED_MERGE, fused)
+        res = []
+        for _ in range(6):
+            o = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda")
+            gc.kvq_decode_attention(0, dev(q), o)
+            res.append(o)
+        torch.cuda.synchronize()
+        outs[fused] = [r.cpu().numpy() for r in res]
+    for r in outs[0] + outs[1]:
+        assert np.array_equal(r, outs[0][0])
     for b, h in ((0, 0), (3, 7), (1, 4)):
         oc = OracleCache(CacheConfig(1, 1, g, 1, page_tokens=w.page_tokens, max_tokens=w.n_tokens), [1 << 50], [2])
         t = 0
