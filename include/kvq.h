@@ -144,8 +144,11 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* cache, int32_t layer, int32_t
  *   KVQ_OPT_SPLITS: number of token-range splits kvq_decode_attention uses per (sequence, KV head),
  *                   1..128; 0 restores the automatic choice.
  *   KVQ_OPT_FUSED_MERGE: 1 = the last workgroup of a (sequence, KV head) merges the split partials inside
- *                   the attention kernel; 0 = a second small kernel does. */
-enum { KVQ_OPT_SPLITS = 0, KVQ_OPT_FUSED_MERGE = 1 };
+ *                   the attention kernel; 0 = a second small kernel does.
+ *   KVQ_OPT_DETERMINISTIC: 1 = tiles are dealt to wavefronts in a fixed order, so repeated calls on the same
+ *                   cache give bit-identical outputs; 0 (default) = wavefronts claim tiles dynamically, which
+ *                   is faster and changes only the floating-point summation order from call to call. */
+enum { KVQ_OPT_SPLITS = 0, KVQ_OPT_FUSED_MERGE = 1, KVQ_OPT_DETERMINISTIC = 2 };
 kvq_status_t kvq_cache_set_option(kvq_cache_t* cache, int32_t option, int32_t value);
 
 /* Free bytes left in the arena's page area (host bookkeeping). */

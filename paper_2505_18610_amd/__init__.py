@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     kvq_arena_bytes, kvq_bytes_per_token_head, kvq_status_string,
     KVQ_OK, KVQ_E_INVALID, KVQ_E_BUDGET, KVQ_E_OOM, KVQ_E_STATE, KVQ_E_HIP,
     KVQ_POLICY_PAPER, KVQ_POLICY_OLDEST_FIRST, KVQ_WHICH_K, KVQ_WHICH_V,
-    KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE,
+    KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE, KVQ_OPT_DETERMINISTIC,
 )

@@ -9,7 +9,7 @@ import numpy as np
 KVQ_OK, KVQ_E_INVALID, KVQ_E_BUDGET, KVQ_E_OOM, KVQ_E_STATE, KVQ_E_HIP = range(6)
 KVQ_POLICY_PAPER, KVQ_POLICY_OLDEST_FIRST = 0, 1
 KVQ_WHICH_K, KVQ_WHICH_V = 0, 1
-KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE = 0, 1
+KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE, KVQ_OPT_DETERMINISTIC = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None

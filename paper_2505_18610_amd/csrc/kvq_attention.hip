@@ -1,8 +1,8 @@
 // Fused de-quantize + single-token GQA decode attention over the mixed-width paged cache (gfx950).
 //
-// One workgroup (4 wavefronts) handles one (sequence, KV head) unit and one byte-balanced range of 32-token
-// tiles; each wavefront streams every fourth tile of the range with 16-byte loads and keeps its own
-// online-softmax state.  Both contractions run on the matrix cores with the g <= 16 query heads of the unit
+// One workgroup (8 wavefronts, one per compute unit) handles one (sequence, KV head) unit and one cost-balanced
+// range of 32-token tiles; its wavefronts claim two-tile chunks of the range from a counter in LDS, stream
+// them with 16-byte loads and keep their own online-softmax state.  Both contractions run on the matrix cores with the g <= 16 query heads of the unit
 // as the 16-wide N dimension:
 //   scores^T[token, head] = sum_grp S[token,grp] * (codes[token, grp-channels] . q[head, grp-channels])
 //                           + sum_grp Z[token,grp] * sum(q[head, grp-channels])
@@ -17,6 +17,7 @@
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -135,7 +136,8 @@ struct WaveState {
 // query operands of one lane: [grp][4 dwords]
 struct QOps {
     uint32_t q[4][4];
-    uint32_t qsum[4];  // quarter 0: hi/lo fp16 split of the per-group sums of q; other quarters: zero
+    uint32_t qsum[2];  // per-group sums of q (times the softmax scale), fp16 hi parts in lane quarter 0, lo parts in
+                       // quarter 1, zero elsewhere: B operand of the K=16 MFMA that adds the zero-point term
     int cls;           // width the operands are arranged for: 16 natural k-slot order; 8/4/2 the (v, v+4)
                        // pairing, pre-scaled by 2^-pos_v of that width's denormal code operands
     int have_qsum;
@@ -173,9 +175,9 @@ __device__ inline void load_q_ops(QOps& Q, const _Float16* q_lds, int lane, int 
             _Float16 h = (_Float16)sum;
             _Float16 l = (_Float16)(sum - (float)h);
             uint32_t hb = __builtin_bit_cast(uint16_t, h), lb = __builtin_bit_cast(uint16_t, l);
-            if (j != 0) { hb = 0u; lb = 0u; }
-            if (grp & 1) { Q.qsum[grp >> 1] |= hb << 16; Q.qsum[2 + (grp >> 1)] |= lb << 16; }
-            else { Q.qsum[grp >> 1] = hb; Q.qsum[2 + (grp >> 1)] = lb; }
+            uint32_t mine = (j == 0) ? hb : (j == 1) ? lb : 0u;
+            if (grp & 1) Q.qsum[grp >> 1] |= mine << 16;
+            else Q.qsum[grp >> 1] = mine;
         }
     }
     Q.have_qsum = 1;
@@ -196,7 +198,11 @@ struct Stage {
     int tok0[TPI];  // first token of each tile (a huge value marks a slot that only pads the stage)
 };
 
+#define KVQ_ATTN_THREADS 512
+#define KVQ_ATTN_WAVES 8
 #define KVQ_PAD_TOK0 0x3fffff00
+#define KVQ_WAVE_LDS_CONST (2 * KVQ_META_TILE_BYTES)  // 16 bytes of fp16 ones, then 16 bytes of zeros
+#define KVQ_WAVE_LDS_BYTES (2 * KVQ_META_TILE_BYTES + 32)
 
 // K half: scores^T (scaled to log2 units) of the 32 tokens of one tile for the 16 head columns.
 // meta_lds: this tile's 1 KiB metadata, already redistributed through LDS.
@@ -228,13 +234,14 @@ __device__ inline void scores_tile(const QOps& Q, const uint32_t (&kw)[2 * B], c
             u32x4 v = ksp[c];
             ks[4 * c] = v.x; ks[4 * c + 1] = v.y; ks[4 * c + 2] = v.z; ks[4 * c + 3] = v.w;
         }
-        half8 qs = as_half8(Q.qsum[0], Q.qsum[1], Q.qsum[2], Q.qsum[3]);
+        const u32x2 qs2 = {Q.qsum[0], Q.qsum[1]};
+        const half4 qs = __builtin_bit_cast(half4, qs2);
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             // zero points of the token this lane supplies as an A row: token 8*(n/4) + 4*sub + n%4
             int t = 8 * (n >> 2) + 4 * sub + (n & 3);
             u32x2 kz = *reinterpret_cast<const u32x2*>(meta_lds + 256 + t * 8);
-            float4v zacc = mfma(as_half8(kz.x, kz.y, kz.x, kz.y), qs, zero4);
+            float4v zacc = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4, kz), qs, zero4, 0, 0, 0);
             float4v acc = zero4;
 #pragma unroll
             for (int grp = 0; grp < 4; ++grp) {
@@ -258,7 +265,7 @@ __device__ inline void scores_tile(const QOps& Q, const uint32_t (&kw)[2 * B], c
 // V half: out^T += V^T p^T with the probabilities `pop` (MFMA B operand) of the same tile.
 template <int B>
 __device__ inline void accumulate_tile(WaveState& st, const uint32_t (&vw)[2 * B], const uint8_t* meta_lds,
-                                       const uint32_t (&pop)[4], int lane) {
+                                       const uint8_t* const_lds, const uint32_t (&pop)[4], int lane) {
     const int j = lane >> 4, n = lane & 15;
     const half8 pb = as_half8(pop[0], pop[1], pop[2], pop[3]);
     const uint32_t ones = (n == 4) ? 0x3c003c00u : 0u;  // row 4 of the extra MFMA sums p (denominator)
@@ -270,9 +277,10 @@ __device__ inline void accumulate_tile(WaveState& st, const uint32_t (&vw)[2 * B
             st.o[nt] = mfma(a, pb, st.o[nt]);
         }
     } else {
-        // rows 0..3 of the extra MFMA: zero points of V group n over the 8 tokens of this quarter
-        u32x4 zv = *reinterpret_cast<const u32x4*>(meta_lds + 768 + (n & 3) * 64 + j * 16);
-        if (n >= 4) { zv.x = ones; zv.y = ones; zv.z = ones; zv.w = ones; }
+        // rows 0..3 of the extra MFMA: zero points of V group n over the 8 tokens of this quarter; row 4: ones;
+        // other rows: zeros (both constants sit behind the wavefront's metadata area)
+        const uint8_t* zsrc = (n < 4) ? meta_lds + 768 + n * 64 + j * 16 : const_lds + (n == 4 ? 0 : 16);
+        u32x4 zv = *reinterpret_cast<const u32x4*>(zsrc);
         st.zl = mfma(as_half8(zv.x, zv.y, zv.z, zv.w), pb, st.zl);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -369,22 +377,47 @@ __device__ inline void compute_stage(WaveState& st, const QOps& Q, const Stage<B
     softmax_stage<B, TPI>(st, s, sg.tok0, n_tokens, lane, pop);
 #pragma unroll
     for (int k = 0; k < TPI; ++k)
-        accumulate_tile<B>(st, sg.vw[k], meta_lds + k * KVQ_META_TILE_BYTES, pop[k], lane);
+        accumulate_tile<B>(st, sg.vw[k], meta_lds + k * KVQ_META_TILE_BYTES, meta_lds + KVQ_WAVE_LDS_CONST, pop[k], lane);
     if constexpr (B < 16) wave_lds_sync();
 }
 
+// What a wavefront needs to find and claim work inside its workgroup's tile range.  The range is cut into
+// chunks of tpc consecutive tiles (2, or 1 when pages hold an odd number of tiles); the 8 wavefronts of the
+// workgroup claim chunks from a counter in LDS, so wavefronts that get more issue slots simply do more chunks.
 struct RunCtx {
     const uint8_t* arena;
-    const u32x4* desc_lds;   // descriptors of pages page0 .. of the current chunk
+    const u32x4* desc_lds;   // descriptors of pages page0 .. of the current descriptor window
+    unsigned* claim_ctr;     // LDS: next unclaimed chunk
     int page0;
     int tpp;
     int unit;
     int n_tokens;
+    int lo, hi;              // tile range of the current descriptor window
+    int tpc;                 // tiles per chunk
+    int n_chunks;
+    int next_static;         // >= 0: deterministic mode, this wavefront takes chunks next_static, +8, +16, ...
     float scale_log2;
 };
 
+__device__ inline int claim_chunk(RunCtx& c) {
+    if (c.next_static >= 0) {
+        const int v = c.next_static;
+        c.next_static += KVQ_ATTN_WAVES;
+        return v;
+    }
+    unsigned v = 0;
+    if ((threadIdx.x & 63) == 0) v = __hip_atomic_fetch_add(c.claim_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return (int)__builtin_amdgcn_readfirstlane(v);
+}
+__device__ inline int chunk_tile(const RunCtx& c, int chunk) { return c.lo + chunk * c.tpc; }
+__device__ inline int chunk_size(const RunCtx& c, int chunk) { return min(c.tpc, c.hi - chunk_tile(c, chunk)); }
+__device__ inline int chunk_bits(const RunCtx& c, int chunk) {
+    return __builtin_amdgcn_readfirstlane(c.desc_lds[chunk_tile(c, chunk) / c.tpp - c.page0].z);
+}
+
 template <int B>
 __device__ inline void tile_addr(const RunCtx& c, int tile, const uint8_t** code, const uint8_t** meta) {
+    tile = __builtin_amdgcn_readfirstlane(tile);  // one tile per wavefront: keep its address in scalar registers
     const int page = tile / c.tpp, tip = tile - page * c.tpp;
     const u32x4 d = c.desc_lds[page - c.page0];
     const uint32_t code_off = __builtin_amdgcn_readfirstlane(d.x);
@@ -394,40 +427,41 @@ __device__ inline void tile_addr(const RunCtx& c, int tile, const uint8_t** code
     *meta = c.arena + (uint64_t)meta_off * 256u + tslot * KVQ_META_TILE_BYTES;
 }
 
-// Issue every global load of one stage (nothing waits here): tiles t, t+4, ... of this wavefront; slots past
-// `end` re-read the first tile and are masked out by their tok0.
+// Issue every global load of one stage (nothing waits here): the tiles of one chunk; slots the chunk does not
+// fill re-read its first tile and are masked out by their tok0.
 template <int B, int TPI>
-__device__ inline void issue_stage(Stage<B, TPI>& sg, const RunCtx& c, int t, int end, int lane) {
+__device__ inline void issue_stage(Stage<B, TPI>& sg, const RunCtx& c, int chunk, int lane) {
+    const int t = chunk_tile(c, chunk), nt = chunk_size(c, chunk);
 #pragma unroll
     for (int k = 0; k < TPI; ++k) {
-        const int tk = t + 4 * k;
-        const bool real = (k == 0) || (tk < end);
+        const bool real = k < nt;
         const uint8_t *code, *meta;
-        tile_addr<B>(c, real ? tk : t, &code, &meta);
+        tile_addr<B>(c, real ? t + k : t, &code, &meta);
         load_string<2 * B>(code, lane, sg.kw[k]);
         load_string<2 * B>(code + 512u * B, lane, sg.vw[k]);
         if constexpr (B < 16) sg.meta[k] = *reinterpret_cast<const u32x4*>(meta + lane * 16);
-        sg.tok0[k] = real ? tk * KVQ_TILE_TOKENS : KVQ_PAD_TOK0;
+        sg.tok0[k] = real ? (t + k) * KVQ_TILE_TOKENS : KVQ_PAD_TOK0;
     }
 }
 
-// This wavefront's tiles first, first+4, ... < end, all of width B, software-pipelined: the loads of the next
-// stage are in flight while the current one is computed (two register stages, ping-pong).
+// Process chunk `chunk` (already claimed, width B) and keep claiming and processing chunks while they have the
+// same width, software-pipelined: the loads of the next chunk are in flight while the current one is computed.
+// Returns the first claimed chunk that was not processed (another width, or past the end of the range).
 template <int B, int TPI>
-__device__ inline void run_tiles(WaveState& st, const QOps& Q, const RunCtx& c, int first, int end,
-                                 uint8_t* meta_lds, int lane) {
-    if (first >= end) return;
+__device__ inline int run_chunks(WaveState& st, const QOps& Q, RunCtx& c, int chunk, uint8_t* meta_lds,
+                                 int lane) {
     if constexpr (B >= 8) {
-        // wide tiles (8 and 16 KiB): one register stage, K and V staggered (V loads fly during the K product,
-        // the next tile's K and metadata loads during the V product)
+        // wide tiles (8 and 16 KiB): one register stage, tile by tile, K and V staggered (V loads fly during
+        // the K product, the next tile's K and metadata loads during the V product)
         uint32_t kw[2 * B], vw[2 * B];
         u32x4 mreg = {0u, 0u, 0u, 0u};
         const uint8_t *code, *meta;
-        tile_addr<B>(c, first, &code, &meta);
+        int t = chunk_tile(c, chunk), k = 0, cur = chunk;
+        tile_addr<B>(c, t, &code, &meta);
         load_string<2 * B>(code, lane, kw);
         if constexpr (B < 16) mreg = *reinterpret_cast<const u32x4*>(meta + lane * 16);
         load_string<2 * B>(code + 512u * B, lane, vw);
-        for (int t = first; t < end; t += 4) {
+        for (;;) {
             float s[1][2][4];
             uint32_t pop[1][4];
             const int tok0[1] = {t * KVQ_TILE_TOKENS};
@@ -436,35 +470,39 @@ __device__ inline void run_tiles(WaveState& st, const QOps& Q, const RunCtx& c, 
                 wave_lds_sync();
             }
             scores_tile<B>(Q, kw, meta_lds, c.scale_log2, lane, s[0]);
-            const bool more = t + 4 < end;
-            if (more) {
-                tile_addr<B>(c, t + 4, &code, &meta);
+            int next_t = -1, next_k = 0, next_c = cur, pending = 0;
+            if (k + 1 < chunk_size(c, cur)) {
+                next_t = t + 1; next_k = k + 1;
+            } else {
+                pending = claim_chunk(c);
+                if (pending < c.n_chunks && chunk_bits(c, pending) == B) { next_t = chunk_tile(c, pending); next_c = pending; }
+            }
+            if (next_t >= 0) {
+                tile_addr<B>(c, next_t, &code, &meta);
                 load_string<2 * B>(code, lane, kw);
                 if constexpr (B < 16) mreg = *reinterpret_cast<const u32x4*>(meta + lane * 16);
             }
             softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
-            accumulate_tile<B>(st, vw, meta_lds, pop[0], lane);
+            accumulate_tile<B>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
             if constexpr (B < 16) wave_lds_sync();
-            if (more) load_string<2 * B>(code + 512u * B, lane, vw);
+            if (next_t < 0) return pending;
+            load_string<2 * B>(code + 512u * B, lane, vw);
+            t = next_t; k = next_k; cur = next_c;
         }
-        return;
     } else {
-        constexpr int STEP = 4 * TPI;
         Stage<B, TPI> s0, s1;
-        issue_stage<B, TPI>(s0, c, first, end, lane);
-        int t = first;
+        issue_stage<B, TPI>(s0, c, chunk, lane);
         for (;;) {
-            const int t1 = t + STEP;
-            const bool has1 = t1 < end;
-            if (has1) issue_stage<B, TPI>(s1, c, t1, end, lane);
+            const int c1 = claim_chunk(c);
+            const bool same1 = c1 < c.n_chunks && chunk_bits(c, c1) == B;
+            if (same1) issue_stage<B, TPI>(s1, c, c1, lane);
             compute_stage<B, TPI>(st, Q, s0, meta_lds, c.n_tokens, c.scale_log2, lane);
-            if (!has1) break;
-            const int t2 = t1 + STEP;
-            const bool has2 = t2 < end;
-            if (has2) issue_stage<B, TPI>(s0, c, t2, end, lane);
+            if (!same1) return c1;
+            const int c2 = claim_chunk(c);
+            const bool same2 = c2 < c.n_chunks && chunk_bits(c, c2) == B;
+            if (same2) issue_stage<B, TPI>(s0, c, c2, lane);
             compute_stage<B, TPI>(st, Q, s1, meta_lds, c.n_tokens, c.scale_log2, lane);
-            if (!has2) break;
-            t = t2;
+            if (!same2) return c2;
         }
     }
 }
@@ -482,59 +520,54 @@ __device__ inline float load_agent(const float* p) {
 // Every thread's global loads are independent of each other, so the whole merge costs about three memory
 // round trips: (m, l) of all splits, then the partial outputs (16 splits per batch), then the store.
 template <bool AGENT>
-__device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, float* lds) {
+__device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, int nthreads) {
     const int g = P.gqa, ns = P.n_splits;
     const int b = unit / P.n_kv_heads, hk = unit - b * P.n_kv_heads;
     const float* po = P.part_o + (size_t)unit * ns * 16 * KVQ_D;
     const float* pml = P.part_ml + (size_t)unit * ns * 32;
-    float* f_lds = lds;                 // [split][16] rescaling factor of each split
-    float* l_lds = lds + 128 * 16;      // [split][16] its denominator
-    float* L_lds = lds + 2 * 128 * 16;  // [16] merged denominator
-    for (int e = tid; e < ns * 16; e += 256) {
-        int sp = e >> 4, head = e & 15;
-        f_lds[e] = AGENT ? load_agent(pml + sp * 32 + head) : pml[sp * 32 + head];
-        l_lds[e] = AGENT ? load_agent(pml + sp * 32 + 16 + head) : pml[sp * 32 + 16 + head];
-    }
-    __syncthreads();
-    {
-        const int head = tid >> 4, l16 = tid & 15;  // 16 threads per head
-        float M = -INFINITY;
-        for (int sp = l16; sp < ns; sp += 16) M = fmaxf(M, f_lds[sp * 16 + head]);
-#pragma unroll
-        for (int m = 1; m < 16; m <<= 1) M = fmaxf(M, __shfl_xor(M, m));
-        float L = 0.f;
-        for (int sp = l16; sp < ns; sp += 16) {
-            float ms = f_lds[sp * 16 + head];
-            float f = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-            f_lds[sp * 16 + head] = f;
-            L += l_lds[sp * 16 + head] * f;
-        }
-#pragma unroll
-        for (int m = 1; m < 16; m <<= 1) L += __shfl_xor(L, m);
-        if (l16 == 0) L_lds[head] = L;
-    }
-    __syncthreads();
-    const int d4 = tid & 31;  // channels 4*d4 .. 4*d4+3
-    for (int head = tid >> 5; head < g; head += 8) {
+    // thread -> (head, 4 channels); every load below is independent of every other, so the merge is one memory
+    // round trip: each thread fetches the (m, l) pairs of its head and its slice of every partial output, then
+    // combines them in registers (splits are taken 16 at a time)
+    const int d4 = tid & 31;
+    for (int head = tid >> 5; head < g; head += nthreads >> 5) {
+        float M = -INFINITY, L = 0.f;
         float4v acc = {0.f, 0.f, 0.f, 0.f};
         for (int s0 = 0; s0 < ns; s0 += 16) {
             float4v v[16];
+            float ms[16], ls[16];
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
-                int sp = min(s0 + k, ns - 1);
+                const int sp = min(s0 + k, ns - 1);
                 const float* src = po + ((size_t)sp * 16 + head) * KVQ_D + 4 * d4;
                 if (AGENT) {
+                    ms[k] = load_agent(pml + sp * 32 + head);
+                    ls[k] = load_agent(pml + sp * 32 + 16 + head);
                     v[k][0] = load_agent(src); v[k][1] = load_agent(src + 1);
                     v[k][2] = load_agent(src + 2); v[k][3] = load_agent(src + 3);
                 } else {
+                    ms[k] = pml[sp * 32 + head];
+                    ls[k] = pml[sp * 32 + 16 + head];
                     v[k] = *reinterpret_cast<const float4v*>(src);
                 }
             }
+            float Mb = M;
 #pragma unroll
             for (int k = 0; k < 16; ++k)
-                if (s0 + k < ns) acc += v[k] * f_lds[(s0 + k) * 16 + head];
+                if (s0 + k < ns) Mb = fmaxf(Mb, ms[k]);
+            const float carry = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mb);
+            acc *= carry;
+            L *= carry;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                if (s0 + k < ns) {
+                    const float f = (ms[k] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms[k] - Mb);
+                    L += ls[k] * f;
+                    acc += v[k] * f;
+                }
+            }
+            M = Mb;
         }
-        const float inv = 1.0f / L_lds[head];
+        const float inv = 1.0f / L;
         size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + 4 * d4;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -545,23 +578,26 @@ __device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, f
     }
 }
 
-#ifndef KVQ_TPI2
-#define KVQ_TPI2 2  // tiles per pipeline stage of the 2-bit tier
-#endif
-#ifndef KVQ_TPI4
-#define KVQ_TPI4 2  // and of the 4-bit tier
-#endif
 #define KVQ_DESC_CACHE 256  // page descriptors staged in LDS per chunk of the split's range
+#ifdef KVQ_DEBUG_TIMING
+__device__ unsigned long long kvq_dbg[1024 * 8];
+#define KVQ_STAMP(k) do { if (lane == 0 && wave == 0) kvq_dbg[(blockIdx.y * gridDim.x + blockIdx.x) % 1024 * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define KVQ_STAMP(k) do { } while (0)
+#endif
 #define KVQ_OPAD 132  // padded row of the LDS reduction slab (floats)
 
-__global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnParams P) {
+
+// grid = (splits, units); 512 threads = 8 wavefronts, one workgroup per compute unit.
+__global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const KvqAttnParams P) {
     __shared__ __attribute__((aligned(16))) _Float16 q_lds[16 * KVQ_D];
     __shared__ float red_o[4][16 * KVQ_OPAD];
-    __shared__ float red_m[4][16];
-    __shared__ float red_l[4][16];
+    __shared__ float red_m[KVQ_ATTN_WAVES][16];
+    __shared__ float red_l[KVQ_ATTN_WAVES][16];
     __shared__ int is_last;
+    __shared__ unsigned claim_ctr;
     __shared__ u32x4 desc_lds[KVQ_DESC_CACHE];
-    __shared__ __attribute__((aligned(16))) uint8_t meta_lds[4 * 2 * KVQ_META_TILE_BYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t meta_lds[KVQ_ATTN_WAVES * KVQ_WAVE_LDS_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane >> 4, n = lane & 15;
@@ -569,11 +605,12 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
     const int g = P.gqa;
     const int b = unit / P.n_kv_heads, hk = unit - b * P.n_kv_heads;
 
+    KVQ_STAMP(0);
     const int tpp = P.tiles_per_page;
     const int t_begin = P.split_begin[split], t_end = P.split_begin[split + 1];
     const int p_first = t_begin / tpp, p_last = (t_end + tpp - 1) / tpp;  // pages touched: [p_first, p_last)
-    // stage q (heads beyond g are zero) and the first chunk of page descriptors with one round trip
-    {
+    // stage q (heads beyond g are zero) and the first window of page descriptors with one round trip
+    if (tid < 256) {
         const int head = tid >> 4, c16 = tid & 15;
         u32x4 qv = {0u, 0u, 0u, 0u};
         if (head < g)
@@ -583,12 +620,14 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
         if (tid < min(KVQ_DESC_CACHE, p_last - p_first)) dv = reinterpret_cast<const u32x4*>(P.table)[p_first + tid];
         *reinterpret_cast<u32x4*>(&q_lds[head * KVQ_D + c16 * 8]) = qv;
         desc_lds[tid] = dv;
-        __syncthreads();
     }
+    if (tid == 0) claim_ctr = 0u;
+    __syncthreads();
+    KVQ_STAMP(1);
     QOps Q;
     Q.cls = -1;
     Q.have_qsum = 0;
-    Q.qsum[0] = Q.qsum[1] = Q.qsum[2] = Q.qsum[3] = 0u;
+    Q.qsum[0] = Q.qsum[1] = 0u;
 
     WaveState st;
 #pragma unroll
@@ -597,37 +636,38 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
     st.m = -INFINITY;
 
     RunCtx ctx;
-    ctx.arena = P.arena; ctx.desc_lds = desc_lds; ctx.tpp = tpp; ctx.unit = unit;
+    ctx.arena = P.arena; ctx.desc_lds = desc_lds; ctx.claim_ctr = &claim_ctr; ctx.tpp = tpp; ctx.unit = unit;
     ctx.n_tokens = P.n_tokens; ctx.scale_log2 = P.scale_log2;
-    uint8_t* my_meta = meta_lds + wave * (2 * KVQ_META_TILE_BYTES);
+    ctx.tpc = (tpp & 1) ? 1 : 2;
+    uint8_t* my_meta = meta_lds + wave * KVQ_WAVE_LDS_BYTES;
+    if (lane < 8) reinterpret_cast<uint32_t*>(my_meta + KVQ_WAVE_LDS_CONST)[lane] = lane < 4 ? 0x3c003c00u : 0u;
     for (int pc = p_first; pc < p_last; pc += KVQ_DESC_CACHE) {
         const int pn = min(KVQ_DESC_CACHE, p_last - pc);
-        if (pc != p_first) {  // further chunks of a very long range
+        if (pc != p_first) {  // further descriptor windows of a very long range
             __syncthreads();
             if (tid < pn) desc_lds[tid] = reinterpret_cast<const u32x4*>(P.table)[pc + tid];
+            if (tid == 0) claim_ctr = 0u;
             __syncthreads();
         }
         ctx.page0 = pc;
-        const int lo = max(t_begin, pc * tpp), hi = min(t_end, (pc + pn) * tpp);
-        // first tile of this wavefront in [lo, hi): tiles are dealt round-robin from t_begin
-        int t = lo + ((t_begin + wave - lo) % 4 + 4) % 4;
-        while (t < hi) {
-            const int page = t / tpp;
-            const int bits = __builtin_amdgcn_readfirstlane(desc_lds[page - pc].z);
-            int pe = page + 1;
-            while (pe < pc + pn && __builtin_amdgcn_readfirstlane(desc_lds[pe - pc].z) == bits) ++pe;
-            const int rend = min(pe * tpp, hi);
+        ctx.lo = max(t_begin, pc * tpp);
+        ctx.hi = min(t_end, (pc + pn) * tpp);
+        ctx.n_chunks = (ctx.hi - ctx.lo + ctx.tpc - 1) / ctx.tpc;
+        ctx.next_static = P.deterministic ? wave : -1;
+        int c = claim_chunk(ctx);
+        while (c < ctx.n_chunks) {
+            const int bits = chunk_bits(ctx, c);
             if (Q.cls != bits) load_q_ops(Q, q_lds, lane, bits, P.scale_log2);
             switch (bits) {
-                case 16: run_tiles<16, 1>(st, Q, ctx, t, rend, my_meta, lane); break;
-                case 8: run_tiles<8, 1>(st, Q, ctx, t, rend, my_meta, lane); break;
-                case 4: run_tiles<4, KVQ_TPI4>(st, Q, ctx, t, rend, my_meta, lane); break;
-                default: run_tiles<2, KVQ_TPI2>(st, Q, ctx, t, rend, my_meta, lane); break;
+                case 16: c = run_chunks<16, 1>(st, Q, ctx, c, my_meta, lane); break;
+                case 8: c = run_chunks<8, 1>(st, Q, ctx, c, my_meta, lane); break;
+                case 4: c = run_chunks<4, 2>(st, Q, ctx, c, my_meta, lane); break;
+                default: c = run_chunks<2, 2>(st, Q, ctx, c, my_meta, lane); break;
             }
-            t += ((rend - t + 3) / 4) * 4;
         }
     }
 
+    KVQ_STAMP(2);
     // ---- wavefront epilogue: add the zero-point term, fetch the denominator
     float l_w = __shfl(st.zl[0], 16 + n);
     {
@@ -640,28 +680,43 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
             st.o[6][i] += z3; st.o[7][i] += z3;
         }
     }
-    // ---- merge the four wavefronts through LDS
-    if (j == 0) { red_m[wave][n] = st.m; }
+    // ---- merge the eight wavefronts through LDS: common maximum, then a fixed-order two-level sum
+    if (j == 0) red_m[wave][n] = st.m;
     __syncthreads();
-    float M = fmaxf(fmaxf(red_m[0][n], red_m[1][n]), fmaxf(red_m[2][n], red_m[3][n]));
-    float f = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - M);
+    float M = red_m[0][n];
+#pragma unroll
+    for (int w = 1; w < KVQ_ATTN_WAVES; ++w) M = fmaxf(M, red_m[w][n]);
+    const float f = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - M);
     if (j == 0) red_l[wave][n] = l_w * f;
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) {
-        float4v v = st.o[nt] * f;
-        *reinterpret_cast<float4v*>(&red_o[wave][n * KVQ_OPAD + 16 * nt + 4 * j]) = v;
+    for (int nt = 0; nt < 8; ++nt) st.o[nt] *= f;
+    if (wave >= 4) {
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt)
+            *reinterpret_cast<float4v*>(&red_o[wave - 4][n * KVQ_OPAD + 16 * nt + 4 * j]) = st.o[nt];
+    }
+    __syncthreads();
+    if (wave < 4) {
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) {
+            float4v* slot = reinterpret_cast<float4v*>(&red_o[wave][n * KVQ_OPAD + 16 * nt + 4 * j]);
+            *slot = st.o[nt] + *slot;
+        }
     }
     __syncthreads();
 
+    KVQ_STAMP(3);
     const bool direct = (P.n_splits == 1);
     float* po = P.part_o + ((size_t)unit * P.n_splits + split) * 16 * KVQ_D;
     float* pml = P.part_ml + ((size_t)unit * P.n_splits + split) * 32;
-    for (int e = tid; e < g * KVQ_D; e += 256) {
+    for (int e = tid; e < g * KVQ_D; e += KVQ_ATTN_THREADS) {
         int head = e >> 7, d = e & 127;
         int li = head * KVQ_OPAD + d;
-        float acc = red_o[0][li] + red_o[1][li] + red_o[2][li] + red_o[3][li];
+        float acc = (red_o[0][li] + red_o[1][li]) + (red_o[2][li] + red_o[3][li]);
         if (direct) {
-            float L = red_l[0][head] + red_l[1][head] + red_l[2][head] + red_l[3][head];
+            float L = 0.f;
+#pragma unroll
+            for (int w = 0; w < KVQ_ATTN_WAVES; ++w) L += red_l[w][head];
             float r = acc / L;
             size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + d;
             if (P.out_fp32) static_cast<float*>(P.out)[oi] = r;
@@ -674,8 +729,11 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
     }
     if (direct) return;
     if (tid < 16) {
-        float Mh = fmaxf(fmaxf(red_m[0][tid], red_m[1][tid]), fmaxf(red_m[2][tid], red_m[3][tid]));
-        float Lh = red_l[0][tid] + red_l[1][tid] + red_l[2][tid] + red_l[3][tid];
+        float Mh = red_m[0][tid], Lh = 0.f;
+#pragma unroll
+        for (int w = 1; w < KVQ_ATTN_WAVES; ++w) Mh = fmaxf(Mh, red_m[w][tid]);
+#pragma unroll
+        for (int w = 0; w < KVQ_ATTN_WAVES; ++w) Lh += red_l[w][tid];
         if (P.fused_merge) { store_agent(pml + tid, Mh); store_agent(pml + 16 + tid, Lh); }
         else { pml[tid] = Mh; pml[16 + tid] = Lh; }
     }
@@ -692,20 +750,27 @@ __global__ __launch_bounds__(256, 2) void kvq_attention_kernel(const KvqAttnPara
         is_last = (old == (uint32_t)P.n_splits - 1u);
     }
     __syncthreads();
+    KVQ_STAMP(4);
     if (!is_last) return;
-    merge_splits<true>(P, unit, tid, &red_o[0][0]);
+    merge_splits<true>(P, unit, tid, KVQ_ATTN_THREADS);
     if (tid == 0) __hip_atomic_store(&P.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    KVQ_STAMP(5);
 }
 
 __global__ __launch_bounds__(256) void kvq_merge_kernel(const KvqAttnParams P) {
-    __shared__ float lds[2 * 128 * 16 + 16];
-    merge_splits<false>(P, blockIdx.x, threadIdx.x, lds);
+    merge_splits<false>(P, blockIdx.x, threadIdx.x, 256);
 }
 
 }  // namespace
 
+#ifdef KVQ_DEBUG_TIMING
+extern "C" int kvq_debug_read(unsigned long long* host) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kvq_dbg), sizeof(unsigned long long) * 1024 * 8);
+}
+#endif
+
 hipError_t kvq_launch_attention(const KvqAttnParams& p, int units, hipStream_t s) {
-    hipLaunchKernelGGL(kvq_attention_kernel, dim3(p.n_splits, units), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(kvq_attention_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.n_splits > 1 && !p.fused_merge) {

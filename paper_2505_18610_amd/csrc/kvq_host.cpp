@@ -98,7 +98,8 @@ struct kvq_cache {
     bool device_ready = false;
     int splits_override = 0;
     int fused_merge = 1;
-    int target_workgroups = 512;
+    int deterministic = 0;
+    int target_workgroups = 256;
 
     uint64_t bpth(int bits) const {
         return kvq_bytes_per_token_head(bits, cfg.head_dim, cfg.group, cfg.count_metadata_in_budget);
@@ -292,7 +293,7 @@ void build_segments(const kvq_cache* c, const Layer& L, std::vector<kvq_segment_
 
 // Relative time one tile of each width costs the attention kernel (measured on MI355X: the narrow widths are
 // bound by de-quantization work, the wide ones by their bytes).
-int tile_cost(int bits) { return bits == 16 ? 33 : bits == 8 ? 18 : bits == 4 ? 12 : 10; }
+int tile_cost(int bits) { return bits == 16 ? 37 : bits == 8 ? 20 : bits == 4 ? 13 : 10; }
 
 // Cost-balanced split of the tile range.
 void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
@@ -317,6 +318,7 @@ void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
             uint64_t target = (total * sp + n_splits - 1) / n_splits;
             if (target > page_end) break;
             uint64_t k = target <= cum ? 0 : (target - cum + cost - 1) / cost;
+            if ((tpp & 1) == 0) k = std::min<uint64_t>((k + 1) & ~1ull, (uint64_t)nt);  // chunks are tile pairs
             L.split_begin[sp++] = (int)i * tpp + (int)k;
         }
         cum = page_end;
@@ -387,7 +389,7 @@ kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_bud
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
             prop.multiProcessorCount > 0)
-            c->target_workgroups = 2 * prop.multiProcessorCount;
+            c->target_workgroups = prop.multiProcessorCount;  // one 8-wavefront workgroup per compute unit
     }
     *out = c;
     return KVQ_OK;
@@ -547,7 +549,7 @@ kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_d
     hipStream_t s = as_stream(hip_stream);
     const int n_tiles = (L.T + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
     int n_splits = c->splits_override;
-    if (n_splits <= 0) n_splits = std::min(c->target_workgroups / std::max(1, c->units), (n_tiles + 3) / 4);
+    if (n_splits <= 0) n_splits = std::min(c->target_workgroups / std::max(1, c->units), (n_tiles + 15) / 16);
     n_splits = std::max(1, std::min(n_splits, std::min(KVQ_MAX_SPLITS, n_tiles)));
     plan_splits(c, L, n_tiles, n_splits);
 
@@ -567,6 +569,7 @@ kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_d
     p.n_splits = n_splits;
     p.out_fp32 = out_is_fp32 ? 1 : 0;
     p.fused_merge = c->fused_merge;
+    p.deterministic = c->deterministic;
     const float scale = softmax_scale != 0.f ? softmax_scale : 1.0f / std::sqrt((float)c->cfg.head_dim);
     p.scale_log2 = scale * 1.44269504088896340736f;
     std::memcpy(p.split_begin, L.split_begin, sizeof(int32_t) * (size_t)(n_splits + 1));
@@ -660,6 +663,9 @@ kvq_status_t kvq_cache_set_option(kvq_cache_t* c, int32_t option, int32_t value)
             return KVQ_OK;
         case KVQ_OPT_FUSED_MERGE:
             c->fused_merge = value ? 1 : 0;
+            return KVQ_OK;
+        case KVQ_OPT_DETERMINISTIC:
+            c->deterministic = value ? 1 : 0;
             return KVQ_OK;
         default: return KVQ_E_INVALID;
     }

@@ -29,6 +29,7 @@ struct KvqAttnParams {
     int32_t n_splits;
     int32_t out_fp32;
     int32_t fused_merge;
+    int32_t deterministic;     // 1: static chunk-to-wavefront assignment (bit-reproducible summation order)
     float scale_log2;          // softmax scale * log2(e)
     int32_t split_begin[KVQ_MAX_SPLITS + 1];  // tile index where each split starts
 };

@@ -244,19 +244,25 @@ def test_full_size_32b_layer_sampled_units():
     gc.kvq_decode_attention(0, dev(q), out)
     got = out.cpu().numpy()
     assert np.all(np.isfinite(got))
-    # the two merge variants do the same arithmetic in the same order: bit-identical outputs, launch after launch
-    outs = {}
-    for fused in (0, 1):
-        gc.kvq_cache_set_option(kq.KVQ_OPT_FUSED_MERGE, fused)
-        res = []
-        for _ in range(6):
-            o = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda")
-            gc.kvq_decode_attention(0, dev(q), o)
-            res.append(o)
-        torch.cuda.synchronize()
-        outs[fused] = [r.cpu().numpy() for r in res]
-    for r in outs[0] + outs[1]:
-        assert np.array_equal(r, outs[0][0])
+    # deterministic mode: the two merge variants do the same arithmetic in the same order, so outputs are
+    # bit-identical launch after launch; default mode: only the summation order moves (far below the tolerance)
+    for det in (1, 0):
+        gc.kvq_cache_set_option(kq.KVQ_OPT_DETERMINISTIC, det)
+        outs = []
+        for fused in (0, 1):
+            gc.kvq_cache_set_option(kq.KVQ_OPT_FUSED_MERGE, fused)
+            res = []
+            for _ in range(6):
+                o = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda")
+                gc.kvq_decode_attention(0, dev(q), o)
+                res.append(o)
+            torch.cuda.synchronize()
+            outs += [r.cpu().numpy() for r in res]
+        for r in outs:
+            if det:
+                assert np.array_equal(r, outs[0])
+            else:
+                assert np.abs(r - got).max() <= 5e-4
     for b, h in ((0, 0), (3, 7), (1, 4)):
         oc = OracleCache(CacheConfig(1, 1, g, 1, page_tokens=w.page_tokens, max_tokens=w.n_tokens), [1 << 50], [2])
         t = 0
