@@ -147,9 +147,19 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* cache, int32_t layer, int32_t
  *                   the attention kernel; 0 = a second small kernel does.
  *   KVQ_OPT_DETERMINISTIC: 1 = tiles are dealt to wavefronts in a fixed order, so repeated calls on the same
  *                   cache give bit-identical outputs; 0 (default) = wavefronts claim tiles dynamically, which
- *                   is faster and changes only the floating-point summation order from call to call. */
-enum { KVQ_OPT_SPLITS = 0, KVQ_OPT_FUSED_MERGE = 1, KVQ_OPT_DETERMINISTIC = 2 };
+ *                   is faster and changes only the floating-point summation order from call to call.
+ *   KVQ_OPT_TILE_COST_{2,4,8,16}BIT: relative time one 32-token tile of that width costs the attention kernel
+ *                   (1..1000000); the token range of a (sequence, KV head) is cut into splits of equal cost. */
+enum { KVQ_OPT_SPLITS = 0, KVQ_OPT_FUSED_MERGE = 1, KVQ_OPT_DETERMINISTIC = 2, KVQ_OPT_TILE_COST_2BIT = 3,
+       KVQ_OPT_TILE_COST_4BIT = 4, KVQ_OPT_TILE_COST_8BIT = 5, KVQ_OPT_TILE_COST_16BIT = 6 };
 kvq_status_t kvq_cache_set_option(kvq_cache_t* cache, int32_t option, int32_t value);
+
+/* Measurement aid, not part of the method: enqueues one plain streaming-read kernel (16-byte loads, no
+ * arithmetic) over buf_dev[0, bytes) with n_workgroups workgroups of 256 threads.  Timed by the caller, it gives
+ * the device's practical HBM read ceiling, next to which the attention kernel's bandwidth is reported.
+ * buf_dev: 16-byte aligned device memory the caller owns; nothing is written to it. */
+kvq_status_t kvq_stream_read_probe(kvq_cache_t* cache, const void* buf_dev, uint64_t bytes, int32_t n_workgroups,
+                                   void* hip_stream);
 
 /* Free bytes left in the arena's page area (host bookkeeping). */
 uint64_t kvq_cache_arena_free_bytes(const kvq_cache_t* cache);

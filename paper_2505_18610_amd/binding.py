@@ -10,6 +10,7 @@ KVQ_OK, KVQ_E_INVALID, KVQ_E_BUDGET, KVQ_E_OOM, KVQ_E_STATE, KVQ_E_HIP = range(6
 KVQ_POLICY_PAPER, KVQ_POLICY_OLDEST_FIRST = 0, 1
 KVQ_WHICH_K, KVQ_WHICH_V = 0, 1
 KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE, KVQ_OPT_DETERMINISTIC = 0, 1, 2
+KVQ_OPT_TILE_COST_2BIT, KVQ_OPT_TILE_COST_4BIT, KVQ_OPT_TILE_COST_8BIT, KVQ_OPT_TILE_COST_16BIT = 3, 4, 5, 6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -55,6 +56,7 @@ _SIGNATURES = {
                                            C.c_void_p, C.c_void_p]),
     "kvq_cache_set_option": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "kvq_cache_arena_free_bytes": (C.c_uint64, [C.c_void_p]),
+    "kvq_stream_read_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p]),
     "kvq_status_string": (C.c_char_p, [C.c_int]),
 }
 
@@ -191,6 +193,10 @@ class KvqCache:
 
     def kvq_cache_set_option(self, option, value):
         self._check(self.lib.kvq_cache_set_option(self.handle, option, value), "kvq_cache_set_option")
+
+    def kvq_stream_read_probe(self, buf, n_workgroups, stream=None):
+        self._check(self.lib.kvq_stream_read_probe(self.handle, _ptr(buf), buf.numel() * buf.element_size(), n_workgroups,
+                                                   _stream(stream)), "kvq_stream_read_probe")
 
     def kvq_cache_arena_free_bytes(self) -> int:
         return int(self.lib.kvq_cache_arena_free_bytes(self.handle))

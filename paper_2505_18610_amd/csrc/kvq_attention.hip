@@ -326,6 +326,7 @@ __device__ inline void softmax_stage(WaveState& st, float (&s)[TPI][2][4], const
     if (__any(lmax > st.m)) {
         float tmax = fmaxf(lmax, __shfl_xor(lmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        // the exact maximum is the reference point: the dominant token then has p = 1 and p * S_v is exact
         float m_new = fmaxf(st.m, tmax);
         float alpha = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - m_new);
 #pragma unroll

@@ -99,6 +99,7 @@ struct kvq_cache {
     int splits_override = 0;
     int fused_merge = 1;
     int deterministic = 0;
+    int tile_cost[4] = {10, 12, 20, 45};  // relative kernel time of one 2/4/8/16-bit tile
     int target_workgroups = 256;
 
     uint64_t bpth(int bits) const {
@@ -293,7 +294,7 @@ void build_segments(const kvq_cache* c, const Layer& L, std::vector<kvq_segment_
 
 // Relative time one tile of each width costs the attention kernel (measured on MI355X: the narrow widths are
 // bound by de-quantization work, the wide ones by their bytes).
-int tile_cost(int bits) { return bits == 16 ? 37 : bits == 8 ? 20 : bits == 4 ? 13 : 10; }
+int cost_index(int bits) { return bits == 16 ? 3 : bits == 8 ? 2 : bits == 4 ? 1 : 0; }
 
 // Cost-balanced split of the tile range.
 void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
@@ -304,7 +305,7 @@ void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
         int nt = std::min(tpp, n_tiles - (int)i * tpp);
         if (nt <= 0) break;
         int b = L.pages[i].bits;
-        total += (uint64_t)nt * tile_cost(b);
+        total += (uint64_t)nt * (uint64_t)c->tile_cost[cost_index(b)];
     }
     int sp = 1;
     L.split_begin[0] = 0;
@@ -312,7 +313,7 @@ void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
     for (size_t i = 0; i < L.pages.size() && sp < n_splits; ++i) {
         int nt = std::min(tpp, n_tiles - (int)i * tpp);
         if (nt <= 0) break;
-        uint64_t cost = (uint64_t)tile_cost(L.pages[i].bits);
+        uint64_t cost = (uint64_t)c->tile_cost[cost_index(L.pages[i].bits)];
         uint64_t page_end = cum + cost * nt;
         while (sp < n_splits) {
             uint64_t target = (total * sp + n_splits - 1) / n_splits;
@@ -667,8 +668,24 @@ kvq_status_t kvq_cache_set_option(kvq_cache_t* c, int32_t option, int32_t value)
         case KVQ_OPT_DETERMINISTIC:
             c->deterministic = value ? 1 : 0;
             return KVQ_OK;
+        case KVQ_OPT_TILE_COST_2BIT:
+        case KVQ_OPT_TILE_COST_4BIT:
+        case KVQ_OPT_TILE_COST_8BIT:
+        case KVQ_OPT_TILE_COST_16BIT:
+            if (value < 1 || value > 1000000) return KVQ_E_INVALID;
+            c->tile_cost[option - KVQ_OPT_TILE_COST_2BIT] = value;
+            for (auto& L : c->layers) L.plan_tiles = -1;
+            return KVQ_OK;
         default: return KVQ_E_INVALID;
     }
+}
+
+kvq_status_t kvq_stream_read_probe(kvq_cache_t* c, const void* buf_dev, uint64_t bytes, int32_t n_workgroups,
+                                   void* hip_stream) {
+    if (!c || c->dry || !buf_dev || bytes < 16 || n_workgroups < 1 || n_workgroups > (1 << 20)) return KVQ_E_INVALID;
+    if (reinterpret_cast<uintptr_t>(buf_dev) & 15u) return KVQ_E_INVALID;
+    uint32_t* sink = reinterpret_cast<uint32_t*>(c->arena + c->jobs_off);  // never written in practice
+    return kvq_launch_stream_read(buf_dev, bytes, n_workgroups, sink, as_stream(hip_stream)) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
 }
 
 uint64_t kvq_cache_arena_free_bytes(const kvq_cache_t* c) { return c ? c->buddy.free_units() * c->unit_bytes : 0; }

@@ -42,6 +42,7 @@ hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* 
                              int tiles_per_page, int units, hipStream_t s);
 hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
                               int tiles_per_page, int units, hipStream_t s);
+hipError_t kvq_launch_stream_read(const void* buf, size_t bytes, int n_workgroups, uint32_t* sink, hipStream_t s);
 hipError_t kvq_launch_fill_u32(uint32_t* dst, uint32_t value, size_t n, hipStream_t s);
 
 // kvq_attention.hip

@@ -336,6 +336,21 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
     reinterpret_cast<uint32_t*>(meta + 512)[lane] = nv;
 }
 
+// Plain streaming read (16 bytes per lane, 4 loads in flight): the practical HBM read ceiling of the device,
+// against which the attention kernel's bandwidth is put next to the published peak.
+__global__ __launch_bounds__(256) void kvq_stream_read_kernel(const u32x4* __restrict__ p, size_t n,
+                                                              uint32_t* __restrict__ sink) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        u32x4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n; i += stride) acc ^= p[i];
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;  // practically never: keeps the loads alive
+}
+
 __global__ void kvq_fill_u32_kernel(uint32_t* dst, uint32_t value, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = value;
@@ -381,6 +396,12 @@ hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob*
         case 2: hipLaunchKernelGGL(kvq_quant16_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
         default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+hipError_t kvq_launch_stream_read(const void* buf, size_t bytes, int n_workgroups, uint32_t* sink, hipStream_t s) {
+    hipLaunchKernelGGL(kvq_stream_read_kernel, dim3((unsigned)n_workgroups), dim3(256), 0, s,
+                       static_cast<const u32x4*>(buf), bytes / 16, sink);
     return hipGetLastError();
 }
 

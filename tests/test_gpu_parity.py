@@ -262,7 +262,7 @@ def test_full_size_32b_layer_sampled_units():
             if det:
                 assert np.array_equal(r, outs[0])
             else:
-                assert np.abs(r - got).max() <= 5e-4
+                assert np.abs(r - got).max() <= 1e-3   # fp16 rounding of p relative to a schedule-dependent maximum
     for b, h in ((0, 0), (3, 7), (1, 4)):
         oc = OracleCache(CacheConfig(1, 1, g, 1, page_tokens=w.page_tokens, max_tokens=w.n_tokens), [1 << 50], [2])
         t = 0
