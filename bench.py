@@ -74,30 +74,35 @@ def build_state(kq, torch, w, steps_total):
 
 
 def measure_requant(kq, torch):
-    """16 -> 8 -> 4 -> 2 on one 14B-shaped block of 16,384 tokens (64 units); GB/s = (read + written) / time."""
-    B, Hkv, T, P = 8, 8, 16384, 256
+    """16 -> 8 -> 4 -> 2 on 14B-shaped blocks of 16,384 tokens (64 units); GB/s = (read + written) / time, best of
+    three blocks (each shrink of a block can run only once)."""
+    B, Hkv, T, P, L = 8, 8, 16384, 256, 3
     units = B * Hkv
-    cfg = kq.KvqConfig(1, B, 40, Hkv, T, page_tokens=P)
-    arena = torch.empty(kq.kvq_arena_bytes(cfg, int(T * units * 512 * 1.8)), dtype=torch.uint8, device="cuda")
-    cache = kq.KvqCache(cfg, [1 << 60], [2], arena=arena)
+    cfg = kq.KvqConfig(L, B, 40, Hkv, T, page_tokens=P)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, int(L * T * units * 512 * 1.7)), dtype=torch.uint8, device="cuda")
+    cache = kq.KvqCache(cfg, [1 << 60] * L, [2] * L, arena=arena)
     g = torch.Generator(device="cuda").manual_seed(14)
     k = torch.randn((B, Hkv, T, 128), device="cuda", generator=g).half()
     v = torch.randn((B, Hkv, T, 128), device="cuda", generator=g).half()
-    cache.kvq_quantize_append(0, k, v, 16)
+    for layer in range(L):
+        cache.kvq_quantize_append(layer, k, v, 16)
     del k, v
     elems = T * units * 256
     per_elem = {8: 3.125, 4: 1.75, 2: 1.0}      # algorithmic bytes per element, read + write, group 32
     out = {}
     for b in (8, 4, 2):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        cache.kvq_progressive_requant(0, segment=0)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1)
-        gbps = elems * per_elem[b] / ms / 1e6
-        out[f"{2 * b}to{b}"] = {"ms": round(ms, 4), "GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+        best = None
+        for layer in range(L):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            cache.kvq_progressive_requant(layer, segment=0)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        gbps = elems * per_elem[b] / best / 1e6
+        out[f"{2 * b}to{b}"] = {"ms": round(best, 4), "GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
     cache.close()
     return out
 

@@ -158,6 +158,137 @@ __device__ inline void store_meta_v(uint8_t* meta, int lane, const uint16_t (&S)
     }
 }
 
+// ------------------------------------------------------------------------------ row-owner quantizer core
+// Quantized widths are produced by "owner" lanes: in each of two passes over a 32-token tile, lane l owns the
+// group (token 16*pass + l/4, channels 32*(l%4) .. +31): 64 contiguous bytes, so the minimum and maximum need
+// no cross-lane traffic.  The owner writes its 32 codes as bytes to LDS -- [token][channel] for a K tile,
+// [channel][token] for a V tile -- from where every lane gathers the slots of the tile layout with 8-byte reads.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+
+__device__ inline uint32_t pk_min_u(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)));
+}
+__device__ inline uint32_t pk_max_u(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)));
+}
+
+#define KVQ_LDS_CODES_K 4096                       // K: [32 tokens][128 channels] code bytes
+#define KVQ_LDS_VGRP (32 * 32 + 16)                // V: per group [32 channels][32 tokens] code bytes, skewed
+#define KVQ_LDS_CODES (4 * KVQ_LDS_VGRP)           // room for either arrangement
+
+// Eq. 1-2 for the 32 fp16 values in w[16] (two per dword).  codes[e] receives the code of element e as a float.
+// Fast path: t = (x - Z) * (1/S) differs from the correctly rounded quotient by < 6.1e-5 for codes up to 255,
+// so rint(t) is the required code unless t lies within 1.3e-4 of a half-integer; if any lane of the wavefront
+// sees such a value the whole step is redone with the IEEE division the definition asks for.
+template <int B>
+__device__ inline void quantize_owner(const uint32_t (&w)[16], float (&codes)[32], uint16_t* S, uint16_t* Z) {
+    constexpr int levels = (1 << B) - 1;
+    uint32_t mn2 = w[0], mx2 = w[0];
+#pragma unroll
+    for (int k = 1; k < 16; ++k) { mn2 = pk_min_u(mn2, w[k]); mx2 = pk_max_u(mx2, w[k]); }
+    const float mn = fminf(h2f((uint16_t)(mn2 & 0xffff)), h2f((uint16_t)(mn2 >> 16)));
+    const float mx = fmaxf(h2f((uint16_t)(mx2 & 0xffff)), h2f((uint16_t)(mx2 >> 16)));
+    float Sf;
+    group_params(mn, mx, levels, S, Z, &Sf);
+    const float rcp = (Sf == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(Sf);
+    float worst = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const float x = h2f((uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffff)));
+        const float t = (x - mn) * rcp;
+        const float r = rintf(t);
+        worst = fmaxf(worst, fabsf(t - r));
+        codes[e] = fminf(r, (float)levels);
+    }
+    if (__any(worst > 0.5f - 1.3e-4f)) {
+        asm volatile("" ::: "memory");  // keep this a branch
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            const float x = h2f((uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffff)));
+            codes[e] = (float)code_of(x, mn, Sf, levels);
+        }
+    }
+}
+
+// Owner -> LDS.  tl = token in tile, grp = channel group, which = 0 K / 1 V.
+__device__ inline void scatter_codes(uint8_t* lds, int which, int tl, int grp, const float (&codes)[32]) {
+    if (!which) {
+        uint32_t d[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            uint32_t v = __builtin_amdgcn_cvt_pk_u8_f32(codes[4 * k], 0u, 0u);
+            v = __builtin_amdgcn_cvt_pk_u8_f32(codes[4 * k + 1], 1u, v);
+            v = __builtin_amdgcn_cvt_pk_u8_f32(codes[4 * k + 2], 2u, v);
+            d[k] = __builtin_amdgcn_cvt_pk_u8_f32(codes[4 * k + 3], 3u, v);
+        }
+        u32x4* dst = reinterpret_cast<u32x4*>(lds + tl * 128 + grp * 32);
+        dst[0] = u32x4{d[0], d[1], d[2], d[3]};
+        dst[1] = u32x4{d[4], d[5], d[6], d[7]};
+    } else {
+        uint8_t* dst = lds + grp * KVQ_LDS_VGRP + tl;
+#pragma unroll
+        for (int c = 0; c < 32; ++c) dst[c * 32] = (uint8_t)(uint32_t)codes[c];
+    }
+}
+
+// 8 code bytes (b0 in the low byte of w0) -> 8 codes of B bits, packed little-endian into the low 8*B bits.
+template <int B>
+__device__ inline void pack8(uint32_t w0, uint32_t w1, uint32_t* lo, uint32_t* hi) {
+    if constexpr (B == 8) {
+        *lo = w0; *hi = w1;
+    } else if constexpr (B == 4) {
+        uint32_t x = w0 | (w0 >> 4), y = w1 | (w1 >> 4);
+        *lo = __builtin_amdgcn_perm(y, x, 0x06040200u);
+        *hi = 0u;
+    } else {
+        uint32_t x = w0 | (w0 >> 6), y = w1 | (w1 >> 6);
+        x |= x >> 12; y |= y >> 12;
+        *lo = __builtin_amdgcn_perm(y, x, 0x0c0c0400u);
+        *hi = 0u;
+    }
+}
+
+// LDS -> the lane's packed string of the tile layout.
+template <int B>
+__device__ inline void gather_string(const uint8_t* lds, int which, int lane, uint32_t (&str)[2 * B]) {
+    const int j = lane >> 4, n = lane & 15;
+#pragma unroll
+    for (int d = 0; d < 2 * B; ++d) str[d] = 0u;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const uint8_t* src;
+        if (!which) {
+            const int sub = p >> 2, grp = p & 3;
+            const int t = 8 * (n >> 2) + 4 * sub + (n & 3);
+            src = lds + t * 128 + grp * 32 + 8 * j;
+        } else {
+            const int ch = 16 * p + n;  // piece p = channel block nt
+            src = lds + (ch >> 5) * KVQ_LDS_VGRP + (ch & 31) * 32 + 8 * j;
+        }
+        const uint32_t w0 = reinterpret_cast<const uint32_t*>(src)[0], w1 = reinterpret_cast<const uint32_t*>(src)[1];
+        uint32_t lo, hi;
+        pack8<B>(w0, w1, &lo, &hi);
+        if constexpr (B == 8) { str[2 * p] = lo; str[2 * p + 1] = hi; }
+        else if constexpr (B == 4) { str[p] = lo; }
+        else { str[p >> 1] |= lo << (16 * (p & 1)); }
+    }
+}
+
+__device__ inline void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Owner lanes write the (S, Z) of their group straight to the tile's metadata.
+__device__ inline void store_meta_owner(uint8_t* meta, int which, int tl, int grp, uint16_t S, uint16_t Z) {
+    uint16_t* ms = reinterpret_cast<uint16_t*>(meta + (which ? 512 : 0));
+    uint16_t* mz = reinterpret_cast<uint16_t*>(meta + (which ? 768 : 256));
+    const int idx = which ? kvq_vmeta_index(tl, grp) : tl * 4 + grp;
+    ms[idx] = S;
+    mz[idx] = Z;
+}
+
 // ------------------------------------------------------------------------------------------------ append
 // grid.x = 2 * (tiles touched) (even: K tile, odd: V tile), grid.y = (sequence, KV head) unit, 64 threads.
 // Writes every slot of every touched tile: stored tokens keep their bits, new tokens are quantized (or
@@ -243,13 +374,80 @@ __global__ __launch_bounds__(64) void kvq_append_kernel(uint8_t* __restrict__ ar
     store_chunks<B>(code, lane, str);
 }
 
+// Quantizing append (B = 8, 4, 2): same grid and contract as kvq_append_kernel, built on the row-owner core.
+template <int B>
+__global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ arena,
+                                                          const KvqPageDesc* __restrict__ table,
+                                                          const uint16_t* __restrict__ k_in,
+                                                          const uint16_t* __restrict__ v_in, int t_old,
+                                                          int n_new, int tpp, int tile0) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
+    const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
+    const int which = blockIdx.x & 1;
+    const int tile = tile0 + (blockIdx.x >> 1);
+    const int unit = blockIdx.y;
+    const int page = tile / tpp, tip = tile - page * tpp;
+    const KvqPageDesc pd = table[page];
+    const uint64_t tslot = (uint64_t)unit * tpp + tip;
+    uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * B);
+    uint8_t* meta = arena + (uint64_t)pd.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
+    const int t_new = t_old + n_new, tok0 = tile * KVQ_TILE_TOKENS;
+    const uint16_t* in = (which ? v_in : k_in) + (uint64_t)unit * n_new * KVQ_D;
+    const int grp = lane & 3;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tl = 16 * pass + (lane >> 2);
+        const int tok = tok0 + tl;
+        const bool isnew = tok >= t_old && tok < t_new;
+        uint32_t w[16];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (isnew) v = *reinterpret_cast<const u32x4*>(in + (uint64_t)(tok - t_old) * KVQ_D + 32 * grp + 8 * c);
+            w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+        }
+        float codes[32];
+        uint16_t S, Z;
+        quantize_owner<B>(w, codes, &S, &Z);  // tokens that are not new quantize zeros: codes 0, S = Z = 0
+        scatter_codes(lds, which, tl, grp, codes);
+        if (tok >= t_old) store_meta_owner(meta, which, tl, grp, S, Z);
+    }
+    wave_sync_lds();
+    uint32_t str[2 * B];
+    gather_string<B>(lds, which, lane, str);
+    // stored tokens keep their bits
+    uint32_t keep = 0;
+    if (!which) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+            if (tok0 + 8 * (n >> 2) + 4 * sub + (n & 3) < t_old) keep |= 1u << sub;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (tok0 + 8 * j + i < t_old) keep |= 1u << i;
+    }
+    if (tok0 < t_old && keep) {
+        uint32_t old[2 * B];
+        load_chunks<B>(code, lane, old);
+#pragma unroll
+        for (int d = 0; d < 2 * B; ++d) {
+            uint32_t m = which ? v_token_mask<B>(keep, d) : (((keep >> (d / B)) & 1u) ? 0xffffffffu : 0u);
+            str[d] = (old[d] & m) | (str[d] & ~m);
+        }
+    }
+    store_chunks<B>(code, lane, str);
+}
+
 // ------------------------------------------------------------------------------------- fp16 page -> b bits
 // grid.x = 2 * n_jobs * tiles_per_page, grid.y = unit, 64 threads.  Direct quantization (Eq. 1-2) of a page
-// that still holds raw fp16 values.
+// that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by
+// owner lanes exactly like an append.
 template <int B>
 __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ arena,
                                                          const KvqRequantJob* __restrict__ jobs, int tpp) {
-    const int lane = threadIdx.x;
+    __shared__ __attribute__((aligned(16))) uint8_t raw_lds[32 * 128 * 2];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
+    const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
     const int idx = blockIdx.x >> 1;
     const int job = idx / tpp, tip = idx - job * tpp;
@@ -259,24 +457,49 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
     const uint8_t* src = arena + (uint64_t)jb.src_code_off256 * 256u + (tslot * 2 + which) * (512u * 16);
     uint8_t* dst = arena + (uint64_t)jb.dst_code_off256 * 256u + (tslot * 2 + which) * (512u * B);
     uint8_t* meta = arena + (uint64_t)jb.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
-    uint32_t in[32];
-    load_chunks<16>(src, lane, in);
-    float x[64];
+    {
+        uint32_t in[32];
+        load_chunks<16>(src, lane, in);
+        if (!which) {
 #pragma unroll
-    for (int d = 0; d < 32; ++d) {
-        x[2 * d] = h2f((uint16_t)(in[d] & 0xffff));
-        x[2 * d + 1] = h2f((uint16_t)(in[d] >> 16));
+            for (int p = 0; p < 8; ++p) {  // piece (sub, grp): 8 consecutive channels of one token
+                const int sub = p >> 2, g = p & 3;
+                const int t = 8 * (n >> 2) + 4 * sub + (n & 3);
+                *reinterpret_cast<u32x4*>(raw_lds + t * 256 + (32 * g + 8 * j) * 2) =
+                    u32x4{in[4 * p], in[4 * p + 1], in[4 * p + 2], in[4 * p + 3]};
+            }
+        } else {
+            uint16_t* r16 = reinterpret_cast<uint16_t*>(raw_lds);
+#pragma unroll
+            for (int d = 0; d < 32; ++d) {  // dword d = slots 2d, 2d+1 = tokens 8j + (2d%8), +1 of channel 16*(d/4)+n
+                const int nt = d >> 2, i = (2 * d) & 7;
+                const int ch = 16 * nt + n;
+                r16[(8 * j + i) * 128 + ch] = (uint16_t)(in[d] & 0xffff);
+                r16[(8 * j + i + 1) * 128 + ch] = (uint16_t)(in[d] >> 16);
+            }
+        }
     }
+    wave_sync_lds();
+    const int grp = lane & 3;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tl = 16 * pass + (lane >> 2);
+        uint32_t w[16];
+        const u32x4* rp = reinterpret_cast<const u32x4*>(raw_lds + tl * 256 + grp * 64);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            u32x4 v = rp[c];
+            w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+        }
+        float codes[32];
+        uint16_t S, Z;
+        quantize_owner<B>(w, codes, &S, &Z);
+        scatter_codes(lds, which, tl, grp, codes);
+        store_meta_owner(meta, which, tl, grp, S, Z);
+    }
+    wave_sync_lds();
     uint32_t str[2 * B];
-    if (!which) {
-        uint16_t S[8], Z[8];
-        quantize_k<B>(x, str, S, Z);
-        store_meta_k(meta, lane, S, Z, 0u);
-    } else {
-        uint16_t S[32], Z[32];
-        quantize_v<B>(x, str, S, Z);
-        store_meta_v(meta, lane, S, Z, 0u);
-    }
+    gather_string<B>(lds, which, lane, str);
     store_chunks<B>(dst, lane, str);
 }
 
@@ -368,9 +591,9 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
     const uint16_t* v = static_cast<const uint16_t*>(v_in);
     switch (bits) {
         case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
-        case 8: hipLaunchKernelGGL(kvq_append_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
-        case 4: hipLaunchKernelGGL(kvq_append_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
-        case 2: hipLaunchKernelGGL(kvq_append_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
+        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
+        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
+        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -56,6 +56,38 @@ def test_quantizer_special_groups():
         assert_same_cache(oc, gc, 0)
 
 
+def test_quantizer_ties_and_near_ties():
+    """Groups built on an exact lattice: values at (k + 1/2) S and one fp16 ulp beside it, for every width.  These
+    are the inputs where a reciprocal-multiply shortcut and the correctly rounded division of Eq. 1 can disagree."""
+    B, H, T, P = 1, 2, 256, 64
+    rng = np.random.default_rng(11)
+    for bits in (8, 4, 2):
+        L = 2 ** bits - 1
+        K = np.empty((B, H, T, 128), np.float16)
+        for t in range(T):
+            for h in range(H):
+                for g in range(4):
+                    S = np.float16(2.0 ** rng.integers(-6, 3) * rng.choice([1.0, 1.5, 1.25, 0.75]))
+                    z = np.float16(rng.integers(-8, 8) * float(S))
+                    k = rng.integers(0, L, 32)
+                    vals = (k + 0.5) * float(S) + float(z)
+                    v16 = vals.astype(np.float16)
+                    jitter = rng.integers(-1, 2, 32)
+                    v16 = np.where(jitter > 0, np.nextafter(v16, np.float16(np.inf)),
+                                   np.where(jitter < 0, np.nextafter(v16, np.float16(-np.inf)), v16)).astype(np.float16)
+                    v16[0], v16[1] = z, np.float16(float(z) + L * float(S))     # pin min and max: scale = S
+                    K[0, h, t, 32 * g:32 * g + 32] = v16
+        assert np.all(np.isfinite(K))
+        oc, gc = make_pair(1, B, 2 * H, H, T, P)
+        append_both(oc, gc, 0, K, K[:, :, ::-1].copy(), bits)
+        assert_same_cache(oc, gc, 0)
+        if bits == 8:      # the same data through the fp16 tier and the 16 -> 8 kernel
+            oc2, gc2 = make_pair(1, B, 2 * H, H, T, P)
+            append_both(oc2, gc2, 0, K, K[:, :, ::-1].copy(), 16)
+            assert gc2.kvq_progressive_requant(0, segment=0) == oc2.requant(0, segment=0)
+            assert_same_cache(oc2, gc2, 0)
+
+
 def test_requant_chain_bit_exact():
     B, H, T, P = 2, 2, 512, 128
     K, V = kvq_synth.make_kv(103, 0, B, H, 0, T)
