@@ -159,7 +159,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="32b", choices=["7b", "14b", "32b", "70b"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-requant", action="store_true")
@@ -215,6 +215,7 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.warmup, steps_total):
         step(i, events)
+    t_issue = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -250,6 +251,7 @@ def main():
         "hbm_GBps_whole_step": round(bytes_per_launch * L / (ms_per_step * 1e-3) / 1e9, 1),
         "hbm_frac_whole_step": round(bytes_per_launch * L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "roofline": roofline,
+        "host_issue_ms_per_step": round((t_issue - t0) * 1e3 / args.steps, 4),
         "append": append_stats,
     }
     del outs

@@ -131,6 +131,8 @@ struct WaveState {
     float4v o[8];   // out^T accumulators: o[nt][i] = channel 16nt + 4j + i of head n (lane = 16j + n)
     float4v zl;     // quarter 0: zero-point sums of V groups 0..3; quarter 1, element 0: softmax denominator
     float m;        // running maximum of head n in log2 units (equal in the four quarters)
+    int oexp;       // the accumulators o[] hold the true sums times 2^oexp (denormal V code operands, see below)
+    int safe_v;     // 1: some V scale of this cache is large; use the overflow-proof V path
 };
 
 // query operands of one lane: [grp][4 dwords]
@@ -262,14 +264,35 @@ __device__ inline void scores_tile(const QOps& Q, const uint32_t (&kw)[2 * B], c
     }
 }
 
-// V half: out^T += V^T p^T with the probabilities `pop` (MFMA B operand) of the same tile.
+// Exponent of the accumulators while tiles of width B are added with denormal code operands: the codes enter
+// the matrix cores as c * 2^(pos - 24) and the probabilities are scaled up by 2^(posmax - pos), so every product
+// carries 2^(posmax - 24).  posmax = 6 / 4 / 0 for 2 / 4 / 8 bits; raw fp16 tiles and the overflow-proof path
+// add true values.
 template <int B>
+__device__ inline int v_exponent(int safe_v) {
+    if (B == 16 || safe_v) return 0;
+    return B == 2 ? 6 - 24 : B == 4 ? 4 - 24 : -24;
+}
+__device__ inline void set_accumulator_exponent(WaveState& st, int e) {
+    if (st.oexp == e) return;
+    const float f = __builtin_ldexpf(1.0f, e - st.oexp);  // exact power of two
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) st.o[nt] *= f;
+    st.oexp = e;
+}
+
+// V half: out^T += V^T p^T with the probabilities `pop` (MFMA B operand) of the same tile.
+// Fast path: V codes as fp16 denormals (one VALU op per two codes); the probabilities absorb the per-register
+// position factor (exact powers of two, p <= 1) before they are multiplied by the V scales.  p * 64 * S_v must
+// stay below the fp16 maximum: caches whose quantizer ever produced a V scale >= 256 take the other path, which
+// builds exact fp16 integers from the codes instead (two ops per two codes) and adds true values.
+template <int B, bool SAFE>
 __device__ inline void accumulate_tile(WaveState& st, const uint32_t (&vw)[2 * B], const uint8_t* meta_lds,
                                        const uint8_t* const_lds, const uint32_t (&pop)[4], int lane) {
     const int j = lane >> 4, n = lane & 15;
     const half8 pb = as_half8(pop[0], pop[1], pop[2], pop[3]);
-    const uint32_t ones = (n == 4) ? 0x3c003c00u : 0u;  // row 4 of the extra MFMA sums p (denominator)
     if constexpr (B == 16) {
+        const uint32_t ones = (n == 4) ? 0x3c003c00u : 0u;  // row 4 of the extra MFMA sums p (denominator)
         st.zl = mfma(as_half8(ones, ones, ones, ones), pb, st.zl);
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
@@ -282,15 +305,39 @@ __device__ inline void accumulate_tile(WaveState& st, const uint32_t (&vw)[2 * B
         const uint8_t* zsrc = (n < 4) ? meta_lds + 768 + n * 64 + j * 16 : const_lds + (n == 4 ? 0 : 16);
         u32x4 zv = *reinterpret_cast<const u32x4*>(zsrc);
         st.zl = mfma(as_half8(zv.x, zv.y, zv.z, zv.w), pb, st.zl);
+        if constexpr (SAFE) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            u32x4 sv = *reinterpret_cast<const u32x4*>(meta_lds + 512 + g * 64 + j * 16);
-            half8 pg = as_half8(pk_mul(pop[0], sv.x), pk_mul(pop[1], sv.y), pk_mul(pop[2], sv.z),
-                                pk_mul(pop[3], sv.w));
+            for (int g = 0; g < 4; ++g) {
+                u32x4 sv = *reinterpret_cast<const u32x4*>(meta_lds + 512 + g * 64 + j * 16);
+                half8 pg = as_half8(pk_mul(pop[0], sv.x), pk_mul(pop[1], sv.y), pk_mul(pop[2], sv.z),
+                                    pk_mul(pop[3], sv.w));
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                int nt = 2 * g + h;
-                st.o[nt] = mfma(dq_piece<B>(vw, nt), pg, st.o[nt]);
+                for (int h = 0; h < 2; ++h) {
+                    int nt = 2 * g + h;
+                    st.o[nt] = mfma(dq_piece<B>(vw, nt), pg, st.o[nt]);
+                }
+            }
+        } else {
+            uint32_t pf[4];  // probabilities times 2^(posmax - pos) of the operand register they meet
+            if constexpr (B == 2) {
+                pf[0] = pk_fma(pop[0], 64.f, 0.f); pf[1] = pk_fma(pop[1], 16.f, 0.f);
+                pf[2] = pk_fma(pop[2], 4.f, 0.f); pf[3] = pop[3];
+            } else if constexpr (B == 4) {
+                pf[0] = pk_fma(pop[0], 16.f, 0.f); pf[1] = pop[1];
+                pf[2] = pk_fma(pop[2], 16.f, 0.f); pf[3] = pop[3];
+            } else {
+                pf[0] = pop[0]; pf[1] = pop[1]; pf[2] = pop[2]; pf[3] = pop[3];
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x4 sv = *reinterpret_cast<const u32x4*>(meta_lds + 512 + g * 64 + j * 16);
+                half8 pg = as_half8(pk_mul(pf[0], sv.x), pk_mul(pf[1], sv.y), pk_mul(pf[2], sv.z),
+                                    pk_mul(pf[3], sv.w));
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    int nt = 2 * g + h;
+                    st.o[nt] = mfma(dq_piece_denorm<B>(vw, nt), pg, st.o[nt]);
+                }
             }
         }
     }
@@ -361,7 +408,7 @@ __device__ inline void wave_lds_sync() {  // orders LDS traffic between the lane
 }
 
 // All TPI tiles of one stage: K products, one joint softmax, V products.
-template <int B, int TPI>
+template <int B, int TPI, bool SAFE>
 __device__ inline void compute_stage(WaveState& st, const QOps& Q, const Stage<B, TPI>& sg, uint8_t* meta_lds,
                                      int n_tokens, float scale_log2, int lane) {
     if constexpr (B < 16) {
@@ -378,7 +425,7 @@ __device__ inline void compute_stage(WaveState& st, const QOps& Q, const Stage<B
     softmax_stage<B, TPI>(st, s, sg.tok0, n_tokens, lane, pop);
 #pragma unroll
     for (int k = 0; k < TPI; ++k)
-        accumulate_tile<B>(st, sg.vw[k], meta_lds + k * KVQ_META_TILE_BYTES, meta_lds + KVQ_WAVE_LDS_CONST, pop[k], lane);
+        accumulate_tile<B, SAFE>(st, sg.vw[k], meta_lds + k * KVQ_META_TILE_BYTES, meta_lds + KVQ_WAVE_LDS_CONST, pop[k], lane);
     if constexpr (B < 16) wave_lds_sync();
 }
 
@@ -448,9 +495,10 @@ __device__ inline void issue_stage(Stage<B, TPI>& sg, const RunCtx& c, int chunk
 // Process chunk `chunk` (already claimed, width B) and keep claiming and processing chunks while they have the
 // same width, software-pipelined: the loads of the next chunk are in flight while the current one is computed.
 // Returns the first claimed chunk that was not processed (another width, or past the end of the range).
-template <int B, int TPI>
-__device__ inline int run_chunks(WaveState& st, const QOps& Q, RunCtx& c, int chunk, uint8_t* meta_lds,
-                                 int lane) {
+template <int B, int TPI, bool SAFE>
+__device__ inline int run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds, RunCtx& c, int chunk,
+                                 uint8_t* meta_lds, int lane) {
+    set_accumulator_exponent(st, v_exponent<B>(SAFE));
     if constexpr (B >= 8) {
         // wide tiles (8 and 16 KiB): one register stage, tile by tile, K and V staggered (V loads fly during
         // the K product, the next tile's K and metadata loads during the V product)
@@ -462,6 +510,7 @@ __device__ inline int run_chunks(WaveState& st, const QOps& Q, RunCtx& c, int ch
         load_string<2 * B>(code, lane, kw);
         if constexpr (B < 16) mreg = *reinterpret_cast<const u32x4*>(meta + lane * 16);
         load_string<2 * B>(code + 512u * B, lane, vw);
+        if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);  // while the first loads are in flight
         for (;;) {
             float s[1][2][4];
             uint32_t pop[1][4];
@@ -484,7 +533,7 @@ __device__ inline int run_chunks(WaveState& st, const QOps& Q, RunCtx& c, int ch
                 if constexpr (B < 16) mreg = *reinterpret_cast<const u32x4*>(meta + lane * 16);
             }
             softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
-            accumulate_tile<B>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
+            accumulate_tile<B, SAFE>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
             if constexpr (B < 16) wave_lds_sync();
             if (next_t < 0) return pending;
             load_string<2 * B>(code + 512u * B, lane, vw);
@@ -493,16 +542,17 @@ __device__ inline int run_chunks(WaveState& st, const QOps& Q, RunCtx& c, int ch
     } else {
         Stage<B, TPI> s0, s1;
         issue_stage<B, TPI>(s0, c, chunk, lane);
+        if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);  // while the first loads are in flight
         for (;;) {
             const int c1 = claim_chunk(c);
             const bool same1 = c1 < c.n_chunks && chunk_bits(c, c1) == B;
             if (same1) issue_stage<B, TPI>(s1, c, c1, lane);
-            compute_stage<B, TPI>(st, Q, s0, meta_lds, c.n_tokens, c.scale_log2, lane);
+            compute_stage<B, TPI, SAFE>(st, Q, s0, meta_lds, c.n_tokens, c.scale_log2, lane);
             if (!same1) return c1;
             const int c2 = claim_chunk(c);
             const bool same2 = c2 < c.n_chunks && chunk_bits(c, c2) == B;
             if (same2) issue_stage<B, TPI>(s0, c, c2, lane);
-            compute_stage<B, TPI>(st, Q, s1, meta_lds, c.n_tokens, c.scale_log2, lane);
+            compute_stage<B, TPI, SAFE>(st, Q, s1, meta_lds, c.n_tokens, c.scale_log2, lane);
             if (!same2) return c2;
         }
     }
@@ -589,16 +639,29 @@ __device__ unsigned long long kvq_dbg[1024 * 8];
 #define KVQ_OPAD 132  // padded row of the LDS reduction slab (floats)
 
 
-// grid = (splits, units); 512 threads = 8 wavefronts, one workgroup per compute unit.
-__global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const KvqAttnParams P) {
-    __shared__ __attribute__((aligned(16))) _Float16 q_lds[16 * KVQ_D];
-    __shared__ float red_o[4][16 * KVQ_OPAD];
-    __shared__ float red_m[KVQ_ATTN_WAVES][16];
-    __shared__ float red_l[KVQ_ATTN_WAVES][16];
-    __shared__ int is_last;
-    __shared__ unsigned claim_ctr;
-    __shared__ u32x4 desc_lds[KVQ_DESC_CACHE];
-    __shared__ __attribute__((aligned(16))) uint8_t meta_lds[KVQ_ATTN_WAVES * KVQ_WAVE_LDS_BYTES];
+// LDS of one workgroup.
+struct AttnShared {
+    __attribute__((aligned(16))) _Float16 q[16 * KVQ_D];
+    float red_o[4][16 * KVQ_OPAD];
+    float red_m[KVQ_ATTN_WAVES][16];
+    float red_l[KVQ_ATTN_WAVES][16];
+    int is_last;
+    unsigned claim_ctr;
+    u32x4 desc[KVQ_DESC_CACHE];
+    __attribute__((aligned(16))) uint8_t meta[KVQ_ATTN_WAVES * KVQ_WAVE_LDS_BYTES];
+};
+
+// The whole kernel for one of the two V paths (SAFE: overflow-proof, see accumulate_tile).
+template <bool SAFE>
+__device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShared& sh) {
+    _Float16* const q_lds = sh.q;
+    float (*const red_o)[16 * KVQ_OPAD] = sh.red_o;
+    float (*const red_m)[16] = sh.red_m;
+    float (*const red_l)[16] = sh.red_l;
+    int& is_last = sh.is_last;
+    unsigned& claim_ctr = sh.claim_ctr;
+    u32x4* const desc_lds = sh.desc;
+    uint8_t* const meta_lds = sh.meta;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane >> 4, n = lane & 15;
@@ -635,6 +698,8 @@ __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const K
     for (int nt = 0; nt < 8; ++nt) st.o[nt] = float4v{0.f, 0.f, 0.f, 0.f};
     st.zl = float4v{0.f, 0.f, 0.f, 0.f};
     st.m = -INFINITY;
+    st.oexp = 0;
+    st.safe_v = SAFE ? 1 : 0;
 
     RunCtx ctx;
     ctx.arena = P.arena; ctx.desc_lds = desc_lds; ctx.claim_ctr = &claim_ctr; ctx.tpp = tpp; ctx.unit = unit;
@@ -658,17 +723,17 @@ __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const K
         int c = claim_chunk(ctx);
         while (c < ctx.n_chunks) {
             const int bits = chunk_bits(ctx, c);
-            if (Q.cls != bits) load_q_ops(Q, q_lds, lane, bits, P.scale_log2);
             switch (bits) {
-                case 16: c = run_chunks<16, 1>(st, Q, ctx, c, my_meta, lane); break;
-                case 8: c = run_chunks<8, 1>(st, Q, ctx, c, my_meta, lane); break;
-                case 4: c = run_chunks<4, 2>(st, Q, ctx, c, my_meta, lane); break;
-                default: c = run_chunks<2, 2>(st, Q, ctx, c, my_meta, lane); break;
+                case 16: c = run_chunks<16, 1, false>(st, Q, q_lds, ctx, c, my_meta, lane); break;
+                case 8: c = run_chunks<8, 1, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
+                case 4: c = run_chunks<4, 2, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
+                default: c = run_chunks<2, 2, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
             }
         }
     }
 
     KVQ_STAMP(2);
+    set_accumulator_exponent(st, 0);
     // ---- wavefront epilogue: add the zero-point term, fetch the denominator
     float l_w = __shfl(st.zl[0], 16 + n);
     {
@@ -756,6 +821,13 @@ __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const K
     merge_splits<true>(P, unit, tid, KVQ_ATTN_THREADS);
     if (tid == 0) __hip_atomic_store(&P.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     KVQ_STAMP(5);
+}
+
+// grid = (splits, units); 512 threads = 8 wavefronts, one workgroup per compute unit.
+__global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const KvqAttnParams P) {
+    __shared__ AttnShared sh;
+    if (__builtin_amdgcn_readfirstlane(P.flags[0] & 1u)) attention_body<true>(P, sh);
+    else attention_body<false>(P, sh);
 }
 
 __global__ __launch_bounds__(256) void kvq_merge_kernel(const KvqAttnParams P) {

@@ -90,7 +90,8 @@ struct kvq_cache {
     uint8_t* arena = nullptr;
     uint64_t arena_bytes = 0;
     uint64_t unit_bytes = 0;
-    uint64_t table_off = 0, jobs_off = 0, part_o_off = 0, part_ml_off = 0, counters_off = 0, pages_off = 0;
+    uint64_t table_off = 0, jobs_off = 0, part_o_off = 0, part_ml_off = 0, counters_off = 0, flags_off = 0, pages_off = 0;
+    uint32_t* flags_dev() const { return reinterpret_cast<uint32_t*>(arena + flags_off); }
     Buddy buddy;
     std::vector<Layer> layers;
     uint8_t* ring = nullptr;
@@ -122,7 +123,7 @@ struct kvq_cache {
 namespace {
 
 struct Regions {
-    uint64_t table_off, jobs_off, part_o_off, part_ml_off, counters_off, pages_off;
+    uint64_t table_off, jobs_off, part_o_off, part_ml_off, counters_off, flags_off, pages_off;
 };
 uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
@@ -150,6 +151,7 @@ Regions layout_regions(const kvq_config_t* c) {
     r.part_o_off = off;    off = align_up(off + units * KVQ_MAX_SPLITS * 16 * KVQ_D * sizeof(float), 256);
     r.part_ml_off = off;   off = align_up(off + units * KVQ_MAX_SPLITS * 32 * sizeof(float), 256);
     r.counters_off = off;  off = align_up(off + units * sizeof(uint32_t), 256);
+    r.flags_off = off;     off = align_up(off + 64, 256);
     uint64_t unit_bytes = 32ull * c->page_tokens * units;
     (void)unit_bytes;
     r.pages_off = align_up(off, 4096);
@@ -176,8 +178,9 @@ kvq_status_t upload(kvq_cache* c, void* dst_dev, const void* src, uint64_t bytes
 
 kvq_status_t ensure_device(kvq_cache* c, hipStream_t s) {
     if (c->dry || c->device_ready) return KVQ_OK;
-    if (kvq_launch_fill_u32(reinterpret_cast<uint32_t*>(c->arena + c->counters_off), 0u, (size_t)c->units, s) !=
-        hipSuccess)
+    // counters and flags are adjacent regions: one fill clears both
+    if (kvq_launch_fill_u32(reinterpret_cast<uint32_t*>(c->arena + c->counters_off), 0u,
+                            (size_t)((c->flags_off + 64 - c->counters_off) / sizeof(uint32_t)), s) != hipSuccess)
         return KVQ_E_HIP;
     c->device_ready = true;
     return KVQ_OK;
@@ -257,8 +260,8 @@ kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, 
         kvq_status_t st = upload(c, jd, jobs.data(), jobs.size() * sizeof(KvqRequantJob), s);
         hipError_t e = hipSuccess;
         if (st == KVQ_OK) {
-            e = (from == 16) ? kvq_launch_quant16(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, s)
-                             : kvq_launch_shrink(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, s);
+            e = (from == 16) ? kvq_launch_quant16(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), s)
+                             : kvq_launch_shrink(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), s);
         }
         if (st != KVQ_OK || e != hipSuccess) {
             for (auto& w : low) {
@@ -370,7 +373,7 @@ kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_bud
     c->unit_bytes = 32ull * cfg->page_tokens * c->units;
     Regions r = layout_regions(cfg);
     c->table_off = r.table_off; c->jobs_off = r.jobs_off; c->part_o_off = r.part_o_off;
-    c->part_ml_off = r.part_ml_off; c->counters_off = r.counters_off; c->pages_off = r.pages_off;
+    c->part_ml_off = r.part_ml_off; c->counters_off = r.counters_off; c->flags_off = r.flags_off; c->pages_off = r.pages_off;
     uint64_t super = c->unit_bytes << kMaxOrder;
     if (arena_bytes < c->pages_off + super) { delete c; return KVQ_E_OOM; }
     uint64_t n_super = (arena_bytes - c->pages_off) / super;
@@ -475,8 +478,16 @@ kvq_status_t kvq_quantize_append(kvq_cache_t* c, int32_t layer, const void* k_de
     st = upload_table(c, layer, (int)old_pages, (int)L.pages.size(), s);
     if (st != KVQ_OK) return st;
     if (!c->dry) {
-        if (kvq_launch_append(e, c->arena, c->table_dev(layer), k_dev, v_dev, t_old, n_new, c->tpp, c->units, s) !=
-            hipSuccess)
+        // short appends (at most two pages touched) carry the page descriptors in the kernel arguments
+        const int pg0 = t_old / P, pg1 = (T - 1) / P;
+        KvqPageDesc two[2];
+        const bool by_arg = pg1 - pg0 <= 1;
+        if (by_arg) {
+            two[0] = c->desc(L.pages[(size_t)pg0]);
+            two[1] = c->desc(L.pages[(size_t)pg1]);
+        }
+        if (kvq_launch_append(e, c->arena, c->table_dev(layer), k_dev, v_dev, t_old, n_new, c->tpp, c->units,
+                              by_arg ? two : nullptr, pg0, c->flags_dev(), s) != hipSuccess)
             return KVQ_E_HIP;
     }
     if (!evicted.empty()) {
@@ -562,6 +573,7 @@ kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_d
     p.part_o = reinterpret_cast<float*>(c->arena + c->part_o_off);
     p.part_ml = reinterpret_cast<float*>(c->arena + c->part_ml_off);
     p.counters = reinterpret_cast<uint32_t*>(c->arena + c->counters_off);
+    p.flags = c->flags_dev();
     p.n_tokens = L.T;
     p.tiles_per_page = c->tpp;
     p.gqa = c->gqa;

@@ -21,6 +21,7 @@ struct KvqAttnParams {
     float* part_o;             // [unit][split][16][128] un-normalised partial outputs
     float* part_ml;            // [unit][split][2][16] running max (log2 units) and sum
     uint32_t* counters;        // [unit] arrival counters of the fused merge (kept at zero between launches)
+    const uint32_t* flags;     // [0] bit 0: some V scale of the cache is >= 256 (set by the quantizing kernels)
     int32_t n_tokens;
     int32_t tiles_per_page;
     int32_t gqa;               // query heads per KV head
@@ -37,11 +38,11 @@ struct KvqAttnParams {
 // kvq_quant.hip
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
-                             hipStream_t s);
+                             const KvqPageDesc* first_two, int first_page, uint32_t* flags, hipStream_t s);
 hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
-                             int tiles_per_page, int units, hipStream_t s);
+                             int tiles_per_page, int units, uint32_t* flags, hipStream_t s);
 hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
-                              int tiles_per_page, int units, hipStream_t s);
+                              int tiles_per_page, int units, uint32_t* flags, hipStream_t s);
 hipError_t kvq_launch_stream_read(const void* buf, size_t bytes, int n_workgroups, uint32_t* sink, hipStream_t s);
 hipError_t kvq_launch_fill_u32(uint32_t* dst, uint32_t value, size_t n, hipStream_t s);
 

@@ -280,6 +280,13 @@ __device__ inline void wave_sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The attention kernel multiplies probabilities (<= 1) by up to 64 and by the V scale in fp16; a cache that ever
+// holds a V scale of 256 or more (a value range no attention layer produces) is marked and takes the kernel's
+// overflow-proof path instead.
+__device__ inline void note_large_v_scale(uint32_t* flags, int which, uint16_t S) {
+    if (which && h2f(S) >= 256.0f) atomicOr(flags, 1u);
+}
+
 // Owner lanes write the (S, Z) of their group straight to the tile's metadata.
 __device__ inline void store_meta_owner(uint8_t* meta, int which, int tl, int grp, uint16_t S, uint16_t Z) {
     uint16_t* ms = reinterpret_cast<uint16_t*>(meta + (which ? 512 : 0));
@@ -290,6 +297,17 @@ __device__ inline void store_meta_owner(uint8_t* meta, int which, int tl, int gr
 }
 
 // ------------------------------------------------------------------------------------------------ append
+// Descriptors of the (at most two) pages a short append touches ride in the kernel arguments, which saves the
+// dependent read of the device page table; longer appends look the table up.
+struct KvqAppendPages {
+    KvqPageDesc d[2];
+    int first_page;  // -1: use the table
+};
+__device__ inline KvqPageDesc append_desc(const KvqPageDesc* table, const KvqAppendPages& ap, int page) {
+    if (ap.first_page < 0) return table[page];
+    return page == ap.first_page ? ap.d[0] : ap.d[1];
+}
+
 // grid.x = 2 * (tiles touched) (even: K tile, odd: V tile), grid.y = (sequence, KV head) unit, 64 threads.
 // Writes every slot of every touched tile: stored tokens keep their bits, new tokens are quantized (or
 // copied for B = 16), slots past the new end are zeroed so that partially filled tiles stay well defined.
@@ -298,13 +316,13 @@ __global__ __launch_bounds__(64) void kvq_append_kernel(uint8_t* __restrict__ ar
                                                         const KvqPageDesc* __restrict__ table,
                                                         const uint16_t* __restrict__ k_in,
                                                         const uint16_t* __restrict__ v_in, int t_old,
-                                                        int n_new, int tpp, int tile0) {
+                                                        int n_new, int tpp, int tile0, KvqAppendPages ap) {
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
     const int tile = tile0 + (blockIdx.x >> 1);
     const int unit = blockIdx.y;
     const int page = tile / tpp, tip = tile - page * tpp;
-    const KvqPageDesc pd = table[page];
+    const KvqPageDesc pd = append_desc(table, ap, page);
     const uint64_t tslot = (uint64_t)unit * tpp + tip;
     uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * B);
     uint8_t* meta = arena + (uint64_t)pd.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
@@ -362,6 +380,37 @@ __global__ __launch_bounds__(64) void kvq_append_kernel(uint8_t* __restrict__ ar
             store_meta_v(meta, lane, S, Z, keep);
         }
     }
+    if constexpr (B == 16) {
+        if (has_old) {
+            // the tile was written in full (zero tail included) when its first token arrived: store only the
+            // new tokens' elements -- whole 16-byte chunks for K, single fp16 values for V
+            if (!which) {
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) {
+                    const int tok = tok0 + 8 * (n >> 2) + 4 * sub + (n & 3);
+                    if (tok >= t_old && tok < t_new) {
+#pragma unroll
+                        for (int c = 4 * sub; c < 4 * sub + 4; ++c)
+                            *reinterpret_cast<u32x4*>(code + (c * 64 + lane) * 16) =
+                                u32x4{str[4 * c], str[4 * c + 1], str[4 * c + 2], str[4 * c + 3]};
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int tok = tok0 + 8 * j + i;
+                    if (tok >= t_old && tok < t_new) {
+#pragma unroll
+                        for (int nt = 0; nt < 8; ++nt) {
+                            const int slot = nt * 8 + i;  // 2 bytes at string offset 2*slot
+                            *reinterpret_cast<uint16_t*>(code + kvq_tile_byte(lane, 2u * slot)) = raw[slot];
+                        }
+                    }
+                }
+            }
+            return;
+        }
+    }
     if (has_old && keep) {
         uint32_t old[2 * B];
         load_chunks<B>(code, lane, old);
@@ -380,14 +429,15 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
                                                           const KvqPageDesc* __restrict__ table,
                                                           const uint16_t* __restrict__ k_in,
                                                           const uint16_t* __restrict__ v_in, int t_old,
-                                                          int n_new, int tpp, int tile0) {
+                                                          int n_new, int tpp, int tile0, KvqAppendPages ap,
+                                                          uint32_t* __restrict__ flags) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
     const int tile = tile0 + (blockIdx.x >> 1);
     const int unit = blockIdx.y;
     const int page = tile / tpp, tip = tile - page * tpp;
-    const KvqPageDesc pd = table[page];
+    const KvqPageDesc pd = append_desc(table, ap, page);
     const uint64_t tslot = (uint64_t)unit * tpp + tip;
     uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * B);
     uint8_t* meta = arena + (uint64_t)pd.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
@@ -409,6 +459,7 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
         float codes[32];
         uint16_t S, Z;
         quantize_owner<B>(w, codes, &S, &Z);  // tokens that are not new quantize zeros: codes 0, S = Z = 0
+        note_large_v_scale(flags, which, S);
         scatter_codes(lds, which, tl, grp, codes);
         if (tok >= t_old) store_meta_owner(meta, which, tl, grp, S, Z);
     }
@@ -444,7 +495,8 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
 // owner lanes exactly like an append.
 template <int B>
 __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ arena,
-                                                         const KvqRequantJob* __restrict__ jobs, int tpp) {
+                                                         const KvqRequantJob* __restrict__ jobs, int tpp,
+                                                         uint32_t* __restrict__ flags) {
     __shared__ __attribute__((aligned(16))) uint8_t raw_lds[32 * 128 * 2];
     __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
@@ -494,6 +546,7 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
         float codes[32];
         uint16_t S, Z;
         quantize_owner<B>(w, codes, &S, &Z);
+        note_large_v_scale(flags, which, S);
         scatter_codes(lds, which, tl, grp, codes);
         store_meta_owner(meta, which, tl, grp, S, Z);
     }
@@ -526,7 +579,8 @@ __device__ inline uint32_t shrink_8_to_4(uint32_t w) {  // 4 bytes -> 4 nibbles 
 // one (page, unit, tile) from 2B to B bits and multiplies its 256 scales by 2^B + 1 in place.
 template <int B>
 __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ arena,
-                                                        const KvqRequantJob* __restrict__ jobs, int tpp) {
+                                                        const KvqRequantJob* __restrict__ jobs, int tpp,
+                                                        uint32_t* __restrict__ flags) {
     const int lane = threadIdx.x;
     const int job = blockIdx.x / tpp, tip = blockIdx.x - job * tpp;
     const int unit = blockIdx.y;
@@ -557,6 +611,8 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
     uint32_t nv = (uint32_t)f2h_rn(h2f((uint16_t)(sv & 0xffff)) * f) | ((uint32_t)f2h_rn(h2f((uint16_t)(sv >> 16)) * f) << 16);
     reinterpret_cast<uint32_t*>(meta)[lane] = nk;
     reinterpret_cast<uint32_t*>(meta + 512)[lane] = nv;
+    note_large_v_scale(flags, 1, (uint16_t)(nv & 0xffff));
+    note_large_v_scale(flags, 1, (uint16_t)(nv >> 16));
 }
 
 // Plain streaming read (16 bytes per lane, 4 loads in flight): the practical HBM read ceiling of the device,
@@ -583,40 +639,44 @@ __global__ void kvq_fill_u32_kernel(uint32_t* dst, uint32_t value, size_t n) {
 
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
-                             hipStream_t s) {
+                             const KvqPageDesc* first_two, int first_page, uint32_t* flags, hipStream_t s) {
     int tile0 = t_old / KVQ_TILE_TOKENS;
     int tile1 = (t_old + n_new + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
     dim3 grid(2 * (tile1 - tile0), units), block(64);
     const uint16_t* k = static_cast<const uint16_t*>(k_in);
     const uint16_t* v = static_cast<const uint16_t*>(v_in);
+    KvqAppendPages ap;
+    ap.first_page = first_two ? first_page : -1;
+    ap.d[0] = first_two ? first_two[0] : KvqPageDesc{0, 0, 0, 0};
+    ap.d[1] = first_two ? first_two[1] : KvqPageDesc{0, 0, 0, 0};
     switch (bits) {
-        case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
-        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
-        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
-        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0); break;
+        case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap); break;
+        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags); break;
+        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags); break;
+        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
-                             int tiles_per_page, int units, hipStream_t s) {
+                             int tiles_per_page, int units, uint32_t* flags, hipStream_t s) {
     dim3 grid(n_jobs * tiles_per_page, units), block(64);
     switch (dst_bits) {
-        case 4: hipLaunchKernelGGL(kvq_shrink_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
-        case 2: hipLaunchKernelGGL(kvq_shrink_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
+        case 4: hipLaunchKernelGGL(kvq_shrink_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
+        case 2: hipLaunchKernelGGL(kvq_shrink_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
-                              int tiles_per_page, int units, hipStream_t s) {
+                              int tiles_per_page, int units, uint32_t* flags, hipStream_t s) {
     dim3 grid(2 * n_jobs * tiles_per_page, units), block(64);
     switch (dst_bits) {
-        case 8: hipLaunchKernelGGL(kvq_quant16_kernel<8>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
-        case 4: hipLaunchKernelGGL(kvq_quant16_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
-        case 2: hipLaunchKernelGGL(kvq_quant16_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page); break;
+        case 8: hipLaunchKernelGGL(kvq_quant16_kernel<8>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
+        case 4: hipLaunchKernelGGL(kvq_quant16_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
+        case 2: hipLaunchKernelGGL(kvq_quant16_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

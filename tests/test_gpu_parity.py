@@ -217,6 +217,32 @@ def test_attention_short_caches(T):
         check_attention(oc, gc, 0, kvq_synth.make_q(400, 0, B, 4, T - 1))
 
 
+def test_large_value_scales_take_the_overflow_proof_path():
+    """V ranges far beyond anything an attention layer produces (scales >= 256) switch the kernel to its second
+    V path; outputs stay within the tolerance scaled to the magnitude of V, before and after the switch."""
+    B, H, T, P = 1, 2, 512, 64
+    K, V = kvq_synth.make_kv(600, 0, B, H, 0, T)
+    Vbig = (V.astype(np.float32) * 600.0).astype(np.float16)
+    oc, gc = make_pair(1, B, 4 * H, H, T, P)
+    q = kvq_synth.make_q(600, 0, B, 4 * H, T - 1)
+
+    def check(scale_v):
+        out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+        gc.kvq_decode_attention(0, dev(q), out)
+        want = oc.attention(0, q)
+        mx, rl = attention_errors(out.cpu().numpy(), want)
+        assert rl <= REL_L2 and mx <= MAX_ABS * scale_v, (mx, rl)
+
+    append_both(oc, gc, 0, K[:, :, :256], V[:, :, :256], 2)        # ordinary values: fast path
+    check(1.0)
+    append_both(oc, gc, 0, K[:, :, 256:384], Vbig[:, :, 256:384], 2)   # 2-bit scales ~ 1000: marks the cache
+    append_both(oc, gc, 0, K[:, :, 384:], Vbig[:, :, 384:], 4)
+    assert_same_cache(oc, gc, 0)
+    check(600.0)
+    assert gc.kvq_progressive_requant(0, segment=1) == oc.requant(0, segment=1)    # 4 -> 2 keeps it marked
+    check(600.0)
+
+
 def test_empty_cache_is_a_state_error():
     _, gc = make_pair(1, 1, 4, 1, 256, 32)
     out = torch.empty((1, 4, 128), dtype=torch.float32, device="cuda")
