@@ -48,6 +48,7 @@ def build_state(kq, torch, w, steps_total):
     Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
     gen_s = time.time() - t0
     append_stats = {}
+    filler = QueueFiller(torch, cache)
     for layer in range(L):
         t = 0
         tiers = list(w.tiers_of_layer(layer))
@@ -55,11 +56,12 @@ def build_state(kq, torch, w, steps_total):
         for n, bits in tiers:
             k = Kd[:, :, t:t + n].contiguous()
             v = Vd[:, :, t:t + n].contiguous()
-            if layer == 0:
+            if layer == 1:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                filler()
                 e0.record()
             cache.kvq_quantize_append(layer, k, v, bits)
-            if layer == 0:
+            if layer == 1:
                 e1.record()
                 torch.cuda.synchronize()
                 ms = e0.elapsed_time(e1)
@@ -69,8 +71,22 @@ def build_state(kq, torch, w, steps_total):
         del k, v
     torch.cuda.synchronize()
     tail = (Kd[:, :, -steps_total:].contiguous(), Vd[:, :, -steps_total:].contiguous())
-    del Kd, Vd
+    del Kd, Vd, filler
     return cache, arena, tail, gen_s, append_stats, (K, V)
+
+
+class QueueFiller:
+    """Keeps the stream busy for a few hundred microseconds (one plain read of 2 GiB) so that a one-shot library
+    call measured with events is already queued when the GPU reaches the first event: the host's enqueue time
+    (allocator walk, table upload, launch) then stays out of the measured interval."""
+
+    def __init__(self, torch, cache):
+        self.cache = cache
+        self.buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+        self.buf.fill_(1)
+
+    def __call__(self):
+        self.cache.kvq_stream_read_probe(self.buf, 2048)
 
 
 def measure_requant(kq, torch):
@@ -89,12 +105,14 @@ def measure_requant(kq, torch):
     del k, v
     elems = T * units * 256
     per_elem = {8: 3.125, 4: 1.75, 2: 1.0}      # algorithmic bytes per element, read + write, group 32
+    filler = QueueFiller(torch, cache)
     out = {}
     for b in (8, 4, 2):
         best = None
         for layer in range(L):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
+            filler()
             e0.record()
             cache.kvq_progressive_requant(layer, segment=0)
             e1.record()

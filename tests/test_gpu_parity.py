@@ -332,3 +332,56 @@ def test_full_size_32b_layer_sampled_units():
         mx, rl = attention_errors(got[b:b + 1, h * g:(h + 1) * g], want)
         print("32b unit", b, h, mx, rl)
         assert mx <= MAX_ABS and rl <= REL_L2, (b, h, mx, rl)
+
+
+def _sampled_full_size(w, B, units_to_check, layer=0):
+    """Build one block of workload w (batch B) through the library and check sampled (sequence, KV head) units
+    against the oracle, which builds only those units."""
+    Hkv, g = w.n_kv_heads, w.n_q_heads // w.n_kv_heads
+    tiers = w.tiers_of_layer(layer)
+    cfg = kq.KvqConfig(1, B, w.n_q_heads, Hkv, w.n_tokens, page_tokens=w.page_tokens)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, w.n_tokens * B * Hkv * 560), dtype=torch.uint8, device="cuda")
+    gc = kq.KvqCache(cfg, [1 << 50], [2], arena=arena)
+    t = 0
+    for n, bits in tiers:
+        for t0 in range(t, t + n, 16384):          # bounded host memory per append
+            t1 = min(t0 + 16384, t + n)
+            K, V = kvq_synth.make_kv(w.seed, layer, B, Hkv, t0, t1)
+            gc.kvq_quantize_append(0, dev(K), dev(V), bits)
+        t += n
+    q = kvq_synth.make_q(w.seed, layer, B, w.n_q_heads, w.n_tokens - 1)
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    gc.kvq_decode_attention(0, dev(q), out)
+    got = out.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    segs = gc.kvq_cache_describe(0)[0]
+    assert [(b - a, bits) for a, b, bits in segs] == [(n, bits) for n, bits in tiers]
+    for b, h in units_to_check:
+        oc = OracleCache(CacheConfig(1, 1, g, 1, page_tokens=w.page_tokens, max_tokens=w.n_tokens), [1 << 50], [2])
+        t = 0
+        for n, bits in tiers:
+            k, v = kvq_synth.make_kv_unit(w.seed, layer, b, h, t, t + n)
+            oc.append(0, k[None, None], v[None, None], bits)
+            t += n
+        want = oc.attention(0, q[b:b + 1, h * g:(h + 1) * g])
+        mx, rl = attention_errors(got[b:b + 1, h * g:(h + 1) * g], want)
+        print(w.name, "unit", b, h, mx, rl)
+        assert mx <= MAX_ABS and rl <= REL_L2, (w.name, b, h, mx, rl)
+
+
+def test_full_size_70b_layer_sampled_units():
+    """One block of the 70B-shaped workload: 128K tokens, 64 q / 8 kv heads, mostly 2- and 4-bit."""
+    _sampled_full_size(kvq_synth.WORKLOADS["70b"], 1, ((0, 0), (0, 5)))
+
+
+def test_full_size_7b_layer_sampled_units():
+    """One block of the 7B-shaped workload at batch 2 of 16 (the launch shape per unit is unchanged)."""
+    _sampled_full_size(kvq_synth.WORKLOADS["7b"], 2, ((0, 1), (1, 3)))
+
+
+def test_full_size_14b_layer_sampled_units():
+    """Two blocks of the 14B-shaped workload (their bulk widths are drawn per block) at batch 1 of 8."""
+    w = kvq_synth.WORKLOADS["14b"]
+    layers = [w.layer_bits.index(b) for b in (2, 8) if b in w.layer_bits]
+    for layer in layers:
+        _sampled_full_size(w, 1, ((0, 2),), layer=layer)
