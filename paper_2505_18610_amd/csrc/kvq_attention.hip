@@ -203,6 +203,12 @@ struct Stage {
 #define KVQ_ATTN_THREADS 512
 #define KVQ_ATTN_WAVES 8
 #define KVQ_PAD_TOK0 0x3fffff00
+#ifndef KVQ_RING_2BIT
+#define KVQ_RING_2BIT 2   // register stages of the 2-bit pipeline (one less is in flight)
+#endif
+#ifndef KVQ_RING_4BIT
+#define KVQ_RING_4BIT 2
+#endif
 #define KVQ_WAVE_LDS_CONST (2 * KVQ_META_TILE_BYTES)  // 16 bytes of fp16 ones, then 16 bytes of zeros
 #define KVQ_WAVE_LDS_BYTES (2 * KVQ_META_TILE_BYTES + 32)
 
@@ -450,7 +456,7 @@ struct RunCtx {
 __device__ inline int claim_chunk(RunCtx& c) {
     if (c.next_static >= 0) {
         const int v = c.next_static;
-        c.next_static += KVQ_ATTN_WAVES;
+        c.next_static = __builtin_amdgcn_readfirstlane(v + KVQ_ATTN_WAVES);  // provably wavefront-uniform
         return v;
     }
     unsigned v = 0;
@@ -493,9 +499,14 @@ __device__ inline void issue_stage(Stage<B, TPI>& sg, const RunCtx& c, int chunk
 }
 
 // Process chunk `chunk` (already claimed, width B) and keep claiming and processing chunks while they have the
-// same width, software-pipelined: the loads of the next chunk are in flight while the current one is computed.
-// Returns the first claimed chunk that was not processed (another width, or past the end of the range).
-template <int B, int TPI, bool SAFE>
+// same width, software-pipelined: the loads of the following chunks are in flight while the current one is
+// computed.  Returns the first claimed chunk that was not processed (another width, or past the end of the range).
+//
+// The steady-state path contains no load that is issued conditionally: the wait counts in front of a stage's
+// first use are then exactly "everything issued after it may still be in flight".  (A load under a condition
+// would make the compiler wait for the stricter of the two paths, i.e. drain the prefetch every time.)  The
+// end of a run therefore has code of its own.
+template <int B, int TPI, int N, bool SAFE>
 __device__ inline int run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds, RunCtx& c, int chunk,
                                  uint8_t* meta_lds, int lane) {
     set_accumulator_exponent(st, v_exponent<B>(SAFE));
@@ -510,7 +521,7 @@ __device__ inline int run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds, 
         load_string<2 * B>(code, lane, kw);
         if constexpr (B < 16) mreg = *reinterpret_cast<const u32x4*>(meta + lane * 16);
         load_string<2 * B>(code + 512u * B, lane, vw);
-        if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);  // while the first loads are in flight
+        if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);
         for (;;) {
             float s[1][2][4];
             uint32_t pop[1][4];
@@ -527,34 +538,62 @@ __device__ inline int run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds, 
                 pending = claim_chunk(c);
                 if (pending < c.n_chunks && chunk_bits(c, pending) == B) { next_t = chunk_tile(c, pending); next_c = pending; }
             }
-            if (next_t >= 0) {
-                tile_addr<B>(c, next_t, &code, &meta);
-                load_string<2 * B>(code, lane, kw);
-                if constexpr (B < 16) mreg = *reinterpret_cast<const u32x4*>(meta + lane * 16);
+            if (next_t < 0) {  // last tile of the run
+                softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
+                accumulate_tile<B, SAFE>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
+                if constexpr (B < 16) wave_lds_sync();
+                return pending;
             }
+            tile_addr<B>(c, next_t, &code, &meta);
+            load_string<2 * B>(code, lane, kw);
+            if constexpr (B < 16) mreg = *reinterpret_cast<const u32x4*>(meta + lane * 16);
             softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
             accumulate_tile<B, SAFE>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
             if constexpr (B < 16) wave_lds_sync();
-            if (next_t < 0) return pending;
             load_string<2 * B>(code + 512u * B, lane, vw);
             t = next_t; k = next_k; cur = next_c;
         }
     } else {
-        Stage<B, TPI> s0, s1;
-        issue_stage<B, TPI>(s0, c, chunk, lane);
-        if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);  // while the first loads are in flight
-        for (;;) {
-            const int c1 = claim_chunk(c);
-            const bool same1 = c1 < c.n_chunks && chunk_bits(c, c1) == B;
-            if (same1) issue_stage<B, TPI>(s1, c, c1, lane);
-            compute_stage<B, TPI, SAFE>(st, Q, s0, meta_lds, c.n_tokens, c.scale_log2, lane);
-            if (!same1) return c1;
-            const int c2 = claim_chunk(c);
-            const bool same2 = c2 < c.n_chunks && chunk_bits(c, c2) == B;
-            if (same2) issue_stage<B, TPI>(s0, c, c2, lane);
-            compute_stage<B, TPI, SAFE>(st, Q, s1, meta_lds, c.n_tokens, c.scale_log2, lane);
-            if (!same2) return c2;
+        // narrow tiles: a ring of N register stages of TPI tiles each, N - 1 of them in flight
+        Stage<B, TPI> sg[N];
+        issue_stage<B, TPI>(sg[0], c, chunk, lane);
+        if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);
+        int pending = 0, n_live = 1, head = 0;
+        // (the run is left by jumps, not by flags: a flag-guarded chain of steps would give the control-flow
+        //  graph paths from a step straight back to itself, and the wait counts are derived from that graph)
+#pragma unroll
+        for (int i = 1; i + 1 < N; ++i) {  // fill the ring
+            pending = claim_chunk(c);
+            if (!(pending < c.n_chunks && chunk_bits(c, pending) == B)) goto drain;
+            issue_stage<B, TPI>(sg[i], c, pending, lane);
+            n_live = i + 1;
         }
+        for (;;) {
+#pragma unroll
+            for (int k = 0; k < N; ++k) {
+                pending = claim_chunk(c);
+                if (!(pending < c.n_chunks && chunk_bits(c, pending) == B)) { head = k; goto drain; }
+                issue_stage<B, TPI>(sg[(k + N - 1) % N], c, pending, lane);
+                compute_stage<B, TPI, SAFE>(st, Q, sg[k], meta_lds, c.n_tokens, c.scale_log2, lane);
+            }
+        }
+    drain:
+        // end of the run: the stages still in flight are sg[head], sg[head + 1], ... (n_live of them); bring
+        // them to the front and compute them in order
+#pragma unroll
+        for (int h = 1; h < N; ++h) {
+            if (head == h) {
+                Stage<B, TPI> tmp[N - 1];
+#pragma unroll
+                for (int i = 0; i + 1 < N; ++i) tmp[i] = sg[(h + i) % N];
+#pragma unroll
+                for (int i = 0; i + 1 < N; ++i) sg[i] = tmp[i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i + 1 < N; ++i)
+            if (i < n_live) compute_stage<B, TPI, SAFE>(st, Q, sg[i], meta_lds, c.n_tokens, c.scale_log2, lane);
+        return pending;
     }
 }
 
@@ -663,7 +702,7 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
     u32x4* const desc_lds = sh.desc;
     uint8_t* const meta_lds = sh.meta;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int j = lane >> 4, n = lane & 15;
     const int split = blockIdx.x, unit = blockIdx.y;
     const int g = P.gqa;
@@ -724,10 +763,10 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
         while (c < ctx.n_chunks) {
             const int bits = chunk_bits(ctx, c);
             switch (bits) {
-                case 16: c = run_chunks<16, 1, false>(st, Q, q_lds, ctx, c, my_meta, lane); break;
-                case 8: c = run_chunks<8, 1, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
-                case 4: c = run_chunks<4, 2, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
-                default: c = run_chunks<2, 2, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
+                case 16: c = run_chunks<16, 1, 2, false>(st, Q, q_lds, ctx, c, my_meta, lane); break;
+                case 8: c = run_chunks<8, 1, 2, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
+                case 4: c = run_chunks<4, 2, KVQ_RING_4BIT, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
+                default: c = run_chunks<2, 2, KVQ_RING_2BIT, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
             }
         }
     }
