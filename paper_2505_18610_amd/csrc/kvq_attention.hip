@@ -606,64 +606,97 @@ __device__ inline float load_agent(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Merge of the split partials of one unit by 256 threads.  lds: >= (2 * 128 * 16 + 16) floats of scratch.
-// Every thread's global loads are independent of each other, so the whole merge costs about three memory
-// round trips: (m, l) of all splits, then the partial outputs (16 splits per batch), then the store.
+// Merge of the split partials of one unit by a whole workgroup (nthreads = 256 or 512).  Threads work in
+// slots of 32 (one head, 4 channels each); when there are more slots than heads the splits are dealt to
+// several slot groups that work side by side and are combined through LDS, so every thread's global loads are
+// independent of each other and the whole merge is one memory round trip plus the store.
+// lds: >= (nthreads / 32) * 32 * 6 floats of scratch.  Contains barriers: call it with the whole workgroup.
 template <bool AGENT>
-__device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, int nthreads) {
+__device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, int nthreads, float* lds) {
     const int g = P.gqa, ns = P.n_splits;
     const int b = unit / P.n_kv_heads, hk = unit - b * P.n_kv_heads;
     const float* po = P.part_o + (size_t)unit * ns * 16 * KVQ_D;
     const float* pml = P.part_ml + (size_t)unit * ns * 32;
-    // thread -> (head, 4 channels); every load below is independent of every other, so the merge is one memory
-    // round trip: each thread fetches the (m, l) pairs of its head and its slice of every partial output, then
-    // combines them in registers (splits are taken 16 at a time)
-    const int d4 = tid & 31;
-    for (int head = tid >> 5; head < g; head += nthreads >> 5) {
+    const int slots = nthreads >> 5;
+    const int hpp = min(g, slots);               // heads per pass
+    const int G = max(1, min(slots / hpp, ns));  // slot groups sharing the splits of one head
+    const int slot = tid >> 5, d4 = tid & 31;
+    const int sgi = slot / hpp, hh = slot - sgi * hpp;
+    for (int h0 = 0; h0 < g; h0 += hpp) {
+        const int head = h0 + hh;
+        const bool active = sgi < G && head < g;
         float M = -INFINITY, L = 0.f;
         float4v acc = {0.f, 0.f, 0.f, 0.f};
-        for (int s0 = 0; s0 < ns; s0 += 16) {
-            float4v v[16];
-            float ms[16], ls[16];
+        if (active) {
+            for (int s0 = sgi; s0 < ns; s0 += 16 * G) {  // this thread's splits: sgi, sgi + G, ...
+                float4v v[16];
+                float ms[16], ls[16];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const int sp = min(s0 + k, ns - 1);
-                const float* src = po + ((size_t)sp * 16 + head) * KVQ_D + 4 * d4;
-                if (AGENT) {
-                    ms[k] = load_agent(pml + sp * 32 + head);
-                    ls[k] = load_agent(pml + sp * 32 + 16 + head);
-                    v[k][0] = load_agent(src); v[k][1] = load_agent(src + 1);
-                    v[k][2] = load_agent(src + 2); v[k][3] = load_agent(src + 3);
-                } else {
-                    ms[k] = pml[sp * 32 + head];
-                    ls[k] = pml[sp * 32 + 16 + head];
-                    v[k] = *reinterpret_cast<const float4v*>(src);
+                for (int k = 0; k < 16; ++k) {
+                    const int sp = s0 + k * G;
+                    ms[k] = -INFINITY; ls[k] = 0.f; v[k] = float4v{0.f, 0.f, 0.f, 0.f};
+                    if (sp < ns) {
+                        const float* src = po + ((size_t)sp * 16 + head) * KVQ_D + 4 * d4;
+                        if (AGENT) {
+                            ms[k] = load_agent(pml + sp * 32 + head);
+                            ls[k] = load_agent(pml + sp * 32 + 16 + head);
+                            v[k][0] = load_agent(src); v[k][1] = load_agent(src + 1);
+                            v[k][2] = load_agent(src + 2); v[k][3] = load_agent(src + 3);
+                        } else {
+                            ms[k] = pml[sp * 32 + head];
+                            ls[k] = pml[sp * 32 + 16 + head];
+                            v[k] = *reinterpret_cast<const float4v*>(src);
+                        }
+                    }
                 }
-            }
-            float Mb = M;
+                float Mb = M;
 #pragma unroll
-            for (int k = 0; k < 16; ++k)
-                if (s0 + k < ns) Mb = fmaxf(Mb, ms[k]);
-            const float carry = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mb);
-            acc *= carry;
-            L *= carry;
+                for (int k = 0; k < 16; ++k)
+                    if (s0 + k * G < ns) Mb = fmaxf(Mb, ms[k]);
+                const float carry = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mb);
+                acc *= carry;
+                L *= carry;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                if (s0 + k < ns) {
-                    const float f = (ms[k] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms[k] - Mb);
-                    L += ls[k] * f;
-                    acc += v[k] * f;
+                for (int k = 0; k < 16; ++k) {
+                    if (s0 + k * G < ns) {
+                        const float f = (ms[k] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms[k] - Mb);
+                        L += ls[k] * f;
+                        acc += v[k] * f;
+                    }
                 }
+                M = Mb;
             }
-            M = Mb;
         }
-        const float inv = 1.0f / L;
-        size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + 4 * d4;
+        if (G > 1) {  // combine the slot groups (fixed order: group 0, 1, ...)
+            float* rec = lds + (size_t)((sgi * hpp + hh) * 32 + d4) * 6;
+            if (active && sgi > 0) {
+                rec[0] = M; rec[1] = L; rec[2] = acc[0]; rec[3] = acc[1]; rec[4] = acc[2]; rec[5] = acc[3];
+            }
+            __syncthreads();
+            if (active && sgi == 0) {
+                float Mt = M;
+                for (int k = 1; k < G; ++k) Mt = fmaxf(Mt, lds[(size_t)((k * hpp + hh) * 32 + d4) * 6]);
+                const float f0 = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mt);
+                acc *= f0;
+                L *= f0;
+                for (int k = 1; k < G; ++k) {
+                    const float* r = lds + (size_t)((k * hpp + hh) * 32 + d4) * 6;
+                    const float f = (r[0] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(r[0] - Mt);
+                    L += r[1] * f;
+                    acc += float4v{r[2], r[3], r[4], r[5]} * f;
+                }
+            }
+            if (h0 + hpp < g) __syncthreads();  // the records are reused by the next pass
+        }
+        if (active && sgi == 0) {
+            const float inv = 1.0f / L;
+            size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + 4 * d4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float r = acc[i] * inv;
-            if (P.out_fp32) static_cast<float*>(P.out)[oi + i] = r;
-            else static_cast<_Float16*>(P.out)[oi + i] = (_Float16)r;
+            for (int i = 0; i < 4; ++i) {
+                float r = acc[i] * inv;
+                if (P.out_fp32) static_cast<float*>(P.out)[oi + i] = r;
+                else static_cast<_Float16*>(P.out)[oi + i] = (_Float16)r;
+            }
         }
     }
 }
@@ -857,7 +890,7 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
     __syncthreads();
     KVQ_STAMP(4);
     if (!is_last) return;
-    merge_splits<true>(P, unit, tid, KVQ_ATTN_THREADS);
+    merge_splits<true>(P, unit, tid, KVQ_ATTN_THREADS, &red_o[0][0]);
     if (tid == 0) __hip_atomic_store(&P.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     KVQ_STAMP(5);
 }
@@ -869,8 +902,10 @@ __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const K
     else attention_body<false>(P, sh);
 }
 
-__global__ __launch_bounds__(256) void kvq_merge_kernel(const KvqAttnParams P) {
-    merge_splits<false>(P, blockIdx.x, threadIdx.x, 256);
+// Same thread count as the attention kernel, so both merge variants add in the same order.
+__global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_merge_kernel(const KvqAttnParams P) {
+    __shared__ float lds[(KVQ_ATTN_THREADS / 32) * 32 * 6];
+    merge_splits<false>(P, blockIdx.x, threadIdx.x, KVQ_ATTN_THREADS, lds);
 }
 
 }  // namespace
@@ -886,7 +921,7 @@ hipError_t kvq_launch_attention(const KvqAttnParams& p, int units, hipStream_t s
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.n_splits > 1 && !p.fused_merge) {
-        hipLaunchKernelGGL(kvq_merge_kernel, dim3(units), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(kvq_merge_kernel, dim3(units), dim3(KVQ_ATTN_THREADS), 0, s, p);
         e = hipGetLastError();
     }
     return e;
