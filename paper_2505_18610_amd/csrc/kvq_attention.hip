@@ -20,6 +20,7 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -606,97 +607,112 @@ __device__ inline float load_agent(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Merge of the split partials of one unit by a whole workgroup (nthreads = 256 or 512).  Threads work in
-// slots of 32 (one head, 4 channels each); when there are more slots than heads the splits are dealt to
-// several slot groups that work side by side and are combined through LDS, so every thread's global loads are
-// independent of each other and the whole merge is one memory round trip plus the store.
-// lds: >= (nthreads / 32) * 32 * 6 floats of scratch.  Contains barriers: call it with the whole workgroup.
+__device__ inline float2v load_pair(const float* p, bool agent) {  // 8 bytes at p (8-byte aligned)
+    if (agent) {
+        const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+        return float2v{__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32))};
+    }
+    return *reinterpret_cast<const float2v*>(p);
+}
+
+#define KVQ_MERGE_LDS_FLOATS (KVQ_MAX_SPLITS * 16 * 3 + 16 + (KVQ_ATTN_THREADS / 32) * 32 * 4)
+
+// Merge of the split partials of one unit by a workgroup of KVQ_ATTN_THREADS threads.  Threads work in 16 slots
+// of 32 (one head, 4 channels per thread); with fewer than 16 heads the splits of a head are dealt to several
+// slot groups.  Every global load is issued before the first one is waited for, so the merge costs one memory
+// round trip, three barriers and the store.  Per split the partials hold (max, sum) pairs per head and the
+// un-normalised output rows.  lds: KVQ_MERGE_LDS_FLOATS floats.  Call it with the whole workgroup.
 template <bool AGENT>
-__device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, int nthreads, float* lds) {
+__device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, float* lds) {
     const int g = P.gqa, ns = P.n_splits;
     const int b = unit / P.n_kv_heads, hk = unit - b * P.n_kv_heads;
     const float* po = P.part_o + (size_t)unit * ns * 16 * KVQ_D;
     const float* pml = P.part_ml + (size_t)unit * ns * 32;
-    const int slots = nthreads >> 5;
-    const int hpp = min(g, slots);               // heads per pass
-    const int G = max(1, min(slots / hpp, ns));  // slot groups sharing the splits of one head
+    float* ml_lds = lds;                               // [split][16] (m, l)
+    float* f_lds = lds + KVQ_MAX_SPLITS * 32;          // [split][16] weight of the split in the merged sum
+    float* invl_lds = f_lds + KVQ_MAX_SPLITS * 16;     // [16]
+    float* rec_lds = invl_lds + 16;                    // [slot][32][4]
+    const int slots = KVQ_ATTN_THREADS >> 5;           // 16 >= g
+    const int G = max(1, min(slots / g, ns));          // slot groups sharing the splits of one head
     const int slot = tid >> 5, d4 = tid & 31;
-    const int sgi = slot / hpp, hh = slot - sgi * hpp;
-    for (int h0 = 0; h0 < g; h0 += hpp) {
-        const int head = h0 + hh;
-        const bool active = sgi < G && head < g;
-        float M = -INFINITY, L = 0.f;
-        float4v acc = {0.f, 0.f, 0.f, 0.f};
-        if (active) {
-            for (int s0 = sgi; s0 < ns; s0 += 16 * G) {  // this thread's splits: sgi, sgi + G, ...
-                float4v v[16];
-                float ms[16], ls[16];
+    const int sgi = slot / g, head = slot - sgi * g;
+    const bool active = sgi < G;
+    // ---- every load of the first round: (m, l) pairs, then this thread's share of the partial outputs
+    float2v mlr[4];
 #pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    const int sp = s0 + k * G;
-                    ms[k] = -INFINITY; ls[k] = 0.f; v[k] = float4v{0.f, 0.f, 0.f, 0.f};
-                    if (sp < ns) {
-                        const float* src = po + ((size_t)sp * 16 + head) * KVQ_D + 4 * d4;
-                        if (AGENT) {
-                            ms[k] = load_agent(pml + sp * 32 + head);
-                            ls[k] = load_agent(pml + sp * 32 + 16 + head);
-                            v[k][0] = load_agent(src); v[k][1] = load_agent(src + 1);
-                            v[k][2] = load_agent(src + 2); v[k][3] = load_agent(src + 3);
-                        } else {
-                            ms[k] = pml[sp * 32 + head];
-                            ls[k] = pml[sp * 32 + 16 + head];
-                            v[k] = *reinterpret_cast<const float4v*>(src);
-                        }
-                    }
-                }
-                float Mb = M;
+    for (int k = 0; k < 4; ++k) {
+        const int e = tid + k * KVQ_ATTN_THREADS;      // pair index: split * g + head
+        mlr[k] = float2v{-INFINITY, 0.f};
+        if (e < ns * g) { const int sp = e / g, h = e - sp * g; mlr[k] = load_pair(pml + sp * 32 + 2 * h, AGENT); }
+    }
+    float2v v[16][2];
 #pragma unroll
-                for (int k = 0; k < 16; ++k)
-                    if (s0 + k * G < ns) Mb = fmaxf(Mb, ms[k]);
-                const float carry = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mb);
-                acc *= carry;
-                L *= carry;
+    for (int k = 0; k < 16; ++k) {
+        const int sp = sgi + k * G;
+        v[k][0] = v[k][1] = float2v{0.f, 0.f};
+        if (active && sp < ns) {
+            const float* src = po + ((size_t)sp * 16 + head) * KVQ_D + 4 * d4;
+            v[k][0] = load_pair(src, AGENT);
+            v[k][1] = load_pair(src + 2, AGENT);
+        }
+    }
 #pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    if (s0 + k * G < ns) {
-                        const float f = (ms[k] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms[k] - Mb);
-                        L += ls[k] * f;
-                        acc += v[k] * f;
-                    }
-                }
-                M = Mb;
+    for (int k = 0; k < 4; ++k) {
+        const int e = tid + k * KVQ_ATTN_THREADS;
+        if (e < ns * g) { const int sp = e / g, h = e - sp * g; ml_lds[(sp * 16 + h) * 2] = mlr[k][0]; ml_lds[(sp * 16 + h) * 2 + 1] = mlr[k][1]; }
+    }
+    __syncthreads();
+    // ---- per head (slot = head, 32 lanes over the splits): common maximum, weights, denominator
+    if (slot < g) {
+        float m = -INFINITY;
+        for (int sp = d4; sp < ns; sp += 32) m = fmaxf(m, ml_lds[(sp * 16 + slot) * 2]);
+#pragma unroll
+        for (int o = 1; o < 32; o <<= 1) m = fmaxf(m, __shfl_xor(m, o));
+        float l = 0.f;
+        for (int sp = d4; sp < ns; sp += 32) {
+            const float ms = ml_lds[(sp * 16 + slot) * 2];
+            const float f = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m);
+            f_lds[sp * 16 + slot] = f;
+            l += ml_lds[(sp * 16 + slot) * 2 + 1] * f;
+        }
+        // fixed-order tree: the same for both merge variants and from launch to launch
+#pragma unroll
+        for (int o = 1; o < 32; o <<= 1) l += __shfl_xor(l, o);
+        if (d4 == 0) invl_lds[slot] = 1.0f / l;
+    }
+    __syncthreads();
+    // ---- weighted sum of this thread's splits (further rounds only beyond 16 * G splits)
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+    if (active) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int sp = sgi + k * G;
+            if (sp < ns) {
+                const float f = f_lds[sp * 16 + head];
+                acc += float4v{v[k][0][0], v[k][0][1], v[k][1][0], v[k][1][1]} * f;
             }
         }
-        if (G > 1) {  // combine the slot groups (fixed order: group 0, 1, ...)
-            float* rec = lds + (size_t)((sgi * hpp + hh) * 32 + d4) * 6;
-            if (active && sgi > 0) {
-                rec[0] = M; rec[1] = L; rec[2] = acc[0]; rec[3] = acc[1]; rec[4] = acc[2]; rec[5] = acc[3];
-            }
-            __syncthreads();
-            if (active && sgi == 0) {
-                float Mt = M;
-                for (int k = 1; k < G; ++k) Mt = fmaxf(Mt, lds[(size_t)((k * hpp + hh) * 32 + d4) * 6]);
-                const float f0 = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mt);
-                acc *= f0;
-                L *= f0;
-                for (int k = 1; k < G; ++k) {
-                    const float* r = lds + (size_t)((k * hpp + hh) * 32 + d4) * 6;
-                    const float f = (r[0] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(r[0] - Mt);
-                    L += r[1] * f;
-                    acc += float4v{r[2], r[3], r[4], r[5]} * f;
-                }
-            }
-            if (h0 + hpp < g) __syncthreads();  // the records are reused by the next pass
+        for (int sp = sgi + 16 * G; sp < ns; sp += G) {
+            const float* src = po + ((size_t)sp * 16 + head) * KVQ_D + 4 * d4;
+            const float2v a = load_pair(src, AGENT), c2 = load_pair(src + 2, AGENT);
+            acc += float4v{a[0], a[1], c2[0], c2[1]} * f_lds[sp * 16 + head];
         }
-        if (active && sgi == 0) {
-            const float inv = 1.0f / L;
-            size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + 4 * d4;
+    }
+    if (G > 1) {  // combine the slot groups in a fixed order
+        if (active && sgi > 0) *reinterpret_cast<float4v*>(rec_lds + (size_t)(slot * 32 + d4) * 4) = acc;
+        __syncthreads();
+        if (active && sgi == 0)
+            for (int k = 1; k < G; ++k) acc += *reinterpret_cast<const float4v*>(rec_lds + (size_t)((k * g + head) * 32 + d4) * 4);
+    }
+    if (active && sgi == 0) {
+        const float inv = invl_lds[head];
+        const size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + 4 * d4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float r = acc[i] * inv;
-                if (P.out_fp32) static_cast<float*>(P.out)[oi + i] = r;
-                else static_cast<_Float16*>(P.out)[oi + i] = (_Float16)r;
-            }
+        for (int i = 0; i < 4; ++i) {
+            const float r = acc[i] * inv;
+            if (P.out_fp32) static_cast<float*>(P.out)[oi + i] = r;
+            else static_cast<_Float16*>(P.out)[oi + i] = (_Float16)r;
         }
     }
 }
@@ -714,7 +730,7 @@ __device__ unsigned long long kvq_dbg[1024 * 8];
 // LDS of one workgroup.
 struct AttnShared {
     __attribute__((aligned(16))) _Float16 q[16 * KVQ_D];
-    float red_o[4][16 * KVQ_OPAD];
+    float red_o[4][16 * KVQ_OPAD];  // wavefront reduction slab, later the scratch of the split merge
     float red_m[KVQ_ATTN_WAVES][16];
     float red_l[KVQ_ATTN_WAVES][16];
     int is_last;
@@ -722,6 +738,8 @@ struct AttnShared {
     u32x4 desc[KVQ_DESC_CACHE];
     __attribute__((aligned(16))) uint8_t meta[KVQ_ATTN_WAVES * KVQ_WAVE_LDS_BYTES];
 };
+
+static_assert(4 * 16 * KVQ_OPAD >= KVQ_MERGE_LDS_FLOATS, "the reduction slab doubles as merge scratch");
 
 // The whole kernel for one of the two V paths (SAFE: overflow-proof, see accumulate_tile).
 template <bool SAFE>
@@ -872,8 +890,8 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
         for (int w = 1; w < KVQ_ATTN_WAVES; ++w) Mh = fmaxf(Mh, red_m[w][tid]);
 #pragma unroll
         for (int w = 0; w < KVQ_ATTN_WAVES; ++w) Lh += red_l[w][tid];
-        if (P.fused_merge) { store_agent(pml + tid, Mh); store_agent(pml + 16 + tid, Lh); }
-        else { pml[tid] = Mh; pml[16 + tid] = Lh; }
+        if (P.fused_merge) { store_agent(pml + 2 * tid, Mh); store_agent(pml + 2 * tid + 1, Lh); }
+        else { pml[2 * tid] = Mh; pml[2 * tid + 1] = Lh; }
     }
     if (!P.fused_merge) return;
 
@@ -890,7 +908,7 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
     __syncthreads();
     KVQ_STAMP(4);
     if (!is_last) return;
-    merge_splits<true>(P, unit, tid, KVQ_ATTN_THREADS, &red_o[0][0]);
+    merge_splits<true>(P, unit, tid, &red_o[0][0]);
     if (tid == 0) __hip_atomic_store(&P.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     KVQ_STAMP(5);
 }
@@ -904,8 +922,8 @@ __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const K
 
 // Same thread count as the attention kernel, so both merge variants add in the same order.
 __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_merge_kernel(const KvqAttnParams P) {
-    __shared__ float lds[(KVQ_ATTN_THREADS / 32) * 32 * 6];
-    merge_splits<false>(P, blockIdx.x, threadIdx.x, KVQ_ATTN_THREADS, lds);
+    __shared__ float lds[KVQ_MERGE_LDS_FLOATS];
+    merge_splits<false>(P, blockIdx.x, threadIdx.x, lds);
 }
 
 }  // namespace

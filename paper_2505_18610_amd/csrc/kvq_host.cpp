@@ -100,7 +100,7 @@ struct kvq_cache {
     int splits_override = 0;
     int fused_merge = 1;
     int deterministic = 0;
-    int tile_cost[4] = {100, 160, 260, 450};  // relative kernel time of one 2/4/8/16-bit tile (measured)
+    int tile_cost[4] = {100, 145, 250, 300};  // relative kernel time of one 2/4/8/16-bit tile (measured)
     int target_workgroups = 256;
 
     uint64_t bpth(int bits) const {

@@ -19,7 +19,7 @@ struct KvqAttnParams {
     const void* q;             // fp16 [batch, n_q_heads, 128]
     void* out;                 // [batch, n_q_heads, 128] fp16 or fp32
     float* part_o;             // [unit][split][16][128] un-normalised partial outputs
-    float* part_ml;            // [unit][split][2][16] running max (log2 units) and sum
+    float* part_ml;            // [unit][split][16] pairs (running max in log2 units, sum)
     uint32_t* counters;        // [unit] arrival counters of the fused merge (kept at zero between launches)
     const uint32_t* flags;     // [0] bit 0: some V scale of the cache is >= 256 (set by the quantizing kernels)
     int32_t n_tokens;
