@@ -18,7 +18,8 @@
  *   - Errors are reported as kvq_status_t; argument, state and budget errors are detected on the host before
  *     anything is enqueued and leave the cache unchanged.  Nothing throws or aborts across this boundary.
  *   - All sequences of a batch have the same length and share one page table per block.
- *   - head_dim is 128, group is 32 channels, 1 <= n_q_heads / n_kv_heads <= 16.
+ *   - head_dim is 128, group is 32, 64 or 128 channels (128 is the paper's setting, Sec. 4.1.2),
+ *     1 <= n_q_heads / n_kv_heads <= 16.
  */
 #ifndef KVQ_H
 #define KVQ_H
@@ -51,7 +52,7 @@ typedef struct {
     int32_t n_q_heads;     /* query heads; query head h reads KV head h / (n_q_heads / n_kv_heads)        */
     int32_t n_kv_heads;
     int32_t head_dim;      /* must be 128                                                                 */
-    int32_t group;         /* quantization group: consecutive channels of one token of one head; 32       */
+    int32_t group;         /* quantization group: consecutive channels of one token of one head; 32 | 64 | 128 */
     int32_t max_tokens;    /* maximum context length per sequence                                         */
     int32_t window;        /* most recent tokens kept at 16 bits (Sec. 4.1.2); multiple of page_tokens    */
     int32_t n_sink;        /* first tokens kept at 16 bits (Sec. 4.1.2); multiple of page_tokens          */

@@ -130,7 +130,7 @@ uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 bool check_config(const kvq_config_t* c) {
     if (!c) return false;
     if (c->n_layers < 1 || c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1) return false;
-    if (c->head_dim != KVQ_D || c->group != KVQ_G) return false;
+    if (c->head_dim != KVQ_D || (c->group != 32 && c->group != 64 && c->group != 128)) return false;
     if (c->n_q_heads % c->n_kv_heads != 0 || c->n_q_heads / c->n_kv_heads > KVQ_MAX_GQA) return false;
     if (c->page_tokens < 32 || c->page_tokens % 32 != 0) return false;
     if (c->max_tokens < 1) return false;
@@ -260,7 +260,7 @@ kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, 
         kvq_status_t st = upload(c, jd, jobs.data(), jobs.size() * sizeof(KvqRequantJob), s);
         hipError_t e = hipSuccess;
         if (st == KVQ_OK) {
-            e = (from == 16) ? kvq_launch_quant16(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), s)
+            e = (from == 16) ? kvq_launch_quant16(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), c->cfg.group, s)
                              : kvq_launch_shrink(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), s);
         }
         if (st != KVQ_OK || e != hipSuccess) {
@@ -487,7 +487,7 @@ kvq_status_t kvq_quantize_append(kvq_cache_t* c, int32_t layer, const void* k_de
             two[1] = c->desc(L.pages[(size_t)pg1]);
         }
         if (kvq_launch_append(e, c->arena, c->table_dev(layer), k_dev, v_dev, t_old, n_new, c->tpp, c->units,
-                              by_arg ? two : nullptr, pg0, c->flags_dev(), s) != hipSuccess)
+                              by_arg ? two : nullptr, pg0, c->flags_dev(), c->cfg.group, s) != hipSuccess)
             return KVQ_E_HIP;
     }
     if (!evicted.empty()) {
@@ -655,8 +655,12 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* c, int32_t layer, int32_t seg
                 }
                 if (b < 16) {
                     const uint16_t* m = reinterpret_cast<const uint16_t*>(meta.data() + tslot * KVQ_META_TILE_BYTES);
-                    for (int g = 0; g < KVQ_NGRP; ++g) {
-                        size_t oi = ((size_t)u * n_seg + tok_seg) * KVQ_NGRP + g;
+                    // the device keeps one (S, Z) per run of 32 channels (a group of 64 or 128 channels repeats
+                    // its pair); the canonical format has one per group
+                    const int gspan = c->cfg.group / KVQ_G, ngrp = KVQ_D / c->cfg.group;
+                    for (int gg = 0; gg < ngrp; ++gg) {
+                        const int g = gg * gspan;
+                        size_t oi = ((size_t)u * n_seg + tok_seg) * ngrp + gg;
                         if (which == KVQ_WHICH_K) { os[oi] = m[t * 4 + g]; oz[oi] = m[128 + t * 4 + g]; }
                         else { os[oi] = m[256 + kvq_vmeta_index(t, g)]; oz[oi] = m[384 + kvq_vmeta_index(t, g)]; }
                     }

@@ -180,14 +180,19 @@ __device__ inline uint32_t pk_max_u(uint32_t a, uint32_t b) {
 // Fast path: t = (x - Z) * (1/S) differs from the correctly rounded quotient by < 6.1e-5 for codes up to 255,
 // so rint(t) is the required code unless t lies within 1.3e-4 of a half-integer; if any lane of the wavefront
 // sees such a value the whole step is redone with the IEEE division the definition asks for.
+// gspan = G / 32: a quantization group of G = 64 or 128 channels spans 2 or 4 neighbouring owner lanes (the
+// owners of one token's four 32-channel runs are lanes 4k .. 4k+3), which then share min, max and so (S, Z).
 template <int B>
-__device__ inline void quantize_owner(const uint32_t (&w)[16], float (&codes)[32], uint16_t* S, uint16_t* Z) {
+__device__ inline void quantize_owner(const uint32_t (&w)[16], float (&codes)[32], uint16_t* S, uint16_t* Z,
+                                      int gspan) {
     constexpr int levels = (1 << B) - 1;
     uint32_t mn2 = w[0], mx2 = w[0];
 #pragma unroll
     for (int k = 1; k < 16; ++k) { mn2 = pk_min_u(mn2, w[k]); mx2 = pk_max_u(mx2, w[k]); }
-    const float mn = fminf(h2f((uint16_t)(mn2 & 0xffff)), h2f((uint16_t)(mn2 >> 16)));
-    const float mx = fmaxf(h2f((uint16_t)(mx2 & 0xffff)), h2f((uint16_t)(mx2 >> 16)));
+    float mn = fminf(h2f((uint16_t)(mn2 & 0xffff)), h2f((uint16_t)(mn2 >> 16)));
+    float mx = fmaxf(h2f((uint16_t)(mx2 & 0xffff)), h2f((uint16_t)(mx2 >> 16)));
+    if (gspan >= 2) { mn = fminf(mn, __shfl_xor(mn, 1)); mx = fmaxf(mx, __shfl_xor(mx, 1)); }
+    if (gspan >= 4) { mn = fminf(mn, __shfl_xor(mn, 2)); mx = fmaxf(mx, __shfl_xor(mx, 2)); }
     float Sf;
     group_params(mn, mx, levels, S, Z, &Sf);
     const float rcp = (Sf == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(Sf);
@@ -430,7 +435,7 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
                                                           const uint16_t* __restrict__ k_in,
                                                           const uint16_t* __restrict__ v_in, int t_old,
                                                           int n_new, int tpp, int tile0, KvqAppendPages ap,
-                                                          uint32_t* __restrict__ flags) {
+                                                          uint32_t* __restrict__ flags, int gspan) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
@@ -458,7 +463,7 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
         }
         float codes[32];
         uint16_t S, Z;
-        quantize_owner<B>(w, codes, &S, &Z);  // tokens that are not new quantize zeros: codes 0, S = Z = 0
+        quantize_owner<B>(w, codes, &S, &Z, gspan);  // tokens that are not new quantize zeros: codes 0, S = Z = 0
         note_large_v_scale(flags, which, S);
         scatter_codes(lds, which, tl, grp, codes);
         if (tok >= t_old) store_meta_owner(meta, which, tl, grp, S, Z);
@@ -496,7 +501,7 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
 template <int B>
 __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ arena,
                                                          const KvqRequantJob* __restrict__ jobs, int tpp,
-                                                         uint32_t* __restrict__ flags) {
+                                                         uint32_t* __restrict__ flags, int gspan) {
     __shared__ __attribute__((aligned(16))) uint8_t raw_lds[32 * 128 * 2];
     __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
@@ -545,7 +550,7 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
         }
         float codes[32];
         uint16_t S, Z;
-        quantize_owner<B>(w, codes, &S, &Z);
+        quantize_owner<B>(w, codes, &S, &Z, gspan);
         note_large_v_scale(flags, which, S);
         scatter_codes(lds, which, tl, grp, codes);
         store_meta_owner(meta, which, tl, grp, S, Z);
@@ -639,7 +644,8 @@ __global__ void kvq_fill_u32_kernel(uint32_t* dst, uint32_t value, size_t n) {
 
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
-                             const KvqPageDesc* first_two, int first_page, uint32_t* flags, hipStream_t s) {
+                             const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group, hipStream_t s) {
+    const int gspan = group / KVQ_G;
     int tile0 = t_old / KVQ_TILE_TOKENS;
     int tile1 = (t_old + n_new + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
     dim3 grid(2 * (tile1 - tile0), units), block(64);
@@ -651,9 +657,9 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
     ap.d[1] = first_two ? first_two[1] : KvqPageDesc{0, 0, 0, 0};
     switch (bits) {
         case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap); break;
-        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags); break;
-        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags); break;
-        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags); break;
+        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan); break;
+        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan); break;
+        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -671,12 +677,12 @@ hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* 
 }
 
 hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
-                              int tiles_per_page, int units, uint32_t* flags, hipStream_t s) {
+                              int tiles_per_page, int units, uint32_t* flags, int group, hipStream_t s) {
     dim3 grid(2 * n_jobs * tiles_per_page, units), block(64);
     switch (dst_bits) {
-        case 8: hipLaunchKernelGGL(kvq_quant16_kernel<8>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
-        case 4: hipLaunchKernelGGL(kvq_quant16_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
-        case 2: hipLaunchKernelGGL(kvq_quant16_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
+        case 8: hipLaunchKernelGGL(kvq_quant16_kernel<8>, grid, block, 0, s, arena, jobs, tiles_per_page, flags, group / KVQ_G); break;
+        case 4: hipLaunchKernelGGL(kvq_quant16_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page, flags, group / KVQ_G); break;
+        case 2: hipLaunchKernelGGL(kvq_quant16_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page, flags, group / KVQ_G); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

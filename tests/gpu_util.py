@@ -14,14 +14,14 @@ def dev(x: np.ndarray) -> torch.Tensor:
 
 
 def make_pair(n_layers, B, Hq, Hkv, max_tokens, P, budgets=None, fbits=None, window=0, n_sink=0, policy=0,
-              meta=1, payload_bytes=None):
+              meta=1, payload_bytes=None, group=32):
     budgets = budgets or [1 << 50] * n_layers
     fbits = fbits or [2] * n_layers
     ocfg = CacheConfig(n_layers, B, Hq, Hkv, page_tokens=P, max_tokens=max_tokens, window=window, n_sink=n_sink,
-                       policy=policy, count_metadata_in_budget=meta)
+                       policy=policy, count_metadata_in_budget=meta, group=group)
     oc = OracleCache(ocfg, budgets, fbits)
     cfg = kq.KvqConfig(n_layers, B, Hq, Hkv, max_tokens, page_tokens=P, window=window, n_sink=n_sink, policy=policy,
-                       count_metadata_in_budget=meta)
+                       count_metadata_in_budget=meta, group=group)
     if payload_bytes is None:
         pages = (max_tokens + P - 1) // P + 4
         payload_bytes = n_layers * pages * P * B * Hkv * 512 + (64 << 20)

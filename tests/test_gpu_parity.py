@@ -123,6 +123,34 @@ def test_shrink_of_directly_quantized_tiers():
     check_attention(oc, gc, 0, kvq_synth.make_q(104, 0, B, 2 * H, 339))
 
 
+@pytest.mark.parametrize("group", [64, 128])
+def test_group_sizes_64_and_128(group):
+    """Quantization groups of 64 and 128 channels (128 is the paper's setting, Sec. 4.1.2): ragged appends at every
+    width, the fp16 tier taken down the whole 16 -> 8 -> 4 -> 2 chain, byte accounting with D/G metadata pairs per
+    token-head, attention over the result.  Codes, scales and zero points are compared bit for bit in the canonical
+    [token][D/G] format."""
+    B, H, T, P = 2, 2, 331, 64
+    K, V = kvq_synth.make_kv(120 + group, 0, B, H, 0, T)
+    for bits in (8, 4, 2):
+        oc, gc = make_pair(1, B, 3 * H, H, 512, P, group=group)
+        t = 0
+        for n in (1, 63, 64, 130, 73):
+            append_both(oc, gc, 0, K[:, :, t:t + n], V[:, :, t:t + n], bits)
+            t += n
+        assert t == T
+        assert_same_cache(oc, gc, 0)
+        assert gc.kvq_cache_describe(0)[1] == T * B * H * bytes_per_token_head(bits, 128, group, True)
+        check_attention(oc, gc, 0, kvq_synth.make_q(120 + group, 0, B, 3 * H, T - 1))
+    oc, gc = make_pair(1, B, 3 * H, H, 512, P, group=group)
+    append_both(oc, gc, 0, K[:, :, :256], V[:, :, :256], 16)
+    q = kvq_synth.make_q(120 + group, 0, B, 3 * H, 255)
+    for want_bits in (8, 4, 2):
+        assert gc.kvq_progressive_requant(0, segment=0) == oc.requant(0, segment=0)
+        assert gc.kvq_cache_describe(0)[0] == [(0, 256, want_bits)]
+        assert_same_cache(oc, gc, 0)
+        check_attention(oc, gc, 0, q)
+
+
 @pytest.mark.parametrize("policy,W,sink,fbit", [(POLICY_PAPER, 0, 0, 2), (POLICY_PAPER, 64, 32, 2),
                                                 (POLICY_OLDEST_FIRST, 32, 0, 2)])
 def test_progressive_decode_run_matches_oracle(policy, W, sink, fbit):

@@ -35,7 +35,7 @@ def test_bytes_per_token_head_matches_oracle_and_paper_shapes():
 
 def test_invalid_configs_and_arguments():
     good = dict(n_layers=1, batch=1, n_q_heads=8, n_kv_heads=2, max_tokens=1024, page_tokens=128)
-    for bad in (dict(head_dim=64), dict(group=128), dict(page_tokens=48), dict(n_q_heads=7), dict(window=100),
+    for bad in (dict(head_dim=64), dict(group=16), dict(group=96), dict(page_tokens=48), dict(n_q_heads=7), dict(window=100),
                 dict(n_sink=5), dict(policy=7), dict(n_q_heads=64, n_kv_heads=2)):
         cfg = kq.KvqConfig(**{**good, **bad})
         assert kq.kvq_arena_bytes(cfg, 0) == 0
@@ -64,12 +64,12 @@ def test_invalid_configs_and_arguments():
     assert kq.kvq_status_string(kq.KVQ_E_OOM) != kq.kvq_status_string(kq.KVQ_OK)
 
 
-def _pair(policy, P, W, sink, budget, fbit, meta=1, Tmax=4096, B=2, H=2):
+def _pair(policy, P, W, sink, budget, fbit, meta=1, Tmax=4096, B=2, H=2, group=32):
     ocfg = CacheConfig(1, B, 2 * H, H, page_tokens=P, max_tokens=Tmax, window=W, n_sink=sink, policy=policy,
-                       count_metadata_in_budget=meta)
+                       count_metadata_in_budget=meta, group=group)
     oc = OracleCache(ocfg, [budget], [fbit])
     cfg = kq.KvqConfig(1, B, 2 * H, H, Tmax, page_tokens=P, window=W, n_sink=sink, policy=policy,
-                       count_metadata_in_budget=meta)
+                       count_metadata_in_budget=meta, group=group)
     gc = kq.KvqCache(cfg, [budget], [fbit], arena=None, arena_bytes=1 << 30)
     return oc, gc
 
@@ -120,6 +120,35 @@ def test_bookkeeping_matches_oracle_on_random_decode_runs(policy, W, sink, fbit)
                 assert gc.kvq_progressive_requant(0, reserve_tokens=n) == done
         _same_state(oc, gc)
     assert exhausted and t > 400
+
+
+@pytest.mark.parametrize("group", [64, 128])
+def test_bookkeeping_with_larger_groups(group):
+    """Groups of 64 / 128 channels change the bytes per token-head (fewer scale / zero-point pairs), hence every
+    budget decision; the paper's own setting is 128 (Sec. 4.1.2)."""
+    P, B, H, fbit = 32, 2, 2, 2
+    budget = B * H * (200 * bytes_per_token_head(fbit, 128, group, True) + P * 512)
+    oc, gc = _pair(POLICY_PAPER, P, 0, 0, budget, fbit, Tmax=512, B=B, H=H, group=group)
+    K, V = kvq_synth.make_kv(78, 0, B, H, 0, 512, rope_base=None)
+    t, exhausted = 0, False
+    while t < 512 and not exhausted:
+        n = min(17, 512 - t)
+        try:
+            oc.append(0, K[:, :, t:t + n], V[:, :, t:t + n])
+            gc.kvq_quantize_append(0, None, None, n_new=n)
+            t += n
+        except BudgetError:
+            with pytest.raises(kq.KvqError):
+                gc.kvq_quantize_append(0, None, None, n_new=n)
+            try:
+                done = oc.requant(0, reserve_tokens=n)
+                assert gc.kvq_progressive_requant(0, reserve_tokens=n) == done
+            except BudgetError:
+                with pytest.raises(kq.KvqError):
+                    gc.kvq_progressive_requant(0, reserve_tokens=n)
+                exhausted = True
+        _same_state(oc, gc)
+    assert exhausted and 200 <= t < 512
 
 
 def test_explicit_construction_and_segment_requant_match_oracle():
