@@ -125,11 +125,13 @@ __device__ inline u32x4 load_stream16(const uint8_t* p) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 }
 
+// tile: wavefront-uniform address (scalar registers); lane_off = 16 * lane, computed once per kernel.  Written
+// this way the loads need no per-load address registers (scalar base + one loop-invariant offset register).
 template <int NDW>
-__device__ inline void load_string(const uint8_t* tile, int lane, uint32_t (&w)[NDW]) {
+__device__ inline void load_string(const uint8_t* tile, uint32_t lane_off, uint32_t (&w)[NDW]) {
 #pragma unroll
     for (int c = 0; c < NDW / 4; ++c) {
-        u32x4 v = load_stream16(tile + (c * 64 + lane) * 16);
+        u32x4 v = load_stream16(tile + lane_off + c * 1024);
         w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
     }
 }
@@ -442,15 +444,28 @@ __device__ inline void compute_stage(WaveState& st, const QOps& Q, const Stage<B
     if constexpr (B < 16) wave_lds_sync();
 }
 
+// A claimed chunk, resolved to addresses; every member is wavefront-uniform (scalar registers).
+struct Claim {
+    int tile;             // first tile
+    int nt;               // tiles (1 .. tpc), adjacent in one page
+    uint32_t bits;        // width of the page; 0: nothing left in this window
+    const uint8_t* code;  // K string of the first tile; its V string follows, then the next tile's pair
+    const uint8_t* meta;  // metadata of the first tile; the next tile's follows
+};
+
 // What a wavefront needs to find and claim work inside its workgroup's tile range.  The range is cut into
 // chunks of tpc consecutive tiles (2, or 1 when pages hold an odd number of tiles); the 8 wavefronts of the
 // workgroup claim chunks from a counter in LDS, so wavefronts that get more issue slots simply do more chunks.
+//   next      - resolved claim, the chunk whose loads are issued next
+//   claim_v   - result of the claim after it (LDS atomic in flight while a stage is computed)
+//   desc_v    - descriptor read of a claimed chunk, chunk index in desc_chunk
 struct RunCtx {
     const uint8_t* arena;
     const u32x4* desc_lds;   // descriptors of pages page0 .. of the current descriptor window
     unsigned* claim_ctr;     // LDS: next unclaimed chunk
     int page0;
     int tpp;
+    uint32_t tpp_magic;      // ceil(2^32 / tpp): tile / tpp = mulhi(tile, magic) for tile < 2^22, tpp <= 2^10
     int unit;
     int n_tokens;
     int lo, hi;              // tile range of the current descriptor window
@@ -458,130 +473,158 @@ struct RunCtx {
     int n_chunks;
     int next_static;         // >= 0: deterministic mode, this wavefront takes chunks next_static, +8, +16, ...
     float scale_log2;
+    uint32_t lane_off;       // 16 * lane
+    Claim next;
+    int desc_chunk;
+    u32x4 desc_v;
+    int claim_v;
 };
 
-__device__ inline int claim_chunk(RunCtx& c) {
+__device__ inline void start_claim(RunCtx& c) {
     if (c.next_static >= 0) {
-        const int v = c.next_static;
-        c.next_static = __builtin_amdgcn_readfirstlane(v + KVQ_ATTN_WAVES);  // provably wavefront-uniform
-        return v;
+        c.claim_v = c.next_static;
+        c.next_static = __builtin_amdgcn_readfirstlane(c.next_static + KVQ_ATTN_WAVES);  // provably uniform
+        return;
     }
-    unsigned v = 0;
-    if ((threadIdx.x & 63) == 0) v = __hip_atomic_fetch_add(c.claim_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    return (int)__builtin_amdgcn_readfirstlane(v);
+    int v = 0;
+    if ((threadIdx.x & 63) == 0) v = (int)__hip_atomic_fetch_add(c.claim_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    c.claim_v = v;
 }
-__device__ inline int chunk_tile(const RunCtx& c, int chunk) { return c.lo + chunk * c.tpc; }
-__device__ inline int chunk_size(const RunCtx& c, int chunk) { return min(c.tpc, c.hi - chunk_tile(c, chunk)); }
-__device__ inline int chunk_bits(const RunCtx& c, int chunk) {
-    return __builtin_amdgcn_readfirstlane(c.desc_lds[chunk_tile(c, chunk) / c.tpp - c.page0].z);
-}
+__device__ inline int finish_claim(const RunCtx& c) { return __builtin_amdgcn_readfirstlane(c.claim_v); }
 
-template <int B>
-__device__ inline void tile_addr(const RunCtx& c, int tile, const uint8_t** code, const uint8_t** meta) {
-    tile = __builtin_amdgcn_readfirstlane(tile);  // one tile per wavefront: keep its address in scalar registers
-    const int page = tile / c.tpp, tip = tile - page * c.tpp;
-    const u32x4 d = c.desc_lds[page - c.page0];
-    const uint32_t code_off = __builtin_amdgcn_readfirstlane(d.x);
-    const uint32_t meta_off = __builtin_amdgcn_readfirstlane(d.y);
+__device__ inline int page_of_tile(const RunCtx& c, int tile) {
+    return c.tpp == 1 ? tile : (int)__umulhi((uint32_t)tile, c.tpp_magic);
+}
+__device__ inline void start_desc(RunCtx& c, int chunk) {
+    chunk = __builtin_amdgcn_readfirstlane(chunk);
+    c.desc_chunk = chunk;
+    const int tile = c.lo + min(chunk, c.n_chunks - 1) * c.tpc;  // past the end: any valid slot, ignored later
+    c.desc_v = c.desc_lds[page_of_tile(c, tile) - c.page0];
+}
+__device__ inline Claim finish_desc(const RunCtx& c) {
+    Claim r;
+    const int chunk = c.desc_chunk;
+    r.tile = c.lo + chunk * c.tpc;
+    r.nt = min(c.tpc, c.hi - r.tile);
+    const uint32_t code_off = __builtin_amdgcn_readfirstlane(c.desc_v.x);
+    const uint32_t meta_off = __builtin_amdgcn_readfirstlane(c.desc_v.y);
+    const uint32_t bits = __builtin_amdgcn_readfirstlane(c.desc_v.z);
+    r.bits = chunk < c.n_chunks ? bits : 0u;
+    const int page = page_of_tile(c, r.tile), tip = r.tile - page * c.tpp;
     const uint64_t tslot = (uint64_t)c.unit * c.tpp + tip;
-    *code = c.arena + (uint64_t)code_off * 256u + tslot * 2 * (512u * B);
-    *meta = c.arena + (uint64_t)meta_off * 256u + tslot * KVQ_META_TILE_BYTES;
+    r.code = c.arena + (uint64_t)code_off * 256u + tslot * (1024u * bits);
+    r.meta = c.arena + (uint64_t)meta_off * 256u + tslot * KVQ_META_TILE_BYTES;
+    return r;
+}
+// Claims the next chunk; between begin and end there should be a stage's worth of arithmetic, which hides the
+// LDS atomic (the descriptor read that follows it is short).  A wavefront commits itself to one chunk beyond the
+// ones in flight, not more: chunks claimed early are chunks nobody else can take when the range runs out.
+__device__ inline void advance_begin(RunCtx& c) { start_claim(c); }
+__device__ inline void advance_end(RunCtx& c) {
+    start_desc(c, finish_claim(c));
+    c.next = finish_desc(c);
 }
 
 // Issue every global load of one stage (nothing waits here): the tiles of one chunk; slots the chunk does not
 // fill re-read its first tile and are masked out by their tok0.
 template <int B, int TPI>
-__device__ inline void issue_stage(Stage<B, TPI>& sg, const RunCtx& c, int chunk, int lane) {
-    const int t = chunk_tile(c, chunk), nt = chunk_size(c, chunk);
+__device__ inline void issue_stage(Stage<B, TPI>& sg, const RunCtx& c, const Claim& cl) {
 #pragma unroll
     for (int k = 0; k < TPI; ++k) {
-        const bool real = k < nt;
-        const uint8_t *code, *meta;
-        tile_addr<B>(c, real ? t + k : t, &code, &meta);
-        load_string<2 * B>(code, lane, sg.kw[k]);
-        load_string<2 * B>(code + 512u * B, lane, sg.vw[k]);
-        if constexpr (B < 16) sg.meta[k] = load_stream16(meta + lane * 16);
-        sg.tok0[k] = real ? (t + k) * KVQ_TILE_TOKENS : KVQ_PAD_TOK0;
+        const bool real = k < cl.nt;
+        const uint8_t* code = cl.code + (real ? k : 0) * (1024u * B);
+        const uint8_t* meta = cl.meta + (real ? k : 0) * KVQ_META_TILE_BYTES;
+        load_string<2 * B>(code, c.lane_off, sg.kw[k]);
+        load_string<2 * B>(code + 512u * B, c.lane_off, sg.vw[k]);
+        if constexpr (B < 16) sg.meta[k] = load_stream16(meta + c.lane_off);
+        sg.tok0[k] = real ? (cl.tile + k) * KVQ_TILE_TOKENS : KVQ_PAD_TOK0;
     }
 }
 
-// Process chunk `chunk` (already claimed, width B) and keep claiming and processing chunks while they have the
-// same width, software-pipelined: the loads of the following chunks are in flight while the current one is
-// computed.  Returns the first claimed chunk that was not processed (another width, or past the end of the range).
+// Process the resolved claim c.next (width B) and keep claiming and processing chunks while they have the same
+// width, software-pipelined: the loads of the following chunks are in flight while the current one is computed.
+// Returns with c.next = the first claimed chunk that was not processed (another width, or bits 0 = nothing left).
 //
 // The steady-state path contains no load that is issued conditionally: the wait counts in front of a stage's
 // first use are then exactly "everything issued after it may still be in flight".  (A load under a condition
 // would make the compiler wait for the stricter of the two paths, i.e. drain the prefetch every time.)  The
 // end of a run therefore has code of its own.
 template <int B, int TPI, int N, bool SAFE>
-__device__ inline int run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds, RunCtx& c, int chunk,
-                                 uint8_t* meta_lds, int lane) {
+__device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds, RunCtx& c, uint8_t* meta_lds,
+                                  int lane) {
     set_accumulator_exponent(st, v_exponent<B>(SAFE));
     if constexpr (B >= 8) {
         // wide tiles (8 and 16 KiB): one register stage, tile by tile, K and V staggered (V loads fly during
         // the K product, the next tile's K and metadata loads during the V product)
         uint32_t kw[2 * B], vw[2 * B];
         u32x4 mreg = {0u, 0u, 0u, 0u};
-        const uint8_t *code, *meta;
-        int t = chunk_tile(c, chunk), k = 0, cur = chunk;
-        tile_addr<B>(c, t, &code, &meta);
-        load_string<2 * B>(code, lane, kw);
-        if constexpr (B < 16) mreg = load_stream16(meta + lane * 16);
-        load_string<2 * B>(code + 512u * B, lane, vw);
+        Claim cur = c.next;
+        int k = 0;
+        load_string<2 * B>(cur.code, c.lane_off, kw);
+        if constexpr (B < 16) mreg = load_stream16(cur.meta + c.lane_off);
+        load_string<2 * B>(cur.code + 512u * B, c.lane_off, vw);
         if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);
         for (;;) {
             float s[1][2][4];
             uint32_t pop[1][4];
-            const int tok0[1] = {t * KVQ_TILE_TOKENS};
+            const int tok0[1] = {(cur.tile + k) * KVQ_TILE_TOKENS};
             if constexpr (B < 16) {
                 *reinterpret_cast<u32x4*>(meta_lds + lane * 16) = mreg;
                 wave_lds_sync();
             }
             scores_tile<B>(Q, kw, meta_lds, c.scale_log2, lane, s[0]);
-            int next_t = -1, next_k = 0, next_c = cur, pending = 0;
-            if (k + 1 < chunk_size(c, cur)) {
-                next_t = t + 1; next_k = k + 1;
-            } else {
-                pending = claim_chunk(c);
-                if (pending < c.n_chunks && chunk_bits(c, pending) == B) { next_t = chunk_tile(c, pending); next_c = pending; }
+            const uint8_t *code, *meta;
+            bool more;
+            if (k + 1 < cur.nt) {  // next tile of the same chunk
+                ++k;
+                code = cur.code + k * (1024u * B);
+                meta = cur.meta + k * KVQ_META_TILE_BYTES;
+                more = true;
+            } else {  // a wide tile takes long enough to claim its successor only now
+                advance_begin(c);
+                advance_end(c);
+                more = c.next.bits == B;
+                if (more) { cur = c.next; k = 0; code = cur.code; meta = cur.meta; }
             }
-            if (next_t < 0) {  // last tile of the run
+            if (!more) {  // last tile of the run
                 softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
                 accumulate_tile<B, SAFE>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
                 if constexpr (B < 16) wave_lds_sync();
-                return pending;
+                return;
             }
-            tile_addr<B>(c, next_t, &code, &meta);
-            load_string<2 * B>(code, lane, kw);
-            if constexpr (B < 16) mreg = load_stream16(meta + lane * 16);
+            load_string<2 * B>(code, c.lane_off, kw);
+            if constexpr (B < 16) mreg = load_stream16(meta + c.lane_off);
             softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
             accumulate_tile<B, SAFE>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
             if constexpr (B < 16) wave_lds_sync();
-            load_string<2 * B>(code + 512u * B, lane, vw);
-            t = next_t; k = next_k; cur = next_c;
+            load_string<2 * B>(code + 512u * B, c.lane_off, vw);
         }
     } else {
         // narrow tiles: a ring of N register stages of TPI tiles each, N - 1 of them in flight
         Stage<B, TPI> sg[N];
-        issue_stage<B, TPI>(sg[0], c, chunk, lane);
+        issue_stage<B, TPI>(sg[0], c, c.next);
+        advance_begin(c);
         if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);
-        int pending = 0, n_live = 1, head = 0;
+        advance_end(c);
+        int n_live = 1, head = 0;
         // (the run is left by jumps, not by flags: a flag-guarded chain of steps would give the control-flow
         //  graph paths from a step straight back to itself, and the wait counts are derived from that graph)
 #pragma unroll
         for (int i = 1; i + 1 < N; ++i) {  // fill the ring
-            pending = claim_chunk(c);
-            if (!(pending < c.n_chunks && chunk_bits(c, pending) == B)) goto drain;
-            issue_stage<B, TPI>(sg[i], c, pending, lane);
+            if (c.next.bits != B) goto drain;
+            issue_stage<B, TPI>(sg[i], c, c.next);
             n_live = i + 1;
+            advance_begin(c);
+            advance_end(c);
         }
         for (;;) {
 #pragma unroll
             for (int k = 0; k < N; ++k) {
-                pending = claim_chunk(c);
-                if (!(pending < c.n_chunks && chunk_bits(c, pending) == B)) { head = k; goto drain; }
-                issue_stage<B, TPI>(sg[(k + N - 1) % N], c, pending, lane);
+                if (c.next.bits != B) { head = k; goto drain; }
+                issue_stage<B, TPI>(sg[(k + N - 1) % N], c, c.next);
+                advance_begin(c);
                 compute_stage<B, TPI, SAFE>(st, Q, sg[k], meta_lds, c.n_tokens, c.scale_log2, lane);
+                advance_end(c);
             }
         }
     drain:
@@ -600,7 +643,6 @@ __device__ inline int run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds, 
 #pragma unroll
         for (int i = 0; i + 1 < N; ++i)
             if (i < n_live) compute_stage<B, TPI, SAFE>(st, Q, sg[i], meta_lds, c.n_tokens, c.scale_log2, lane);
-        return pending;
     }
 }
 
@@ -781,7 +823,7 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
         *reinterpret_cast<u32x4*>(&q_lds[head * KVQ_D + c16 * 8]) = qv;
         desc_lds[tid] = dv;
     }
-    if (tid == 0) claim_ctr = 0u;
+    if (tid == 0) claim_ctr = KVQ_ATTN_WAVES;  // the first chunk of every wavefront is its own index
     __syncthreads();
     KVQ_STAMP(1);
     QOps Q;
@@ -799,8 +841,10 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
 
     RunCtx ctx;
     ctx.arena = P.arena; ctx.desc_lds = desc_lds; ctx.claim_ctr = &claim_ctr; ctx.tpp = tpp; ctx.unit = unit;
+    ctx.tpp_magic = P.tpp_magic;
     ctx.n_tokens = P.n_tokens; ctx.scale_log2 = P.scale_log2;
     ctx.tpc = (tpp & 1) ? 1 : 2;
+    ctx.lane_off = (uint32_t)lane * 16u;
     uint8_t* my_meta = meta_lds + wave * KVQ_WAVE_LDS_BYTES;
     if (lane < 8) reinterpret_cast<uint32_t*>(my_meta + KVQ_WAVE_LDS_CONST)[lane] = lane < 4 ? 0x3c003c00u : 0u;
     for (int pc = p_first; pc < p_last; pc += KVQ_DESC_CACHE) {
@@ -808,22 +852,25 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
         if (pc != p_first) {  // further descriptor windows of a very long range
             __syncthreads();
             if (tid < pn) desc_lds[tid] = reinterpret_cast<const u32x4*>(P.table)[pc + tid];
-            if (tid == 0) claim_ctr = 0u;
+            if (tid == 0) claim_ctr = KVQ_ATTN_WAVES;
             __syncthreads();
         }
         ctx.page0 = pc;
         ctx.lo = max(t_begin, pc * tpp);
         ctx.hi = min(t_end, (pc + pn) * tpp);
         ctx.n_chunks = (ctx.hi - ctx.lo + ctx.tpc - 1) / ctx.tpc;
-        ctx.next_static = P.deterministic ? wave : -1;
-        int c = claim_chunk(ctx);
-        while (c < ctx.n_chunks) {
-            const int bits = chunk_bits(ctx, c);
-            switch (bits) {
-                case 16: c = run_chunks<16, 1, 2, false>(st, Q, q_lds, ctx, c, my_meta, lane); break;
-                case 8: c = run_chunks<8, 1, 2, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
-                case 4: c = run_chunks<4, 2, KVQ_RING_4BIT, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
-                default: c = run_chunks<2, 2, KVQ_RING_2BIT, SAFE>(st, Q, q_lds, ctx, c, my_meta, lane); break;
+        if (ctx.n_chunks <= 0) continue;
+        // the first chunk of every wavefront is its own index (the counter starts behind them); from then on
+        // chunks are claimed, always two ahead of the arithmetic
+        ctx.next_static = P.deterministic ? wave + KVQ_ATTN_WAVES : -1;
+        start_desc(ctx, wave);
+        ctx.next = finish_desc(ctx);
+        while (ctx.next.bits != 0u) {
+            switch (ctx.next.bits) {
+                case 16: run_chunks<16, 1, 2, false>(st, Q, q_lds, ctx, my_meta, lane); break;
+                case 8: run_chunks<8, 1, 2, SAFE>(st, Q, q_lds, ctx, my_meta, lane); break;
+                case 4: run_chunks<4, 2, KVQ_RING_4BIT, SAFE>(st, Q, q_lds, ctx, my_meta, lane); break;
+                default: run_chunks<2, 2, KVQ_RING_2BIT, SAFE>(st, Q, q_lds, ctx, my_meta, lane); break;
             }
         }
     }

@@ -132,8 +132,8 @@ bool check_config(const kvq_config_t* c) {
     if (c->n_layers < 1 || c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1) return false;
     if (c->head_dim != KVQ_D || (c->group != 32 && c->group != 64 && c->group != 128)) return false;
     if (c->n_q_heads % c->n_kv_heads != 0 || c->n_q_heads / c->n_kv_heads > KVQ_MAX_GQA) return false;
-    if (c->page_tokens < 32 || c->page_tokens % 32 != 0) return false;
-    if (c->max_tokens < 1) return false;
+    if (c->page_tokens < 32 || c->page_tokens % 32 != 0 || c->page_tokens > 32768) return false;
+    if (c->max_tokens < 1 || c->max_tokens > (1 << 26)) return false;  // tile indices stay below 2^21 (exact magic division)
     if (c->window < 0 || c->window % c->page_tokens != 0) return false;
     if (c->n_sink < 0 || c->n_sink % c->page_tokens != 0) return false;
     if (c->policy != KVQ_POLICY_PAPER && c->policy != KVQ_POLICY_OLDEST_FIRST) return false;
@@ -576,6 +576,7 @@ kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_d
     p.flags = c->flags_dev();
     p.n_tokens = L.T;
     p.tiles_per_page = c->tpp;
+    p.tpp_magic = c->tpp > 1 ? (uint32_t)(((1ull << 32) + (uint64_t)c->tpp - 1) / (uint64_t)c->tpp) : 0u;
     p.gqa = c->gqa;
     p.n_q_heads = c->cfg.n_q_heads;
     p.n_kv_heads = c->cfg.n_kv_heads;

@@ -24,6 +24,7 @@ struct KvqAttnParams {
     const uint32_t* flags;     // [0] bit 0: some V scale of the cache is >= 256 (set by the quantizing kernels)
     int32_t n_tokens;
     int32_t tiles_per_page;
+    uint32_t tpp_magic;        // ceil(2^32 / tiles_per_page) (unused when tiles_per_page == 1)
     int32_t gqa;               // query heads per KV head
     int32_t n_q_heads;
     int32_t n_kv_heads;
