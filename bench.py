@@ -130,7 +130,7 @@ def measure_read_ceiling(kq, torch, cache):
     buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
     buf.fill_(1)
     best = 0.0
-    for wgs in (512, 2048, 8192):
+    for wgs in (512, 2048, 4096, 8192, 16384):
         for rep in range(3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()

@@ -121,6 +121,23 @@ __device__ inline void load_chunks(const uint8_t* tile, int lane, uint32_t (&str
         str[4 * c] = v.x; str[4 * c + 1] = v.y; str[4 * c + 2] = v.z; str[4 * c + 3] = v.w;
     }
 }
+// Streaming variants for the page-at-a-time kernels, which read and write every byte exactly once.
+template <int B>
+__device__ inline void load_chunks_stream(const uint8_t* tile, int lane, uint32_t (&str)[2 * B]) {
+#pragma unroll
+    for (int c = 0; c < B / 2; ++c) {
+        u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + (c * 64 + lane) * 16));
+        str[4 * c] = v.x; str[4 * c + 1] = v.y; str[4 * c + 2] = v.z; str[4 * c + 3] = v.w;
+    }
+}
+template <int B>
+__device__ inline void store_chunks_stream(uint8_t* tile, int lane, const uint32_t (&str)[2 * B]) {
+#pragma unroll
+    for (int c = 0; c < B / 2; ++c) {
+        u32x4 v = {str[4 * c], str[4 * c + 1], str[4 * c + 2], str[4 * c + 3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(tile + (c * 64 + lane) * 16));
+    }
+}
 
 // keep_k: bit sub set = the token of sub-tile `sub` of this lane must keep its stored value
 __device__ inline void store_meta_k(uint8_t* meta, int lane, const uint16_t (&S)[8], const uint16_t (&Z)[8],
@@ -516,7 +533,7 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
     uint8_t* meta = arena + (uint64_t)jb.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
     {
         uint32_t in[32];
-        load_chunks<16>(src, lane, in);
+        load_chunks_stream<16>(src, lane, in);
         if (!which) {
 #pragma unroll
             for (int p = 0; p < 8; ++p) {  // piece (sub, grp): 8 consecutive channels of one token
@@ -558,7 +575,7 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
     wave_sync_lds();
     uint32_t str[2 * B];
     gather_string<B>(lds, which, lane, str);
-    store_chunks<B>(dst, lane, str);
+    store_chunks_stream<B>(dst, lane, str);
 }
 
 // ------------------------------------------------------------------------------- Equivalent Right Shift
@@ -600,7 +617,7 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
 #pragma unroll
     for (int kv = 0; kv < 2; ++kv) {
         uint32_t in[4 * B];
-        load_chunks<2 * B>(src + kv * (512u * 2 * B), lane, in);
+        load_chunks_stream<2 * B>(src + kv * (512u * 2 * B), lane, in);
         uint32_t out[2 * B];
 #pragma unroll
         for (int d = 0; d < 2 * B; ++d) {
@@ -609,7 +626,7 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
             else
                 out[d] = shrink_8_to_4(in[2 * d]) | (shrink_8_to_4(in[2 * d + 1]) << 16);
         }
-        store_chunks<B>(dst + kv * (512u * B), lane, out);
+        store_chunks_stream<B>(dst + kv * (512u * B), lane, out);
     }
     const float f = (float)((1 << B) + 1);
     uint32_t nk = (uint32_t)f2h_rn(h2f((uint16_t)(sk & 0xffff)) * f) | ((uint32_t)f2h_rn(h2f((uint16_t)(sk >> 16)) * f) << 16);
@@ -620,7 +637,7 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
     note_large_v_scale(flags, 1, (uint16_t)(nv >> 16));
 }
 
-// Plain streaming read (16 bytes per lane, 4 loads in flight): the practical HBM read ceiling of the device,
+// Plain streaming read (16 bytes per lane, 4 non-temporal loads in flight): the practical HBM read ceiling of the device,
 // against which the attention kernel's bandwidth is put next to the published peak.
 __global__ __launch_bounds__(256) void kvq_stream_read_kernel(const u32x4* __restrict__ p, size_t n,
                                                               uint32_t* __restrict__ sink) {
@@ -628,10 +645,11 @@ __global__ __launch_bounds__(256) void kvq_stream_read_kernel(const u32x4* __res
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     u32x4 acc = {0u, 0u, 0u, 0u};
     for (; i + 3 * stride < n; i += 4 * stride) {
-        u32x4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        u32x4 a = __builtin_nontemporal_load(p + i), b = __builtin_nontemporal_load(p + i + stride);
+        u32x4 c = __builtin_nontemporal_load(p + i + 2 * stride), d = __builtin_nontemporal_load(p + i + 3 * stride);
         acc ^= a ^ b ^ c ^ d;
     }
-    for (; i < n; i += stride) acc ^= p[i];
+    for (; i < n; i += stride) acc ^= __builtin_nontemporal_load(p + i);
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;  // practically never: keeps the loads alive
 }
 
