@@ -66,7 +66,9 @@ def build_state(kq, torch, w, steps_total):
                 torch.cuda.synchronize()
                 ms = e0.elapsed_time(e1)
                 moved = n * units * (512 + kq.kvq_bytes_per_token_head(bits))
-                append_stats[f"bulk_{bits}bit_GBps"] = round(moved / ms / 1e6, 1)
+                # one-shot construction appends of this workload's tiers; a tier of a few hundred tokens is a
+                # launch-bound call, so the token count is part of the key
+                append_stats[f"bulk_{bits}bit_{n}tok_GBps"] = round(moved / ms / 1e6, 1)
             t += n
         del k, v
     torch.cuda.synchronize()
