@@ -257,11 +257,13 @@ kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, 
             jobs[i].pad = 0;
         }
         KvqRequantJob* jd = reinterpret_cast<KvqRequantJob*>(c->arena + c->jobs_off);
-        kvq_status_t st = upload(c, jd, jobs.data(), jobs.size() * sizeof(KvqRequantJob), s);
+        const bool by_arg = jobs.size() <= (size_t)KVQ_JOBS_BY_ARG;  // short lists ride in the kernel arguments
+        kvq_status_t st = by_arg ? KVQ_OK : upload(c, jd, jobs.data(), jobs.size() * sizeof(KvqRequantJob), s);
         hipError_t e = hipSuccess;
         if (st == KVQ_OK) {
-            e = (from == 16) ? kvq_launch_quant16(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), c->cfg.group, s)
-                             : kvq_launch_shrink(to, c->arena, jd, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), s);
+            const KvqRequantJob* jh = by_arg ? jobs.data() : nullptr;
+            e = (from == 16) ? kvq_launch_quant16(to, c->arena, jd, jh, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), c->cfg.group, s)
+                             : kvq_launch_shrink(to, c->arena, jd, jh, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), s);
         }
         if (st != KVQ_OK || e != hipSuccess) {
             for (auto& w : low) {

@@ -13,6 +13,15 @@ struct KvqRequantJob {        // one page to re-quantize
     uint32_t pad;
 };
 
+// Up to KVQ_JOBS_BY_ARG jobs ride in the kernel arguments (no table upload in front of the launch);
+// longer lists are read from the uploaded table.
+#define KVQ_JOBS_BY_ARG 192
+struct KvqJobArgs {
+    int32_t n;  // 0: read the table
+    int32_t pad[3];
+    KvqRequantJob jobs[KVQ_JOBS_BY_ARG];
+};
+
 struct KvqAttnParams {
     const uint8_t* arena;
     const KvqPageDesc* table;  // this block's page table
@@ -40,10 +49,12 @@ struct KvqAttnParams {
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
                              const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group, hipStream_t s);
-hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
-                             int tiles_per_page, int units, uint32_t* flags, hipStream_t s);
-hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
-                              int tiles_per_page, int units, uint32_t* flags, int group, hipStream_t s);
+hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs_dev,
+                             const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
+                             uint32_t* flags, hipStream_t s);
+hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs_dev,
+                              const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
+                              uint32_t* flags, int group, hipStream_t s);
 hipError_t kvq_launch_stream_read(const void* buf, size_t bytes, int n_workgroups, uint32_t* sink, hipStream_t s);
 hipError_t kvq_launch_fill_u32(uint32_t* dst, uint32_t value, size_t n, hipStream_t s);
 

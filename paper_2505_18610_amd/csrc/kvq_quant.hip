@@ -518,7 +518,8 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
 template <int B>
 __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ arena,
                                                          const KvqRequantJob* __restrict__ jobs, int tpp,
-                                                         uint32_t* __restrict__ flags, int gspan) {
+                                                         uint32_t* __restrict__ flags, int gspan,
+                                                         const KvqJobArgs ja) {
     __shared__ __attribute__((aligned(16))) uint8_t raw_lds[32 * 128 * 2];
     __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
@@ -526,7 +527,7 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
     const int idx = blockIdx.x >> 1;
     const int job = idx / tpp, tip = idx - job * tpp;
     const int unit = blockIdx.y;
-    const KvqRequantJob jb = jobs[job];
+    const KvqRequantJob jb = ja.n ? ja.jobs[job] : jobs[job];
     const uint64_t tslot = (uint64_t)unit * tpp + tip;
     const uint8_t* src = arena + (uint64_t)jb.src_code_off256 * 256u + (tslot * 2 + which) * (512u * 16);
     uint8_t* dst = arena + (uint64_t)jb.dst_code_off256 * 256u + (tslot * 2 + which) * (512u * B);
@@ -602,11 +603,11 @@ __device__ inline uint32_t shrink_8_to_4(uint32_t w) {  // 4 bytes -> 4 nibbles 
 template <int B>
 __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ arena,
                                                         const KvqRequantJob* __restrict__ jobs, int tpp,
-                                                        uint32_t* __restrict__ flags) {
+                                                        uint32_t* __restrict__ flags, const KvqJobArgs ja) {
     const int lane = threadIdx.x;
     const int job = blockIdx.x / tpp, tip = blockIdx.x - job * tpp;
     const int unit = blockIdx.y;
-    const KvqRequantJob jb = jobs[job];
+    const KvqRequantJob jb = ja.n ? ja.jobs[job] : jobs[job];
     const uint64_t tslot = (uint64_t)unit * tpp + tip;
     const uint8_t* src = arena + (uint64_t)jb.src_code_off256 * 256u + tslot * 2 * (512u * 2 * B);
     uint8_t* dst = arena + (uint64_t)jb.dst_code_off256 * 256u + tslot * 2 * (512u * B);
@@ -683,24 +684,38 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
     return hipGetLastError();
 }
 
-hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
-                             int tiles_per_page, int units, uint32_t* flags, hipStream_t s) {
+static void fill_job_args(KvqJobArgs& ja, const KvqRequantJob* jobs_host, int n_jobs) {
+    ja.n = (jobs_host && n_jobs <= KVQ_JOBS_BY_ARG) ? n_jobs : 0;
+    ja.pad[0] = ja.pad[1] = ja.pad[2] = 0;
+    for (int i = 0; i < ja.n; ++i) ja.jobs[i] = jobs_host[i];
+}
+
+// jobs_host != nullptr and n_jobs <= KVQ_JOBS_BY_ARG: the list travels in the kernel arguments and jobs_dev is
+// not read; otherwise jobs_dev must already hold the list (in stream order).
+hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs_dev,
+                             const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
+                             uint32_t* flags, hipStream_t s) {
     dim3 grid(n_jobs * tiles_per_page, units), block(64);
+    KvqJobArgs ja;
+    fill_job_args(ja, jobs_host, n_jobs);
     switch (dst_bits) {
-        case 4: hipLaunchKernelGGL(kvq_shrink_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
-        case 2: hipLaunchKernelGGL(kvq_shrink_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page, flags); break;
+        case 4: hipLaunchKernelGGL(kvq_shrink_kernel<4>, grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, ja); break;
+        case 2: hipLaunchKernelGGL(kvq_shrink_kernel<2>, grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, ja); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs, int n_jobs,
-                              int tiles_per_page, int units, uint32_t* flags, int group, hipStream_t s) {
+hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs_dev,
+                              const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
+                              uint32_t* flags, int group, hipStream_t s) {
     dim3 grid(2 * n_jobs * tiles_per_page, units), block(64);
+    KvqJobArgs ja;
+    fill_job_args(ja, jobs_host, n_jobs);
     switch (dst_bits) {
-        case 8: hipLaunchKernelGGL(kvq_quant16_kernel<8>, grid, block, 0, s, arena, jobs, tiles_per_page, flags, group / KVQ_G); break;
-        case 4: hipLaunchKernelGGL(kvq_quant16_kernel<4>, grid, block, 0, s, arena, jobs, tiles_per_page, flags, group / KVQ_G); break;
-        case 2: hipLaunchKernelGGL(kvq_quant16_kernel<2>, grid, block, 0, s, arena, jobs, tiles_per_page, flags, group / KVQ_G); break;
+        case 8: hipLaunchKernelGGL(kvq_quant16_kernel<8>, grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, group / KVQ_G, ja); break;
+        case 4: hipLaunchKernelGGL(kvq_quant16_kernel<4>, grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, group / KVQ_G, ja); break;
+        case 2: hipLaunchKernelGGL(kvq_quant16_kernel<2>, grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, group / KVQ_G, ja); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -104,6 +104,20 @@ def test_requant_chain_bit_exact():
     assert e.value.status == kq.KVQ_E_STATE
 
 
+def test_requant_of_more_pages_than_ride_in_the_kernel_arguments():
+    """Short job lists travel in the kernel arguments, long ones through the uploaded table: 210 pages in one call."""
+    B, H, P = 1, 1, 32
+    T = 210 * P
+    K, V = kvq_synth.make_kv(105, 0, B, H, 0, T)
+    oc, gc = make_pair(1, B, 2 * H, H, T, P)
+    append_both(oc, gc, 0, K, V, 16)
+    for want_bits in (8, 4, 2):
+        assert gc.kvq_progressive_requant(0, segment=0) == oc.requant(0, segment=0) == 210
+        assert gc.kvq_cache_describe(0)[0] == [(0, T, want_bits)]
+        assert_same_cache(oc, gc, 0)
+    check_attention(oc, gc, 0, kvq_synth.make_q(105, 0, B, 2 * H, T - 1))
+
+
 def test_shrink_of_directly_quantized_tiers():
     """8 -> 4 and 4 -> 2 starting from tokens that entered at 8 / 4 bits, with a partly filled last page."""
     B, H, P = 1, 2, 64
