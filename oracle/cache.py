@@ -11,7 +11,7 @@ from __future__ import annotations
 import dataclasses
 import numpy as np
 
-from .quantizer import (quantize, dequantize, pack_codes, shrink_codes, shrink_scale,
+from .quantizer import (quantize, dequantize, pack_codes, shrink_step, SHIFT_EQUIVALENT,
                         bytes_per_token_head)
 from .attention import decode_attention_fp64
 
@@ -41,6 +41,7 @@ class CacheConfig:
     page_tokens: int = 128
     policy: int = POLICY_PAPER
     count_metadata_in_budget: int = 1
+    shift_strategy: int = SHIFT_EQUIVALENT   # how 2b -> b steps treat codes, S and Z (Sec. 4.3.1)
 
 
 class _Page:
@@ -194,7 +195,8 @@ class OracleCache:
 
         From 16 bits: direct quantization of the stored fp16 values (Eq. 1-2); by the
         appendix theorem this is what an integer 16-bit tier followed by Eq. 3 would give.
-        From 2b to b bits: Eq. 3 on the codes, S_b = (2^b + 1) S_2b, Z unchanged.
+        From 2b to b bits: Eq. 3 on the codes, S_b = (2^b + 1) S_2b, Z unchanged (or one of the two
+        ablation strategies of Sec. 4.3.1 when the configuration asks for it).
         """
         G = self.cfg.group
         if pg.bits == 16:
@@ -203,8 +205,8 @@ class OracleCache:
             pg.k = pg.v = None
         else:
             assert target_bits * 2 == pg.bits
-            pg.kc, pg.vc = shrink_codes(pg.kc, target_bits), shrink_codes(pg.vc, target_bits)
-            pg.ks, pg.vs = shrink_scale(pg.ks, target_bits), shrink_scale(pg.vs, target_bits)
+            pg.kc, pg.ks, pg.kz = shrink_step(pg.kc, pg.ks, pg.kz, target_bits, self.cfg.shift_strategy)
+            pg.vc, pg.vs, pg.vz = shrink_step(pg.vc, pg.vs, pg.vz, target_bits, self.cfg.shift_strategy)
         pg.bits = target_bits
 
     def requant(self, layer, segment=-1, reserve_tokens=0):
@@ -262,6 +264,16 @@ class OracleCache:
             else:
                 ks.append(dequantize(p.kc, p.ks, p.kz, G)); vs.append(dequantize(p.vc, p.vs, p.vz, G))
         return np.concatenate(ks, 2), np.concatenate(vs, 2)
+
+    def reconstruction_sq_error(self, layer, K, V):
+        """(sum over all cached elements of (K_hat - K)^2, the same for V) in fp64: how far the de-quantized cache
+        is from the fp16 tensors K, V [B, H, T, D] it was built from (the measure used to compare the bit-width
+        shrinking strategies of Sec. 4.3.1 without a model)."""
+        Kh, Vh = self.dequantized(layer)
+        T = Kh.shape[2]
+        dk = Kh - K[:, :, :T].astype(np.float64)
+        dv = Vh - V[:, :, :T].astype(np.float64)
+        return float(np.sum(dk * dk)), float(np.sum(dv * dv))
 
     def attention(self, layer, q, scale=None):
         K, V = self.dequantized(layer)

@@ -64,6 +64,35 @@ def shrink_scale(S2b: np.ndarray, b: int) -> np.ndarray:
     return out
 
 
+SHIFT_EQUIVALENT, SHIFT_DIRECT, SHIFT_MODIFIED = 0, 1, 2
+
+
+def shrink_step(x2b: np.ndarray, S2b: np.ndarray, Z2b: np.ndarray, b: int, strategy: int):
+    """One 2b -> b bit-width shrinking step under one of the three strategies of the ablation in Sec. 4.3.1.
+
+    Equivalent Right Shift (the method's own, Eq. 3): X_b = ((2^{2b} - 2^b + 1)(X_{2b} + 2^{b-1})) >> 3b,
+        S_b = (2^b + 1) S_{2b}, Z_b = Z_{2b}.
+    Direct Right Shift: X_b = X_{2b} >> b (the upper b bits), S_b = (2^b + 1) S_{2b}, Z_b = Z_{2b}: the dynamic
+        range [Z, Z + (2^{2b} - 1) S_{2b}] is preserved.
+    Modified Right Shift: X_b = X_{2b} >> b, S_b = 2^b S_{2b}, Z_b = Z_{2b} + (S_b - S_{2b}) / 2: a b-bit level is the
+        mean of the 2b-bit levels that share its upper b bits.
+    S and Z are fp16: products and the sum are formed in fp32 (the products are exact there) and rounded to
+    nearest-even into fp16.  Returns (X_b, S_b, Z_b).
+    """
+    assert b in (8, 4, 2) and strategy in (SHIFT_EQUIVALENT, SHIFT_DIRECT, SHIFT_MODIFIED)
+    Sf, Zf = S2b.astype(np.float32), Z2b.astype(np.float32)
+    if strategy == SHIFT_EQUIVALENT:
+        return shrink_codes(x2b, b), shrink_scale(S2b, b), Z2b.copy()
+    xb = (x2b.astype(np.uint64) >> np.uint64(b)).astype(x2b.dtype)
+    if strategy == SHIFT_DIRECT:
+        return xb, shrink_scale(S2b, b), Z2b.copy()
+    Sb32 = Sf * np.float32(1 << b)
+    half = np.float32(0.5) * (Sb32 - Sf)          # = S_2b (2^b - 1) / 2, exact in fp32
+    Sb, Zb = Sb32.astype(np.float16), (Zf + half).astype(np.float16)
+    assert np.all(np.isfinite(Sb)) and np.all(np.isfinite(Zb))
+    return xb, Sb, Zb
+
+
 def pack_codes(codes: np.ndarray, b: int) -> np.ndarray:
     """Canonical packing: element i of a row sits at bit offset (i*b) mod 8 of byte (i*b)//8, low bits first."""
     per = 8 // b

@@ -132,3 +132,31 @@ def test_width_change_inside_page_is_rejected_and_budget_failure_leaves_state():
     c.append(0, K[:, :, 64:100], V[:, :, 64:100], 4)
     assert c.segments(0) == [(0, 64, 8), (64, 100, 4)]
     assert c.bytes_used(0) == 64 * 288 + 36 * 160
+
+
+def test_shift_strategy_chains_and_reconstruction_error():
+    """The cache applies the configured strategy to every 2b -> b step; the reconstruction error of a cache is the
+    squared distance of its de-quantized content from the tensors it was built from (zero for the 16-bit tier, and
+    within the round-trip bound S/2 per element after direct quantization)."""
+    from oracle import (quantize, dequantize, shrink_step, SHIFT_EQUIVALENT, SHIFT_DIRECT, SHIFT_MODIFIED)
+    import kvq_synth
+    B, H, T, P = 1, 2, 128, 64
+    K, V = kvq_synth.make_kv(55, 0, B, H, 0, T)
+    for st in (SHIFT_EQUIVALENT, SHIFT_DIRECT, SHIFT_MODIFIED):
+        oc = OracleCache(CacheConfig(1, B, 2 * H, H, page_tokens=P, max_tokens=T, shift_strategy=st), [1 << 40], [2])
+        oc.append(0, K, V, 16)
+        assert oc.reconstruction_sq_error(0, K, V) == (0.0, 0.0)
+        oc.requant(0, segment=0)                                   # 16 -> 8: Eq. 1-2 whatever the strategy
+        kc, ks, kz = quantize(K, 8, 32)
+        ek, ev = oc.reconstruction_sq_error(0, K, V)
+        assert ek == pytest.approx(float(np.sum((dequantize(kc, ks, kz, 32) - K.astype(np.float64)) ** 2)))
+        bound = np.sum((np.repeat(ks.astype(np.float64), 32, -1) * (0.5 + 255 * 2.0 ** -11)) ** 2)
+        assert ek <= bound
+        for b in (4, 2):
+            oc.requant(0, segment=0)
+            kc, ks, kz = shrink_step(kc, ks, kz, b, st)
+            codes, S, Z = oc.export_segment(0, 0, "K")
+            assert np.array_equal(S, ks) and np.array_equal(Z, kz)
+            ek2, _ = oc.reconstruction_sq_error(0, K, V)
+            assert ek2 == pytest.approx(float(np.sum((dequantize(kc, ks, kz, 32) - K.astype(np.float64)) ** 2)))
+            assert ek2 > ek

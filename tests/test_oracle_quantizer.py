@@ -177,3 +177,55 @@ def test_table1_byte_counts():
     assert [bytes_per_token_head(b, 128, 32, True) for b in (16, 8, 4, 2)] == [512, 288, 160, 96]
     assert [bytes_per_token_head(b, 128, 128, True) for b in (16, 8, 4, 2)] == [512, 264, 136, 72]
     assert [bytes_per_token_head(b, 128, 32, False) for b in (16, 8, 4, 2)] == [512, 256, 128, 64]
+
+
+# ---------------------------------------------------------------- the ablation's two other shift strategies (Sec. 4.3.1)
+def test_direct_and_modified_shift_properties_stated_by_the_paper():
+    """Direct Right Shift keeps the upper b bits and the dynamic range (Z_b = Z_2b, S_b = (2^b + 1) S_2b);
+    Modified Right Shift maps levels that share their upper b bits to their mean (S_b = 2^b S_2b,
+    Z_b = Z_2b + (S_b - S_2b) / 2).  Checked in exact rationals for every 2b-bit code."""
+    from fractions import Fraction
+    from oracle import shrink_step, SHIFT_DIRECT, SHIFT_MODIFIED
+    S2, Z2 = Fraction(3, 64), Fraction(-7, 8)          # exactly representable in fp16
+    for b in (4, 2):
+        codes = np.arange(1 << (2 * b), dtype=np.uint8 if b < 8 else np.uint16)
+        S16, Z16 = np.array([float(S2)], np.float16), np.array([float(Z2)], np.float16)
+        xd, Sd, Zd = shrink_step(codes, S16, Z16, b, SHIFT_DIRECT)
+        xm, Sm, Zm = shrink_step(codes, S16, Z16, b, SHIFT_MODIFIED)
+        assert np.array_equal(xd, codes >> b) and np.array_equal(xm, codes >> b)
+        Sd_, Zd_, Sm_, Zm_ = (Fraction(float(v[0])) for v in (Sd, Zd, Sm, Zm))
+        assert Sd_ == ((1 << b) + 1) * S2 and Zd_ == Z2
+        # dynamic range kept: the top and bottom levels de-quantize to the same values as before
+        assert Zd_ + int(xd[-1]) * Sd_ == Z2 + int(codes[-1]) * S2 and Zd_ + int(xd[0]) * Sd_ == Z2
+        assert Sm_ == (1 << b) * S2 and Zm_ == Z2 + (Sm_ - S2) / 2
+        for k in range(1 << b):                         # bucket k: codes k 2^b .. k 2^b + 2^b - 1
+            bucket = [Z2 + c * S2 for c in range(k << b, (k + 1) << b)]
+            assert Zm_ + k * Sm_ == sum(bucket) / len(bucket)
+
+
+def test_shift_strategies_reconstruction_error_ordering_on_uniform_codes():
+    """Closed forms for codes uniform over [0, 2^{2b}): mean squared distance between a 2b-bit level and its
+    b-bit image, in units of S_2b^2.  Modified = (4^b - 1)/12 (within-bucket variance); Equivalent =
+    round-to-nearest on a grid of step 2^b + 1; Direct is the largest of the three.  These fix the arithmetic of
+    all three strategies independently of the implementation."""
+    from oracle import shrink_step, SHIFT_EQUIVALENT, SHIFT_DIRECT, SHIFT_MODIFIED
+    one, zero = np.array([1.0], np.float16), np.array([0.0], np.float16)
+    for b in (4, 2):
+        n = 1 << (2 * b)
+        codes = np.arange(n, dtype=np.uint8)
+        mse = {}
+        for st in (SHIFT_EQUIVALENT, SHIFT_DIRECT, SHIFT_MODIFIED):
+            xb, S, Z = shrink_step(codes, one, zero, b, st)
+            rec = xb.astype(np.float64) * float(S[0]) + float(Z[0])
+            mse[st] = float(np.mean((rec - codes) ** 2))
+        assert mse[SHIFT_MODIFIED] == pytest.approx(((1 << b) ** 2 - 1) / 12.0)
+        brute_eq = np.mean([(((2 ** b) + 1) * round_half_up(c / ((2 ** b) + 1)) - c) ** 2 for c in range(n)])
+        assert mse[SHIFT_EQUIVALENT] == pytest.approx(brute_eq)
+        brute_dir = np.mean([(((2 ** b) + 1) * (c >> b) - c) ** 2 for c in range(n)])
+        assert mse[SHIFT_DIRECT] == pytest.approx(brute_dir)
+        assert mse[SHIFT_DIRECT] > mse[SHIFT_EQUIVALENT] and mse[SHIFT_DIRECT] > mse[SHIFT_MODIFIED]
+
+
+def round_half_up(x):
+    import math
+    return math.floor(x + 0.5)
