@@ -150,10 +150,29 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* cache, int32_t layer, int32_t
  *                   cache give bit-identical outputs; 0 (default) = wavefronts claim tiles dynamically, which
  *                   is faster and changes only the floating-point summation order from call to call.
  *   KVQ_OPT_TILE_COST_{2,4,8,16}BIT: relative time one 32-token tile of that width costs the attention kernel
- *                   (1..1000000); the token range of a (sequence, KV head) is cut into splits of equal cost. */
+ *                   (1..1000000); the token range of a (sequence, KV head) is cut into splits of equal cost.
+ *   KVQ_OPT_SHIFT_STRATEGY: how later 2b -> b steps of kvq_progressive_requant treat codes, S and Z, for the
+ *                   comparison of Sec. 4.3.1 (the step from the 16-bit tier is Eq. 1-2 under every strategy):
+ *                   KVQ_SHIFT_EQUIVALENT (default, Eq. 3): X_b = ((2^2b - 2^b + 1)(X_2b + 2^(b-1))) >> 3b,
+ *                       S_b = (2^b + 1) S_2b, Z kept;
+ *                   KVQ_SHIFT_DIRECT:   X_b = X_2b >> b, S_b = (2^b + 1) S_2b, Z kept;
+ *                   KVQ_SHIFT_MODIFIED: X_b = X_2b >> b, S_b = 2^b S_2b, Z_b = Z_2b + (S_b - S_2b) / 2.
+ *                   S_b and Z_b are formed in fp32 and rounded to nearest-even into fp16. */
 enum { KVQ_OPT_SPLITS = 0, KVQ_OPT_FUSED_MERGE = 1, KVQ_OPT_DETERMINISTIC = 2, KVQ_OPT_TILE_COST_2BIT = 3,
-       KVQ_OPT_TILE_COST_4BIT = 4, KVQ_OPT_TILE_COST_8BIT = 5, KVQ_OPT_TILE_COST_16BIT = 6 };
+       KVQ_OPT_TILE_COST_4BIT = 4, KVQ_OPT_TILE_COST_8BIT = 5, KVQ_OPT_TILE_COST_16BIT = 6,
+       KVQ_OPT_SHIFT_STRATEGY = 7 };
+enum { KVQ_SHIFT_EQUIVALENT = 0, KVQ_SHIFT_DIRECT = 1, KVQ_SHIFT_MODIFIED = 2 };
 kvq_status_t kvq_cache_set_option(kvq_cache_t* cache, int32_t option, int32_t value);
+
+/* Reconstruction error of a block's cache against the fp16 tensors it was built from (the model-free measure used
+ * to compare the bit-width shrinking strategies of Sec. 4.3.1): sq_err_host[0] = sum over all cached K elements of
+ * (K_hat - K)^2 with K_hat = code * S + Z (raw value in the 16-bit tier), sq_err_host[1] the same for V.
+ * k_ref_dev, v_ref_dev: device, fp16 [batch, n_kv_heads, n_tokens, 128] with n_tokens the block's current length.
+ * sq_err_host: host, 2 doubles.  Squares are added in fp32 inside a 32-token tile and in fp64 across tiles.
+ * Enqueues on the stream, then waits for it (like kvq_cache_export_segment).  KVQ_E_STATE on an empty block or an
+ * accounting-only cache. */
+kvq_status_t kvq_cache_sq_error(kvq_cache_t* cache, int32_t layer, const void* k_ref_dev, const void* v_ref_dev,
+                                double* sq_err_host, void* hip_stream);
 
 /* Measurement aid, not part of the method: enqueues one plain streaming-read kernel (16-byte loads, no
  * arithmetic) over buf_dev[0, bytes) with n_workgroups workgroups of 256 threads.  Timed by the caller, it gives

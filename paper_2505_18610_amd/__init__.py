@@ -10,4 +10,5 @@ from .binding import (  # noqa: F401
     KVQ_POLICY_PAPER, KVQ_POLICY_OLDEST_FIRST, KVQ_WHICH_K, KVQ_WHICH_V,
     KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE, KVQ_OPT_DETERMINISTIC,
     KVQ_OPT_TILE_COST_2BIT, KVQ_OPT_TILE_COST_4BIT, KVQ_OPT_TILE_COST_8BIT, KVQ_OPT_TILE_COST_16BIT,
+    KVQ_OPT_SHIFT_STRATEGY, KVQ_SHIFT_EQUIVALENT, KVQ_SHIFT_DIRECT, KVQ_SHIFT_MODIFIED,
 )

@@ -11,6 +11,8 @@ KVQ_POLICY_PAPER, KVQ_POLICY_OLDEST_FIRST = 0, 1
 KVQ_WHICH_K, KVQ_WHICH_V = 0, 1
 KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE, KVQ_OPT_DETERMINISTIC = 0, 1, 2
 KVQ_OPT_TILE_COST_2BIT, KVQ_OPT_TILE_COST_4BIT, KVQ_OPT_TILE_COST_8BIT, KVQ_OPT_TILE_COST_16BIT = 3, 4, 5, 6
+KVQ_OPT_SHIFT_STRATEGY = 7
+KVQ_SHIFT_EQUIVALENT, KVQ_SHIFT_DIRECT, KVQ_SHIFT_MODIFIED = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -56,6 +58,7 @@ _SIGNATURES = {
                                            C.c_void_p, C.c_void_p]),
     "kvq_cache_set_option": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "kvq_cache_arena_free_bytes": (C.c_uint64, [C.c_void_p]),
+    "kvq_cache_sq_error": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
     "kvq_stream_read_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p]),
     "kvq_status_string": (C.c_char_p, [C.c_int]),
 }
@@ -193,6 +196,13 @@ class KvqCache:
 
     def kvq_cache_set_option(self, option, value):
         self._check(self.lib.kvq_cache_set_option(self.handle, option, value), "kvq_cache_set_option")
+
+    def kvq_cache_sq_error(self, layer, k_ref, v_ref, stream=None):
+        """(sum (K_hat - K)^2, sum (V_hat - V)^2) of the block against fp16 device tensors [B, Hkv, T, 128]."""
+        out = (C.c_double * 2)()
+        self._check(self.lib.kvq_cache_sq_error(self.handle, layer, _ptr(k_ref), _ptr(v_ref), out, _stream(stream)),
+                    "kvq_cache_sq_error")
+        return float(out[0]), float(out[1])
 
     def kvq_stream_read_probe(self, buf, n_workgroups, stream=None):
         self._check(self.lib.kvq_stream_read_probe(self.handle, _ptr(buf), buf.numel() * buf.element_size(), n_workgroups,

@@ -100,6 +100,7 @@ struct kvq_cache {
     int splits_override = 0;
     int fused_merge = 1;
     int deterministic = 0;
+    int shift_strategy = KVQ_SHIFT_EQUIVALENT;  // how 2b -> b steps treat codes, S and Z (Sec. 4.3.1)
     int tile_cost[4] = {100, 145, 250, 300};  // relative kernel time of one 2/4/8/16-bit tile (measured)
     int target_workgroups = 256;
 
@@ -263,7 +264,7 @@ kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, 
         if (st == KVQ_OK) {
             const KvqRequantJob* jh = by_arg ? jobs.data() : nullptr;
             e = (from == 16) ? kvq_launch_quant16(to, c->arena, jd, jh, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), c->cfg.group, s)
-                             : kvq_launch_shrink(to, c->arena, jd, jh, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), s);
+                             : kvq_launch_shrink(to, c->shift_strategy, c->arena, jd, jh, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), s);
         }
         if (st != KVQ_OK || e != hipSuccess) {
             for (auto& w : low) {
@@ -687,6 +688,10 @@ kvq_status_t kvq_cache_set_option(kvq_cache_t* c, int32_t option, int32_t value)
         case KVQ_OPT_DETERMINISTIC:
             c->deterministic = value ? 1 : 0;
             return KVQ_OK;
+        case KVQ_OPT_SHIFT_STRATEGY:
+            if (value != KVQ_SHIFT_EQUIVALENT && value != KVQ_SHIFT_DIRECT && value != KVQ_SHIFT_MODIFIED) return KVQ_E_INVALID;
+            c->shift_strategy = value;
+            return KVQ_OK;
         case KVQ_OPT_TILE_COST_2BIT:
         case KVQ_OPT_TILE_COST_4BIT:
         case KVQ_OPT_TILE_COST_8BIT:
@@ -697,6 +702,22 @@ kvq_status_t kvq_cache_set_option(kvq_cache_t* c, int32_t option, int32_t value)
             return KVQ_OK;
         default: return KVQ_E_INVALID;
     }
+}
+
+kvq_status_t kvq_cache_sq_error(kvq_cache_t* c, int32_t layer, const void* k_ref_dev, const void* v_ref_dev,
+                                double* sq_err_host, void* hip_stream) {
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !k_ref_dev || !v_ref_dev || !sq_err_host) return KVQ_E_INVALID;
+    if (c->dry) return KVQ_E_STATE;
+    const Layer& L = c->layers[(size_t)layer];
+    if (L.T == 0) return KVQ_E_STATE;
+    hipStream_t s = as_stream(hip_stream);
+    double* err = reinterpret_cast<double*>(c->arena + c->flags_off + 16);  // two accumulators behind the flags
+    if (kvq_launch_fill_u32(reinterpret_cast<uint32_t*>(err), 0u, 4, s) != hipSuccess) return KVQ_E_HIP;
+    if (kvq_launch_sq_error(c->arena, c->table_dev(layer), k_ref_dev, v_ref_dev, L.T, c->tpp, c->units, err, s) != hipSuccess)
+        return KVQ_E_HIP;
+    if (hipMemcpyAsync(sq_err_host, err, 2 * sizeof(double), hipMemcpyDeviceToHost, s) != hipSuccess) return KVQ_E_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return KVQ_E_HIP;
+    return KVQ_OK;
 }
 
 kvq_status_t kvq_stream_read_probe(kvq_cache_t* c, const void* buf_dev, uint64_t bytes, int32_t n_workgroups,

@@ -49,12 +49,14 @@ struct KvqAttnParams {
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
                              const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group, hipStream_t s);
-hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs_dev,
+hipError_t kvq_launch_shrink(int dst_bits, int strategy, uint8_t* arena, const KvqRequantJob* jobs_dev,
                              const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
                              uint32_t* flags, hipStream_t s);
 hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs_dev,
                               const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
                               uint32_t* flags, int group, hipStream_t s);
+hipError_t kvq_launch_sq_error(const uint8_t* arena, const KvqPageDesc* table, const void* k_ref, const void* v_ref,
+                               int n_tokens, int tiles_per_page, int units, double* err, hipStream_t s);
 hipError_t kvq_launch_stream_read(const void* buf, size_t bytes, int n_workgroups, uint32_t* sink, hipStream_t s);
 hipError_t kvq_launch_fill_u32(uint32_t* dst, uint32_t value, size_t n, hipStream_t s);
 

@@ -598,9 +598,31 @@ __device__ inline uint32_t shrink_8_to_4(uint32_t w) {  // 4 bytes -> 4 nibbles 
     return (c | (c >> 8)) & 0xffffu;
 }
 
+// The two other strategies of the ablation (Sec. 4.3.1) keep the upper B bits of every 2B-bit code.
+__device__ inline uint32_t trunc_4_to_2(uint32_t w) {  // 8 nibbles -> their upper two bits, packed (16 bits)
+    uint32_t e = (w >> 2) & 0x03030303u, o = (w >> 6) & 0x03030303u;
+    uint32_t c = e | (o << 2);
+    c = (c | (c >> 4)) & 0x00ff00ffu;
+    return (c | (c >> 8)) & 0xffffu;
+}
+__device__ inline uint32_t trunc_8_to_4(uint32_t w) {  // 4 bytes -> their upper nibbles, packed (16 bits)
+    uint32_t e = (w >> 4) & 0x000f000fu, o = (w >> 12) & 0x000f000fu;
+    uint32_t c = e | (o << 4);
+    return (c | (c >> 8)) & 0xffffu;
+}
+
+#define KVQ_SHIFT_EQUIVALENT_ 0
+#define KVQ_SHIFT_DIRECT_ 1
+#define KVQ_SHIFT_MODIFIED_ 2
+
 // grid.x = n_jobs * tiles_per_page, grid.y = unit, 64 threads; one wavefront shrinks the K and the V tile of
-// one (page, unit, tile) from 2B to B bits and multiplies its 256 scales by 2^B + 1 in place.
-template <int B>
+// one (page, unit, tile) from 2B to B bits and rewrites its 256 scales (and, for the Modified strategy, zero
+// points) in place.
+//   STRAT 0, Equivalent Right Shift (Eq. 3):  codes by Eq. 3, S <- (2^B + 1) S, Z kept
+//   STRAT 1, Direct Right Shift:              codes >> B,     S <- (2^B + 1) S, Z kept
+//   STRAT 2, Modified Right Shift:            codes >> B,     S <- 2^B S,       Z <- Z + (2^B S - S) / 2
+// Products and the sum are formed in fp32 (the products are exact) and rounded to nearest-even into fp16.
+template <int B, int STRAT>
 __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ arena,
                                                         const KvqRequantJob* __restrict__ jobs, int tpp,
                                                         uint32_t* __restrict__ flags, const KvqJobArgs ja) {
@@ -612,9 +634,15 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
     const uint8_t* src = arena + (uint64_t)jb.src_code_off256 * 256u + tslot * 2 * (512u * 2 * B);
     uint8_t* dst = arena + (uint64_t)jb.dst_code_off256 * 256u + tslot * 2 * (512u * B);
     uint8_t* meta = arena + (uint64_t)jb.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
-    // scales: K block at +0 and V block at +512, 64 dwords each, one dword (two fp16) per lane
+    // K scales at +0, K zero points at +256, V scales at +512, V zero points at +768: 64 dwords each, one
+    // dword (two fp16) per lane, a zero point at the same index as its scale
     uint32_t sk = reinterpret_cast<const uint32_t*>(meta)[lane];
     uint32_t sv = reinterpret_cast<const uint32_t*>(meta + 512)[lane];
+    uint32_t zk = 0u, zv = 0u;
+    if constexpr (STRAT == KVQ_SHIFT_MODIFIED_) {
+        zk = reinterpret_cast<const uint32_t*>(meta + 256)[lane];
+        zv = reinterpret_cast<const uint32_t*>(meta + 768)[lane];
+    }
 #pragma unroll
     for (int kv = 0; kv < 2; ++kv) {
         uint32_t in[4 * B];
@@ -622,20 +650,91 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
         uint32_t out[2 * B];
 #pragma unroll
         for (int d = 0; d < 2 * B; ++d) {
-            if constexpr (B == 2)
-                out[d] = shrink_4_to_2(in[2 * d]) | (shrink_4_to_2(in[2 * d + 1]) << 16);
-            else
-                out[d] = shrink_8_to_4(in[2 * d]) | (shrink_8_to_4(in[2 * d + 1]) << 16);
+            if constexpr (STRAT == KVQ_SHIFT_EQUIVALENT_) {
+                if constexpr (B == 2) out[d] = shrink_4_to_2(in[2 * d]) | (shrink_4_to_2(in[2 * d + 1]) << 16);
+                else out[d] = shrink_8_to_4(in[2 * d]) | (shrink_8_to_4(in[2 * d + 1]) << 16);
+            } else {
+                if constexpr (B == 2) out[d] = trunc_4_to_2(in[2 * d]) | (trunc_4_to_2(in[2 * d + 1]) << 16);
+                else out[d] = trunc_8_to_4(in[2 * d]) | (trunc_8_to_4(in[2 * d + 1]) << 16);
+            }
         }
         store_chunks_stream<B>(dst + kv * (512u * B), lane, out);
     }
-    const float f = (float)((1 << B) + 1);
-    uint32_t nk = (uint32_t)f2h_rn(h2f((uint16_t)(sk & 0xffff)) * f) | ((uint32_t)f2h_rn(h2f((uint16_t)(sk >> 16)) * f) << 16);
-    uint32_t nv = (uint32_t)f2h_rn(h2f((uint16_t)(sv & 0xffff)) * f) | ((uint32_t)f2h_rn(h2f((uint16_t)(sv >> 16)) * f) << 16);
+    const float f = STRAT == KVQ_SHIFT_MODIFIED_ ? (float)(1 << B) : (float)((1 << B) + 1);
+    uint32_t nk = 0u, nv = 0u, nzk = 0u, nzv = 0u;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const float s_k = h2f((uint16_t)(sk >> (16 * h))), s_v = h2f((uint16_t)(sv >> (16 * h)));
+        const float nk32 = s_k * f, nv32 = s_v * f;
+        nk |= (uint32_t)f2h_rn(nk32) << (16 * h);
+        nv |= (uint32_t)f2h_rn(nv32) << (16 * h);
+        if constexpr (STRAT == KVQ_SHIFT_MODIFIED_) {
+            const float hk = 0.5f * (nk32 - s_k), hv = 0.5f * (nv32 - s_v);  // exact
+            nzk |= (uint32_t)f2h_rn(h2f((uint16_t)(zk >> (16 * h))) + hk) << (16 * h);
+            nzv |= (uint32_t)f2h_rn(h2f((uint16_t)(zv >> (16 * h))) + hv) << (16 * h);
+        }
+    }
     reinterpret_cast<uint32_t*>(meta)[lane] = nk;
     reinterpret_cast<uint32_t*>(meta + 512)[lane] = nv;
+    if constexpr (STRAT == KVQ_SHIFT_MODIFIED_) {
+        reinterpret_cast<uint32_t*>(meta + 256)[lane] = nzk;
+        reinterpret_cast<uint32_t*>(meta + 768)[lane] = nzv;
+    }
     note_large_v_scale(flags, 1, (uint16_t)(nv & 0xffff));
     note_large_v_scale(flags, 1, (uint16_t)(nv >> 16));
+}
+
+// --------------------------------------------------------------------------------- reconstruction error
+// grid.x = 2 * tiles (even: K tile, odd: V tile), grid.y = unit, 64 threads.  Adds, over the tile's stored
+// tokens, (x_hat - x)^2 with x_hat = code * S + Z (or the raw value of a 16-bit tile) and x the reference fp16
+// tensor [unit][token][128], into err[0] (K) or err[1] (V).  fp32 inside a tile, fp64 across tiles.
+__global__ __launch_bounds__(64) void kvq_sq_error_kernel(const uint8_t* __restrict__ arena,
+                                                          const KvqPageDesc* __restrict__ table,
+                                                          const uint16_t* __restrict__ k_ref,
+                                                          const uint16_t* __restrict__ v_ref, int n_tokens, int tpp,
+                                                          double* __restrict__ err) {
+    const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
+    const int which = blockIdx.x & 1, tile = blockIdx.x >> 1, unit = blockIdx.y;
+    const int page = tile / tpp, tip = tile - page * tpp;
+    const KvqPageDesc pd = table[page];
+    const int B = (int)pd.bits;
+    const uint64_t tslot = (uint64_t)unit * tpp + tip;
+    const uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * (uint32_t)B);
+    const uint16_t* meta = reinterpret_cast<const uint16_t*>(arena + (uint64_t)pd.meta_off256 * 256u +
+                                                             tslot * KVQ_META_TILE_BYTES);
+    const uint16_t* ref = (which ? v_ref : k_ref) + (uint64_t)unit * n_tokens * KVQ_D;
+    const int tok0 = tile * KVQ_TILE_TOKENS;
+    float acc = 0.f;
+    for (int slot = 0; slot < 64; ++slot) {
+        int t, d, g;
+        if (!which) {
+            const int p = slot >> 3, i = slot & 7, sub = p >> 2;
+            g = p & 3;
+            t = 8 * (n >> 2) + 4 * sub + (n & 3);
+            d = 32 * g + 8 * j + i;
+        } else {
+            const int nt = slot >> 3, i = slot & 7;
+            t = 8 * j + i;
+            d = 16 * nt + n;
+            g = d >> 5;
+        }
+        if (tok0 + t >= n_tokens) continue;
+        const uint32_t bit = (uint32_t)slot * (uint32_t)B;
+        const uint8_t* at = code + kvq_tile_byte(lane, bit >> 3);
+        float xh;
+        if (B == 16) {
+            xh = h2f(*reinterpret_cast<const uint16_t*>(at));
+        } else {
+            const uint32_t c = ((uint32_t)*at >> (bit & 7u)) & ((1u << B) - 1u);
+            const int mi = which ? 256 + kvq_vmeta_index(t, g) : t * 4 + g;
+            xh = (float)c * h2f(meta[mi]) + h2f(meta[mi + 128]);
+        }
+        const float dx = xh - h2f(ref[(uint64_t)(tok0 + t) * KVQ_D + d]);
+        acc += dx * dx;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) atomicAdd(&err[which], (double)acc);
 }
 
 // Plain streaming read (16 bytes per lane, 4 non-temporal loads in flight): the practical HBM read ceiling of the device,
@@ -692,17 +791,33 @@ static void fill_job_args(KvqJobArgs& ja, const KvqRequantJob* jobs_host, int n_
 
 // jobs_host != nullptr and n_jobs <= KVQ_JOBS_BY_ARG: the list travels in the kernel arguments and jobs_dev is
 // not read; otherwise jobs_dev must already hold the list (in stream order).
-hipError_t kvq_launch_shrink(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs_dev,
+hipError_t kvq_launch_shrink(int dst_bits, int strategy, uint8_t* arena, const KvqRequantJob* jobs_dev,
                              const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
                              uint32_t* flags, hipStream_t s) {
     dim3 grid(n_jobs * tiles_per_page, units), block(64);
     KvqJobArgs ja;
     fill_job_args(ja, jobs_host, n_jobs);
-    switch (dst_bits) {
-        case 4: hipLaunchKernelGGL(kvq_shrink_kernel<4>, grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, ja); break;
-        case 2: hipLaunchKernelGGL(kvq_shrink_kernel<2>, grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, ja); break;
+#define KVQ_SHRINK_CASE(B_, S_) \
+    hipLaunchKernelGGL((kvq_shrink_kernel<B_, S_>), grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, ja)
+    switch (dst_bits * 4 + strategy) {
+        case 4 * 4 + 0: KVQ_SHRINK_CASE(4, 0); break;
+        case 4 * 4 + 1: KVQ_SHRINK_CASE(4, 1); break;
+        case 4 * 4 + 2: KVQ_SHRINK_CASE(4, 2); break;
+        case 2 * 4 + 0: KVQ_SHRINK_CASE(2, 0); break;
+        case 2 * 4 + 1: KVQ_SHRINK_CASE(2, 1); break;
+        case 2 * 4 + 2: KVQ_SHRINK_CASE(2, 2); break;
         default: return hipErrorInvalidValue;
     }
+#undef KVQ_SHRINK_CASE
+    return hipGetLastError();
+}
+
+hipError_t kvq_launch_sq_error(const uint8_t* arena, const KvqPageDesc* table, const void* k_ref, const void* v_ref,
+                               int n_tokens, int tiles_per_page, int units, double* err, hipStream_t s) {
+    const int n_tiles = (n_tokens + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
+    hipLaunchKernelGGL(kvq_sq_error_kernel, dim3(2 * n_tiles, units), dim3(64), 0, s, arena, table,
+                       static_cast<const uint16_t*>(k_ref), static_cast<const uint16_t*>(v_ref), n_tokens,
+                       tiles_per_page, err);
     return hipGetLastError();
 }
 

@@ -14,11 +14,11 @@ def dev(x: np.ndarray) -> torch.Tensor:
 
 
 def make_pair(n_layers, B, Hq, Hkv, max_tokens, P, budgets=None, fbits=None, window=0, n_sink=0, policy=0,
-              meta=1, payload_bytes=None, group=32):
+              meta=1, payload_bytes=None, group=32, shift_strategy=0):
     budgets = budgets or [1 << 50] * n_layers
     fbits = fbits or [2] * n_layers
     ocfg = CacheConfig(n_layers, B, Hq, Hkv, page_tokens=P, max_tokens=max_tokens, window=window, n_sink=n_sink,
-                       policy=policy, count_metadata_in_budget=meta, group=group)
+                       policy=policy, count_metadata_in_budget=meta, group=group, shift_strategy=shift_strategy)
     oc = OracleCache(ocfg, budgets, fbits)
     cfg = kq.KvqConfig(n_layers, B, Hq, Hkv, max_tokens, page_tokens=P, window=window, n_sink=n_sink, policy=policy,
                        count_metadata_in_budget=meta, group=group)
@@ -27,6 +27,8 @@ def make_pair(n_layers, B, Hq, Hkv, max_tokens, P, budgets=None, fbits=None, win
         payload_bytes = n_layers * pages * P * B * Hkv * 512 + (64 << 20)
     arena = torch.empty(kq.kvq_arena_bytes(cfg, payload_bytes), dtype=torch.uint8, device="cuda")
     gc = kq.KvqCache(cfg, budgets, fbits, arena=arena)
+    if shift_strategy:
+        gc.kvq_cache_set_option(kq.KVQ_OPT_SHIFT_STRATEGY, shift_strategy)
     return oc, gc
 
 

@@ -137,6 +137,37 @@ def test_shrink_of_directly_quantized_tiers():
     check_attention(oc, gc, 0, kvq_synth.make_q(104, 0, B, 2 * H, 339))
 
 
+@pytest.mark.parametrize("strategy", [0, 1, 2])
+def test_shift_strategies_and_reconstruction_error(strategy):
+    """The three bit-width shrinking strategies compared in Sec. 4.3.1 (0 Equivalent = Eq. 3, 1 Direct, 2 Modified):
+    codes, S and Z after every step of the chain are bit-exact against the oracle (the Modified strategy also
+    rewrites Z), attention runs over the result, and the reconstruction error the library reports equals the
+    oracle's (fp32 inside a tile, fp64 across tiles: relative 1e-5)."""
+    B, H, T, P = 2, 2, 448, 64
+    K, V = kvq_synth.make_kv(130 + strategy, 0, B, H, 0, T)
+    Kd, Vd = dev(K), dev(V)
+    oc, gc = make_pair(1, B, 3 * H, H, 512, P, shift_strategy=strategy)
+    append_both(oc, gc, 0, K, V, 16)
+    assert gc.kvq_cache_sq_error(0, Kd, Vd) == (0.0, 0.0)
+    q = kvq_synth.make_q(130 + strategy, 0, B, 3 * H, T - 1)
+    errs = []
+    for want_bits in (8, 4, 2):
+        assert gc.kvq_progressive_requant(0, segment=0) == oc.requant(0, segment=0)
+        assert gc.kvq_cache_describe(0)[0] == [(0, T, want_bits)]
+        assert_same_cache(oc, gc, 0)
+        check_attention(oc, gc, 0, q)
+        got, want = gc.kvq_cache_sq_error(0, Kd, Vd), oc.reconstruction_sq_error(0, K, V)
+        assert got[0] == pytest.approx(want[0], rel=1e-5) and got[1] == pytest.approx(want[1], rel=1e-5)
+        errs.append(got)
+    assert errs[0][0] < errs[1][0] < errs[2][0] and errs[0][1] < errs[1][1] < errs[2][1]
+    # a mixed cache: 2-bit pages, then tokens that entered at 8 bits, then a ragged 16-bit tail
+    K2, V2 = kvq_synth.make_kv(130 + strategy, 0, B, H, T, T + 50)
+    append_both(oc, gc, 0, K2[:, :, :30], V2[:, :, :30], 8)
+    Kall, Vall = np.concatenate([K, K2[:, :, :30]], 2), np.concatenate([V, V2[:, :, :30]], 2)
+    got, want = gc.kvq_cache_sq_error(0, dev(Kall), dev(Vall)), oc.reconstruction_sq_error(0, Kall, Vall)
+    assert got[0] == pytest.approx(want[0], rel=1e-5) and got[1] == pytest.approx(want[1], rel=1e-5)
+
+
 @pytest.mark.parametrize("group", [64, 128])
 def test_group_sizes_64_and_128(group):
     """Quantization groups of 64 and 128 channels (128 is the paper's setting, Sec. 4.1.2): ragged appends at every
