@@ -126,6 +126,32 @@ def measure_requant(kq, torch):
     return out
 
 
+def compare_shift_strategies(kq, torch, kvq_synth):
+    """Sec. 4.3.1 without a model: mean squared reconstruction error of K and V after the 16 -> 8 -> 4 -> 2 chain under
+    the three bit-width shrinking strategies, on a 14B-shaped slice of the synthetic recipe (8 KV heads, 2 sequences,
+    4,096 tokens, RoPE-rotated K with 4 outlier channels per head); all arithmetic runs in the library's kernels."""
+    B, Hkv, T, P = 2, 8, 4096, 256
+    K, V = kvq_synth.make_kv(14, 0, B, Hkv, 0, T)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    n = float(K.size)
+    cfg = kq.KvqConfig(1, B, 40, Hkv, T, page_tokens=P)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, int(T * B * Hkv * 512 * 1.7)), dtype=torch.uint8, device="cuda")
+    out = {}
+    for name, st in (("equivalent", kq.KVQ_SHIFT_EQUIVALENT), ("direct", kq.KVQ_SHIFT_DIRECT),
+                     ("modified", kq.KVQ_SHIFT_MODIFIED)):
+        cache = kq.KvqCache(cfg, [1 << 60], [2], arena=arena)
+        cache.kvq_cache_set_option(kq.KVQ_OPT_SHIFT_STRATEGY, st)
+        cache.kvq_quantize_append(0, Kd, Vd, 16)
+        row = {}
+        for b in (8, 4, 2):
+            cache.kvq_progressive_requant(0, segment=0)
+            ek, ev = cache.kvq_cache_sq_error(0, Kd, Vd)
+            row[f"{b}bit"] = {"mse_K": float(f"{ek / n:.4e}"), "mse_V": float(f"{ev / n:.4e}")}
+        out[name] = row
+        cache.close()
+    return out
+
+
 def measure_read_ceiling(kq, torch, cache):
     """Plain streaming-read kernel over 4 GiB (far beyond the last-level cache): the practical HBM read ceiling."""
     buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
@@ -295,6 +321,7 @@ def main():
     roofline["frac_of_plain_read_kernel"] = round(achieved / ceiling, 4)
     if not args.no_requant:
         result["requant"] = measure_requant(kq, torch)
+        result["shift_strategies_mse"] = compare_shift_strategies(kq, torch, kvq_synth)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, KV, q_np)
     result["setup_seconds"] = {"generate_inputs": round(gen_s, 1)}
