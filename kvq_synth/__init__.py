@@ -44,11 +44,13 @@ def outlier_channels(seed: int, h: int, d: int = HEAD_DIM, n_out: int = 4) -> np
 
 
 def make_kv_unit(seed: int, layer: int, b: int, h: int, t0: int, t1: int, d: int = HEAD_DIM,
-                 rope_base: float | None = 1.0e6, outlier_gain: float = 20.0, n_out: int = 4):
+                 rope_base: float | None = 1.0e6, outlier_gain: float = 20.0, n_out: int = 4,
+                 pos_scale: float = 1.0):
     """K and V (fp16, [t1-t0, d]) of one (layer, sequence b, KV head h) for tokens t0..t1-1.
 
     Every 1024-token block of a unit has its own counter-based stream, so any token range
-    can be produced without generating the tokens before it.
+    can be produced without generating the tokens before it.  pos_scale: token m is rotated
+    at position pos_scale * m (positional interpolation of calibration data, Sec. 3.3, Eq. 10).
     """
     BLK = 1024
     ks, vs = [], []
@@ -60,7 +62,7 @@ def make_kv_unit(seed: int, layer: int, b: int, h: int, t0: int, t1: int, d: int
         k = rk.standard_normal((BLK, d), dtype=np.float32).astype(np.float64) * gain
         v = rv.standard_normal((BLK, d), dtype=np.float32)
         if rope_base is not None:
-            k = rope_rotate(k, np.arange(blk * BLK, (blk + 1) * BLK), rope_base)
+            k = rope_rotate(k, pos_scale * np.arange(blk * BLK, (blk + 1) * BLK), rope_base)
         lo, hi = max(t0, blk * BLK) - blk * BLK, min(t1, (blk + 1) * BLK) - blk * BLK
         ks.append(k[lo:hi].astype(np.float16))
         vs.append(v[lo:hi].astype(np.float16))
@@ -70,13 +72,13 @@ def make_kv_unit(seed: int, layer: int, b: int, h: int, t0: int, t1: int, d: int
 
 
 def make_kv(seed: int, layer: int, batch: int, n_kv: int, t0: int, t1: int, d: int = HEAD_DIM,
-            rope_base: float | None = 1.0e6, outlier_gain: float = 20.0):
+            rope_base: float | None = 1.0e6, outlier_gain: float = 20.0, pos_scale: float = 1.0):
     """K, V fp16 [batch, n_kv, t1-t0, d] for one layer."""
     K = np.empty((batch, n_kv, t1 - t0, d), np.float16)
     V = np.empty_like(K)
     for b in range(batch):
         for h in range(n_kv):
-            K[b, h], V[b, h] = make_kv_unit(seed, layer, b, h, t0, t1, d, rope_base, outlier_gain)
+            K[b, h], V[b, h] = make_kv_unit(seed, layer, b, h, t0, t1, d, rope_base, outlier_gain, pos_scale=pos_scale)
     return K, V
 
 

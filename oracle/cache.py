@@ -12,7 +12,7 @@ import dataclasses
 import numpy as np
 
 from .quantizer import (quantize, dequantize, pack_codes, shrink_step, SHIFT_EQUIVALENT,
-                        bytes_per_token_head)
+                        bytes_per_token_head, reparam_keys, reparam_queries)
 from .attention import decode_attention_fp64
 
 POLICY_PAPER = 0
@@ -70,6 +70,18 @@ class OracleCache:
         assert all(f in (2, 4, 8, 16) for f in block_fbit)
         self.cfg = cfg
         self.layers = [_Layer(b, f) for b, f in zip(block_budget_bytes, block_fbit)]
+        self.lam = [None] * len(self.layers)   # per block: fp32 [n_kv_heads, D] reparameterization factors or None
+
+    def set_reparam(self, layer, lam):
+        """Channel-wise reparameterization of one block (Sec. 3.3, Eq. 7): from now on its keys are stored as
+        K Lambda^{-1} (all widths) and its queries are used as Q Lambda.  Only on an empty block."""
+        if self.layers[layer].T != 0:
+            raise StateError("reparameterization factors must be set before the first append")
+        if lam is not None:
+            lam = np.asarray(lam)
+            assert lam.dtype == np.float32 and lam.shape == (self.cfg.n_kv_heads, self.cfg.head_dim)
+            assert np.all(np.isfinite(lam)) and np.all(lam > 0)
+        self.lam[layer] = lam
 
     # ---------------------------------------------------------------- bookkeeping
     def _bpth(self, bits):
@@ -131,6 +143,8 @@ class OracleCache:
             return
         if L.T + n_new > c.max_tokens:
             raise StateError("max_tokens exceeded")
+        if self.lam[layer] is not None:
+            k = reparam_keys(k, self.lam[layer])
         e = self._entry_bits(layer, entry_bits)
         if L.T % P != 0 and L.pages[-1].bits != e:
             raise StateError("width change inside a page")
@@ -276,6 +290,8 @@ class OracleCache:
         return float(np.sum(dk * dk)), float(np.sum(dv * dv))
 
     def attention(self, layer, q, scale=None):
+        if self.lam[layer] is not None:
+            q = reparam_queries(q, self.lam[layer], self.cfg.n_kv_heads)
         K, V = self.dequantized(layer)
         return decode_attention_fp64(q, K, V, scale)
 

@@ -64,6 +64,43 @@ def shrink_scale(S2b: np.ndarray, b: int) -> np.ndarray:
     return out
 
 
+LAMBDA_FLOOR = np.float32(1.0e-5)   # |K| maxima below this count as this (a channel that is zero everywhere)
+
+
+def calibrate_lambda(K_calib: np.ndarray, alpha: float) -> np.ndarray:
+    """Channel-wise reparameterization factors (Sec. 3.3, Eq. 8): lambda_i = (max_m |K_{m,i}|)^alpha.
+
+    K_calib: fp16 [batch, n_kv_heads, T, D] (rotated keys of the calibration sequences); the maximum runs over
+    the sequences and token positions m of one KV head.  The maximum of the magnitude is taken (an outlier
+    channel may be negative), floored at LAMBDA_FLOOR.  Returns fp32 [n_kv_heads, D]; pow is evaluated in fp64
+    and rounded to fp32.
+    """
+    assert K_calib.dtype == np.float16 and K_calib.ndim == 4
+    mx = np.abs(K_calib.astype(np.float32)).max(axis=(0, 2))
+    mx = np.maximum(mx, LAMBDA_FLOOR)
+    return np.power(mx.astype(np.float64), float(alpha)).astype(np.float32)
+
+
+def reparam_keys(K: np.ndarray, lam: np.ndarray) -> np.ndarray:
+    """K Lambda^{-1} of Eq. 7: every channel i of KV head h is multiplied by the fp32 reciprocal 1/lambda_{h,i}
+    (one correctly rounded fp32 division per channel, one fp32 product per element), rounded to fp16."""
+    assert K.dtype == np.float16 and lam.dtype == np.float32 and lam.shape == (K.shape[1], K.shape[3])
+    r = (np.float32(1.0) / lam)[None, :, None, :]
+    out = (K.astype(np.float32) * r).astype(np.float16)
+    assert np.all(np.isfinite(out))
+    return out
+
+
+def reparam_queries(q: np.ndarray, lam: np.ndarray, n_kv_heads: int) -> np.ndarray:
+    """Q Lambda of Eq. 7: query head h uses the factors of KV head h // (n_q_heads / n_kv_heads); fp32 product
+    rounded to fp16.  q: fp16 [batch, n_q_heads, D]."""
+    assert q.dtype == np.float16 and lam.dtype == np.float32
+    g = q.shape[1] // n_kv_heads
+    out = (q.astype(np.float32) * np.repeat(lam, g, axis=0)[None]).astype(np.float16)
+    assert np.all(np.isfinite(out))
+    return out
+
+
 SHIFT_EQUIVALENT, SHIFT_DIRECT, SHIFT_MODIFIED = 0, 1, 2
 
 

@@ -160,3 +160,68 @@ def test_shift_strategy_chains_and_reconstruction_error():
             ek2, _ = oc.reconstruction_sq_error(0, K, V)
             assert ek2 == pytest.approx(float(np.sum((dequantize(kc, ks, kz, 32) - K.astype(np.float64)) ** 2)))
             assert ek2 > ek
+
+
+# ------------------------------------------------------------ channel-wise reparameterization (Sec. 3.3, Eq. 7-8)
+def test_reparam_lambda_formula_on_hand_made_keys():
+    from oracle import calibrate_lambda, LAMBDA_FLOOR
+    K = np.zeros((2, 1, 5, 128), np.float16)
+    K[0, 0, 3, 0] = 4.0          # max |K| = 4
+    K[1, 0, 1, 1] = -9.0         # the largest magnitude is negative
+    K[0, 0, 0, 2] = 0.25
+    K[1, 0, 4, 2] = 0.125
+    lam = calibrate_lambda(K, 0.5)
+    assert lam.shape == (1, 128) and lam.dtype == np.float32
+    assert lam[0, 0] == 2.0 and lam[0, 1] == 3.0 and lam[0, 2] == 0.5
+    assert lam[0, 3] == pytest.approx(float(LAMBDA_FLOOR) ** 0.5, rel=1e-6)     # an all-zero channel
+    assert np.array_equal(calibrate_lambda(K, 0.0), np.ones((1, 128), np.float32))
+    assert calibrate_lambda(K, 1.0)[0, 1] == 9.0
+
+
+def test_reparam_is_exact_for_power_of_two_factors_and_close_otherwise():
+    """Q Lambda (K Lambda^-1)^T = Q K^T: with power-of-two factors both scalings are exact in fp16 (up to elements
+    that fall into the fp16 subnormal range), so a 16-bit cache reproduces the outputs to 1e-6; with arbitrary
+    factors the fp16 rounding of K / lambda and q * lambda moves the result by about 1e-3."""
+    import kvq_synth
+    B, H, g, T = 1, 2, 3, 96
+    K, V = kvq_synth.make_kv(56, 0, B, H, 0, T)
+    q = kvq_synth.make_q(56, 0, B, H * g, T - 1)
+    cfg = CacheConfig(1, B, H * g, H, page_tokens=32, max_tokens=T)
+    base = OracleCache(cfg, [1 << 40], [2]); base.append(0, K, V, 16)
+    want = base.attention(0, q)
+    rng = np.random.default_rng(1)
+    lam2 = (2.0 ** rng.integers(-2, 3, (H, 128))).astype(np.float32)
+    oc = OracleCache(cfg, [1 << 40], [2]); oc.set_reparam(0, lam2); oc.append(0, K, V, 16)
+    assert np.abs(oc.attention(0, q) - want).max() < 1e-6
+    lam = rng.uniform(0.5, 3.0, (H, 128)).astype(np.float32)
+    oc = OracleCache(cfg, [1 << 40], [2]); oc.set_reparam(0, lam); oc.append(0, K, V, 16)
+    d = np.abs(oc.attention(0, q) - want).max()
+    assert 1e-6 < d < 5e-3
+    with pytest.raises(StateError):
+        oc.set_reparam(0, lam2)                      # not on a block that already holds tokens
+
+
+def test_reparam_moves_outliers_out_of_the_keys():
+    """The motivation of Sec. 3.3 on the synthetic keys (4 channels per head x20): with lambda from Eq. 8 at
+    alpha = 0.5 the stored keys' outlier channels shrink by sqrt(their maximum), and 4-bit attention gets closer to
+    the exact attention over the raw tensors."""
+    import kvq_synth
+    from oracle import calibrate_lambda, reparam_keys, decode_attention_fp64
+    B, H, g, T = 1, 2, 2, 512
+    K, V = kvq_synth.make_kv(57, 0, B, H, 0, T)
+    q = kvq_synth.make_q(57, 0, B, H * g, T - 1)
+    lam = calibrate_lambda(K, 0.5)
+    out_ch = kvq_synth.outlier_channels(57, 0, 128, 4)
+    Kp = reparam_keys(K, lam)
+    ratio = np.abs(K[0, 0]).max(0)[out_ch] / np.abs(Kp[0, 0]).max(0)[out_ch]
+    assert np.allclose(ratio, lam[0, out_ch], rtol=2e-3)
+    exact = decode_attention_fp64(q, K.astype(np.float64), V.astype(np.float64))
+    cfg = CacheConfig(1, B, H * g, H, page_tokens=64, max_tokens=T)
+    errs = []
+    for use in (False, True):
+        oc = OracleCache(cfg, [1 << 40], [2])
+        if use:
+            oc.set_reparam(0, lam)
+        oc.append(0, K, V, 4)
+        errs.append(float(np.linalg.norm(oc.attention(0, q) - exact) / np.linalg.norm(exact)))
+    assert errs[1] < errs[0]
