@@ -164,6 +164,23 @@ enum { KVQ_OPT_SPLITS = 0, KVQ_OPT_FUSED_MERGE = 1, KVQ_OPT_DETERMINISTIC = 2, K
 enum { KVQ_SHIFT_EQUIVALENT = 0, KVQ_SHIFT_DIRECT = 1, KVQ_SHIFT_MODIFIED = 2 };
 kvq_status_t kvq_cache_set_option(kvq_cache_t* cache, int32_t option, int32_t value);
 
+/* Channel-wise reparameterization of one block (Sec. 3.3, Eq. 7): P = (Q Lambda) Q((K Lambda^-1)^T).  After this call
+ * kvq_quantize_append stores the block's keys as K Lambda^-1 at every width (fp32 product of the fp16 key with the
+ * fp32 reciprocal 1 / lambda of its channel, rounded to nearest-even into fp16, before Eq. 1-2), and
+ * kvq_decode_attention multiplies the queries by lambda when it loads them (fp32 product, rounded to fp16).  V is
+ * untouched.  lambda_dev: device, fp32 [n_kv_heads][128], finite and > 0 (not checked); it is copied, together with
+ * its reciprocals, into the arena by a kernel on the stream, so the caller's array may be released afterwards.
+ * lambda_dev == NULL switches the reparameterization off.  KVQ_E_STATE unless the block is empty. */
+kvq_status_t kvq_cache_set_reparam(kvq_cache_t* cache, int32_t layer, const float* lambda_dev, void* hip_stream);
+
+/* Calibration of the factors (Sec. 3.3, Eq. 8): lambda[h][i] = (max_m |K[., h, m, i]|)^alpha over the sequences and
+ * token positions of the calibration keys (magnitudes; maxima below 1e-5 count as 1e-5), pow in fp64 rounded to
+ * fp32.  k_calib_dev: device, fp16 [batch, n_kv_heads, n_tokens, 128], keys as they would be appended (rotated; for
+ * the paper's calibration with positional interpolation, Eq. 10, rotated at positions s * m).  lambda_dev: device,
+ * fp32 [n_kv_heads][128], written.  0 <= alpha <= 4.  Needs no cache; enqueues three small kernels on the stream. */
+kvq_status_t kvq_calibrate_lambda(const void* k_calib_dev, int32_t batch, int32_t n_kv_heads, int32_t n_tokens,
+                                  float alpha, float* lambda_dev, void* hip_stream);
+
 /* Reconstruction error of a block's cache against the fp16 tensors it was built from (the model-free measure used
  * to compare the bit-width shrinking strategies of Sec. 4.3.1): sq_err_host[0] = sum over all cached K elements of
  * (K_hat - K)^2 with K_hat = code * S + Z (raw value in the 16-bit tier), sq_err_host[1] the same for V.

@@ -58,6 +58,8 @@ _SIGNATURES = {
                                            C.c_void_p, C.c_void_p]),
     "kvq_cache_set_option": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "kvq_cache_arena_free_bytes": (C.c_uint64, [C.c_void_p]),
+    "kvq_cache_set_reparam": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
+    "kvq_calibrate_lambda": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]),
     "kvq_cache_sq_error": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
     "kvq_stream_read_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p]),
     "kvq_status_string": (C.c_char_p, [C.c_int]),
@@ -91,6 +93,15 @@ def kvq_status_string(status) -> str:
 
 def kvq_arena_bytes(cfg: KvqConfig, payload_bytes: int) -> int:
     return int(load_library().kvq_arena_bytes(C.byref(cfg), int(payload_bytes)))
+
+
+def kvq_calibrate_lambda(k_calib, alpha, lam_out, stream=None):
+    """k_calib: fp16 device tensor [batch, n_kv_heads, n_tokens, 128]; lam_out: fp32 device tensor [n_kv_heads, 128]."""
+    b, h, t, d = k_calib.shape
+    assert d == 128 and tuple(lam_out.shape) == (h, 128)
+    st = load_library().kvq_calibrate_lambda(_ptr(k_calib), b, h, t, float(alpha), _ptr(lam_out), _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_calibrate_lambda")
 
 
 def kvq_bytes_per_token_head(bits, head_dim=128, group=32, count_metadata=1) -> int:
@@ -196,6 +207,11 @@ class KvqCache:
 
     def kvq_cache_set_option(self, option, value):
         self._check(self.lib.kvq_cache_set_option(self.handle, option, value), "kvq_cache_set_option")
+
+    def kvq_cache_set_reparam(self, layer, lam, stream=None):
+        """lam: fp32 device tensor [n_kv_heads, 128], or None to switch the reparameterization off."""
+        self._check(self.lib.kvq_cache_set_reparam(self.handle, layer, _ptr(lam) if lam is not None else None,
+                                                   _stream(stream)), "kvq_cache_set_reparam")
 
     def kvq_cache_sq_error(self, layer, k_ref, v_ref, stream=None):
         """(sum (K_hat - K)^2, sum (V_hat - V)^2) of the block against fp16 device tensors [B, Hkv, T, 128]."""

@@ -815,9 +815,23 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
     if (tid < 256) {
         const int head = tid >> 4, c16 = tid & 15;
         u32x4 qv = {0u, 0u, 0u, 0u};
-        if (head < g)
+        if (head < g) {
             qv = *reinterpret_cast<const u32x4*>(static_cast<const _Float16*>(P.q) +
                                                  ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + c16 * 8);
+            if (P.lambda) {  // Q Lambda of the channel-wise reparameterization (Sec. 3.3, Eq. 7): fp32 product, RNE to fp16
+                const float* lam = P.lambda + hk * KVQ_D + c16 * 8;
+                uint32_t* qw = reinterpret_cast<uint32_t*>(&qv);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const _Float16 lo = __builtin_bit_cast(_Float16, (uint16_t)(qw[e] & 0xffff));
+                    const _Float16 hi = __builtin_bit_cast(_Float16, (uint16_t)(qw[e] >> 16));
+                    float plo = (float)lo * lam[2 * e], phi = (float)hi * lam[2 * e + 1];
+                    asm volatile("" : "+v"(plo), "+v"(phi));  // two roundings (fp32, then fp16), never a fused one
+                    const _Float16 nlo = (_Float16)plo, nhi = (_Float16)phi;
+                    qw[e] = (uint32_t)__builtin_bit_cast(uint16_t, nlo) | ((uint32_t)__builtin_bit_cast(uint16_t, nhi) << 16);
+                }
+            }
+        }
         u32x4 dv = {0u, 0u, 0u, 0u};
         if (tid < min(KVQ_DESC_CACHE, p_last - p_first)) dv = reinterpret_cast<const u32x4*>(P.table)[p_first + tid];
         *reinterpret_cast<u32x4*>(&q_lds[head * KVQ_D + c16 * 8]) = qv;

@@ -74,6 +74,7 @@ struct Layer {
     uint64_t budget = 0;
     int fbit = 2;
     int T = 0;
+    bool reparam = false;  // keys stored as K / lambda, queries multiplied by lambda (Sec. 3.3)
     std::vector<Page> pages;
     // split plan cache of kvq_decode_attention
     int plan_tiles = -1, plan_splits = 0;
@@ -91,6 +92,7 @@ struct kvq_cache {
     uint64_t arena_bytes = 0;
     uint64_t unit_bytes = 0;
     uint64_t table_off = 0, jobs_off = 0, part_o_off = 0, part_ml_off = 0, counters_off = 0, flags_off = 0, pages_off = 0;
+    uint64_t reparam_off = 0;  // per block: lambda [n_kv_heads][128] fp32, then 1 / lambda
     uint32_t* flags_dev() const { return reinterpret_cast<uint32_t*>(arena + flags_off); }
     Buddy buddy;
     std::vector<Layer> layers;
@@ -116,6 +118,9 @@ struct kvq_cache {
         d.pad = 0;
         return d;
     }
+    float* lambda_dev(int layer) const {  // lambda of the block; its reciprocals follow
+        return reinterpret_cast<float*>(arena + reparam_off) + (size_t)layer * 2 * cfg.n_kv_heads * KVQ_D;
+    }
     KvqPageDesc* table_dev(int layer) const {
         return reinterpret_cast<KvqPageDesc*>(arena + table_off) + (size_t)layer * max_pages;
     }
@@ -124,7 +129,7 @@ struct kvq_cache {
 namespace {
 
 struct Regions {
-    uint64_t table_off, jobs_off, part_o_off, part_ml_off, counters_off, flags_off, pages_off;
+    uint64_t table_off, jobs_off, part_o_off, part_ml_off, counters_off, flags_off, reparam_off, pages_off;
 };
 uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
@@ -153,6 +158,7 @@ Regions layout_regions(const kvq_config_t* c) {
     r.part_ml_off = off;   off = align_up(off + units * KVQ_MAX_SPLITS * 32 * sizeof(float), 256);
     r.counters_off = off;  off = align_up(off + units * sizeof(uint32_t), 256);
     r.flags_off = off;     off = align_up(off + 64, 256);
+    r.reparam_off = off;   off = align_up(off + (uint64_t)c->n_layers * 2 * c->n_kv_heads * KVQ_D * sizeof(float), 256);
     uint64_t unit_bytes = 32ull * c->page_tokens * units;
     (void)unit_bytes;
     r.pages_off = align_up(off, 4096);
@@ -377,6 +383,7 @@ kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_bud
     Regions r = layout_regions(cfg);
     c->table_off = r.table_off; c->jobs_off = r.jobs_off; c->part_o_off = r.part_o_off;
     c->part_ml_off = r.part_ml_off; c->counters_off = r.counters_off; c->flags_off = r.flags_off; c->pages_off = r.pages_off;
+    c->reparam_off = r.reparam_off;
     uint64_t super = c->unit_bytes << kMaxOrder;
     if (arena_bytes < c->pages_off + super) { delete c; return KVQ_E_OOM; }
     uint64_t n_super = (arena_bytes - c->pages_off) / super;
@@ -490,7 +497,8 @@ kvq_status_t kvq_quantize_append(kvq_cache_t* c, int32_t layer, const void* k_de
             two[1] = c->desc(L.pages[(size_t)pg1]);
         }
         if (kvq_launch_append(e, c->arena, c->table_dev(layer), k_dev, v_dev, t_old, n_new, c->tpp, c->units,
-                              by_arg ? two : nullptr, pg0, c->flags_dev(), c->cfg.group, s) != hipSuccess)
+                              by_arg ? two : nullptr, pg0, c->flags_dev(), c->cfg.group,
+                              L.reparam ? c->lambda_dev(layer) + c->cfg.n_kv_heads * KVQ_D : nullptr, c->cfg.n_kv_heads, s) != hipSuccess)
             return KVQ_E_HIP;
     }
     if (!evicted.empty()) {
@@ -572,6 +580,7 @@ kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_d
     p.arena = c->arena;
     p.table = c->table_dev(layer);
     p.q = q_dev;
+    p.lambda = L.reparam ? c->lambda_dev(layer) : nullptr;
     p.out = out_dev;
     p.part_o = reinterpret_cast<float*>(c->arena + c->part_o_off);
     p.part_ml = reinterpret_cast<float*>(c->arena + c->part_ml_off);
@@ -702,6 +711,29 @@ kvq_status_t kvq_cache_set_option(kvq_cache_t* c, int32_t option, int32_t value)
             return KVQ_OK;
         default: return KVQ_E_INVALID;
     }
+}
+
+kvq_status_t kvq_cache_set_reparam(kvq_cache_t* c, int32_t layer, const float* lambda_dev, void* hip_stream) {
+    if (!c || layer < 0 || layer >= c->cfg.n_layers) return KVQ_E_INVALID;
+    Layer& L = c->layers[(size_t)layer];
+    if (L.T != 0) return KVQ_E_STATE;
+    if (!lambda_dev) { L.reparam = false; return KVQ_OK; }
+    if (!c->dry) {
+        kvq_status_t st = ensure_device(c, as_stream(hip_stream));
+        if (st != KVQ_OK) return st;
+        if (kvq_launch_reparam_store(lambda_dev, c->lambda_dev(layer), c->cfg.n_kv_heads * KVQ_D, as_stream(hip_stream)) != hipSuccess)
+            return KVQ_E_HIP;
+    }
+    L.reparam = true;
+    return KVQ_OK;
+}
+
+kvq_status_t kvq_calibrate_lambda(const void* k_calib_dev, int32_t batch, int32_t n_kv_heads, int32_t n_tokens,
+                                  float alpha, float* lambda_dev, void* hip_stream) {
+    if (!k_calib_dev || !lambda_dev || batch < 1 || n_kv_heads < 1 || n_tokens < 1 || !(alpha >= 0.0f && alpha <= 4.0f))
+        return KVQ_E_INVALID;
+    return kvq_launch_calibrate(k_calib_dev, batch, n_kv_heads, n_tokens, alpha, 1.0e-5f, lambda_dev,
+                                as_stream(hip_stream)) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
 }
 
 kvq_status_t kvq_cache_sq_error(kvq_cache_t* c, int32_t layer, const void* k_ref_dev, const void* v_ref_dev,

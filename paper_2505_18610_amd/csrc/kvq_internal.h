@@ -26,6 +26,7 @@ struct KvqAttnParams {
     const uint8_t* arena;
     const KvqPageDesc* table;  // this block's page table
     const void* q;             // fp16 [batch, n_q_heads, 128]
+    const float* lambda;       // [n_kv_heads][128] reparameterization factors applied to q at load, or null
     void* out;                 // [batch, n_q_heads, 128] fp16 or fp32
     float* part_o;             // [unit][split][16][128] un-normalised partial outputs
     float* part_ml;            // [unit][split][16] pairs (running max in log2 units, sum)
@@ -48,13 +49,17 @@ struct KvqAttnParams {
 // kvq_quant.hip
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
-                             const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group, hipStream_t s);
+                             const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group,
+                             const float* rinv, int n_kv_heads, hipStream_t s);
 hipError_t kvq_launch_shrink(int dst_bits, int strategy, uint8_t* arena, const KvqRequantJob* jobs_dev,
                              const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
                              uint32_t* flags, hipStream_t s);
 hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob* jobs_dev,
                               const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
                               uint32_t* flags, int group, hipStream_t s);
+hipError_t kvq_launch_reparam_store(const float* lambda, float* dst, int n, hipStream_t s);
+hipError_t kvq_launch_calibrate(const void* k, int batch, int n_kv_heads, int n_tokens, float alpha, float floor_,
+                                float* lambda, hipStream_t s);
 hipError_t kvq_launch_sq_error(const uint8_t* arena, const KvqPageDesc* table, const void* k_ref, const void* v_ref,
                                int n_tokens, int tiles_per_page, int units, double* err, hipStream_t s);
 hipError_t kvq_launch_stream_read(const void* buf, size_t bytes, int n_workgroups, uint32_t* sink, hipStream_t s);

@@ -13,6 +13,22 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ inline float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
 __device__ inline uint16_t f2h_rn(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }  // RNE
 
+// K Lambda^{-1} of Eq. 7 on 8 consecutive channels (4 dwords of fp16 pairs): fp32 product with the channel's
+// reciprocal factor, rounded to nearest-even into fp16.
+// The product is rounded to fp32 first and to fp16 second, as two separate IEEE operations: the empty asm keeps the
+// compiler from fusing them into a mixed-precision instruction that rounds the exact product once (1 fp16 ulp apart
+// in about one element of 10^4).
+__device__ inline uint32_t scale_pair(uint32_t w, float r_lo, float r_hi) {
+    float lo = h2f((uint16_t)(w & 0xffff)) * r_lo, hi = h2f((uint16_t)(w >> 16)) * r_hi;
+    asm volatile("" : "+v"(lo), "+v"(hi));
+    return (uint32_t)f2h_rn(lo) | ((uint32_t)f2h_rn(hi) << 16);
+}
+__device__ inline u32x4 scale_keys8(u32x4 v, const float* rinv) {
+    const float4 r0 = *reinterpret_cast<const float4*>(rinv), r1 = *reinterpret_cast<const float4*>(rinv + 4);
+    return u32x4{scale_pair(v.x, r0.x, r0.y), scale_pair(v.y, r0.z, r0.w), scale_pair(v.z, r1.x, r1.y),
+                 scale_pair(v.w, r1.z, r1.w)};
+}
+
 // (S, Z) of one group from its min and max (both exact fp16 values held as float), Eq. 2.
 __device__ inline void group_params(float mn, float mx, int levels, uint16_t* S, uint16_t* Z, float* Sf) {
     float s32 = (mx - mn) / (float)levels;  // one fp32 subtract, one correctly rounded fp32 divide
@@ -338,7 +354,8 @@ __global__ __launch_bounds__(64) void kvq_append_kernel(uint8_t* __restrict__ ar
                                                         const KvqPageDesc* __restrict__ table,
                                                         const uint16_t* __restrict__ k_in,
                                                         const uint16_t* __restrict__ v_in, int t_old,
-                                                        int n_new, int tpp, int tile0, KvqAppendPages ap) {
+                                                        int n_new, int tpp, int tile0, KvqAppendPages ap,
+                                                        const float* __restrict__ rinv, int n_kv_heads) {
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
     const int tile = tile0 + (blockIdx.x >> 1);
@@ -363,8 +380,10 @@ __global__ __launch_bounds__(64) void kvq_append_kernel(uint8_t* __restrict__ ar
 #pragma unroll
             for (int grp = 0; grp < 4; ++grp) {
                 u32x4 v = {0u, 0u, 0u, 0u};
-                if (isnew)
+                if (isnew) {
                     v = *reinterpret_cast<const u32x4*>(in + (uint64_t)(tok - t_old) * KVQ_D + 32 * grp + 8 * j);
+                    if (rinv) v = scale_keys8(v, rinv + (unit % n_kv_heads) * KVQ_D + 32 * grp + 8 * j);
+                }
                 int s0 = (sub * 4 + grp) * 8;
                 raw[s0 + 0] = v.x & 0xffff; raw[s0 + 1] = v.x >> 16;
                 raw[s0 + 2] = v.y & 0xffff; raw[s0 + 3] = v.y >> 16;
@@ -452,7 +471,8 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
                                                           const uint16_t* __restrict__ k_in,
                                                           const uint16_t* __restrict__ v_in, int t_old,
                                                           int n_new, int tpp, int tile0, KvqAppendPages ap,
-                                                          uint32_t* __restrict__ flags, int gspan) {
+                                                          uint32_t* __restrict__ flags, int gspan,
+                                                          const float* __restrict__ rinv, int n_kv_heads) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
@@ -475,7 +495,10 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (isnew) v = *reinterpret_cast<const u32x4*>(in + (uint64_t)(tok - t_old) * KVQ_D + 32 * grp + 8 * c);
+            if (isnew) {
+                v = *reinterpret_cast<const u32x4*>(in + (uint64_t)(tok - t_old) * KVQ_D + 32 * grp + 8 * c);
+                if (rinv && !which) v = scale_keys8(v, rinv + (unit % n_kv_heads) * KVQ_D + 32 * grp + 8 * c);
+            }
             w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
         }
         float codes[32];
@@ -737,6 +760,31 @@ __global__ __launch_bounds__(64) void kvq_sq_error_kernel(const uint8_t* __restr
     if (lane == 0) atomicAdd(&err[which], (double)acc);
 }
 
+// ------------------------------------------------------------------------ channel-wise reparameterization
+// dst[0 .. n) = lambda, dst[n .. 2n) = 1 / lambda (one correctly rounded fp32 division per channel).
+__global__ void kvq_reparam_store_kernel(const float* __restrict__ lambda, float* __restrict__ dst, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { const float l = lambda[i]; dst[i] = l; dst[n + i] = 1.0f / l; }
+}
+// Eq. 8, first half: acc[h][i] = max over sequences and tokens of |K|.  grid (n_kv_heads, slices), 128 threads
+// (one channel each); acc holds float bit patterns of non-negative values, whose unsigned order is their order.
+__global__ __launch_bounds__(128) void kvq_absmax_kernel(const uint16_t* __restrict__ k, int batch, int n_kv_heads,
+                                                         int n_tokens, uint32_t* __restrict__ acc) {
+    const int h = blockIdx.x, c = threadIdx.x;
+    float m = 0.f;
+    const long rows = (long)batch * n_tokens;
+    for (long r = blockIdx.y; r < rows; r += gridDim.y) {
+        const long bb = r / n_tokens, t = r - bb * n_tokens;
+        m = fmaxf(m, fabsf(h2f(k[((bb * n_kv_heads + h) * n_tokens + t) * KVQ_D + c])));
+    }
+    atomicMax(&acc[h * KVQ_D + c], __float_as_uint(m));
+}
+// Eq. 8, second half, in place: lambda = max(absmax, floor)^alpha, pow in fp64, rounded to fp32.
+__global__ void kvq_lambda_pow_kernel(float* __restrict__ lam, int n, float alpha, float floor_) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) lam[i] = (float)pow((double)fmaxf(lam[i], floor_), (double)alpha);
+}
+
 // Plain streaming read (16 bytes per lane, 4 non-temporal loads in flight): the practical HBM read ceiling of the device,
 // against which the attention kernel's bandwidth is put next to the published peak.
 __global__ __launch_bounds__(256) void kvq_stream_read_kernel(const u32x4* __restrict__ p, size_t n,
@@ -762,7 +810,8 @@ __global__ void kvq_fill_u32_kernel(uint32_t* dst, uint32_t value, size_t n) {
 
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
-                             const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group, hipStream_t s) {
+                             const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group,
+                             const float* rinv, int n_kv_heads, hipStream_t s) {
     const int gspan = group / KVQ_G;
     int tile0 = t_old / KVQ_TILE_TOKENS;
     int tile1 = (t_old + n_new + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
@@ -774,10 +823,10 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
     ap.d[0] = first_two ? first_two[0] : KvqPageDesc{0, 0, 0, 0};
     ap.d[1] = first_two ? first_two[1] : KvqPageDesc{0, 0, 0, 0};
     switch (bits) {
-        case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap); break;
-        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan); break;
-        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan); break;
-        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan); break;
+        case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, rinv, n_kv_heads); break;
+        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads); break;
+        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads); break;
+        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -833,6 +882,23 @@ hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob*
         case 2: hipLaunchKernelGGL(kvq_quant16_kernel<2>, grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, group / KVQ_G, ja); break;
         default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+hipError_t kvq_launch_reparam_store(const float* lambda, float* dst, int n, hipStream_t s) {
+    hipLaunchKernelGGL(kvq_reparam_store_kernel, dim3((n + 255) / 256), dim3(256), 0, s, lambda, dst, n);
+    return hipGetLastError();
+}
+
+hipError_t kvq_launch_calibrate(const void* k, int batch, int n_kv_heads, int n_tokens, float alpha, float floor_,
+                                float* lambda, hipStream_t s) {
+    const int n = n_kv_heads * KVQ_D;
+    hipLaunchKernelGGL(kvq_fill_u32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, reinterpret_cast<uint32_t*>(lambda), 0u, (size_t)n);
+    const long rows = (long)batch * n_tokens;
+    const int slices = (int)(rows < 1024 ? rows : 1024);
+    hipLaunchKernelGGL(kvq_absmax_kernel, dim3(n_kv_heads, slices), dim3(128), 0, s, static_cast<const uint16_t*>(k),
+                       batch, n_kv_heads, n_tokens, reinterpret_cast<uint32_t*>(lambda));
+    hipLaunchKernelGGL(kvq_lambda_pow_kernel, dim3((n + 255) / 256), dim3(256), 0, s, lambda, n, alpha, floor_);
     return hipGetLastError();
 }
 

@@ -168,6 +168,46 @@ def test_shift_strategies_and_reconstruction_error(strategy):
     assert got[0] == pytest.approx(want[0], rel=1e-5) and got[1] == pytest.approx(want[1], rel=1e-5)
 
 
+def test_channel_reparameterization_matches_oracle():
+    """Sec. 3.3, Eq. 7-8: lambda from the calibration kernel equals the oracle's (pow in fp64: one fp32 ulp); with the
+    same lambda on both sides the stored keys K / lambda are bit-exact at every width and through the shrink chain,
+    and attention with q * lambda matches.  The factors cannot be changed once a block holds tokens."""
+    from oracle import calibrate_lambda
+    B, H, g, T, P = 2, 2, 3, 300, 64
+    K, V = kvq_synth.make_kv(140, 0, B, H, 0, T)
+    Kc, _ = kvq_synth.make_kv(141, 0, B, H, 0, 128, pos_scale=8.0)       # short calibration keys, interpolated positions
+    lam = calibrate_lambda(Kc, 0.5)
+    lam_dev = torch.empty((H, 128), dtype=torch.float32, device="cuda")
+    kq.kvq_calibrate_lambda(dev(Kc), 0.5, lam_dev)
+    assert np.allclose(lam_dev.cpu().numpy(), lam, rtol=3e-7, atol=0)
+    q = kvq_synth.make_q(140, 0, B, H * g, T - 1)
+    for bits in (16, 8, 4, 2):
+        oc, gc = make_pair(1, B, H * g, H, 512, P)
+        oc.set_reparam(0, lam)
+        gc.kvq_cache_set_reparam(0, dev(lam))
+        t = 0
+        for n in (1, 70, 129, 100):
+            append_both(oc, gc, 0, K[:, :, t:t + n], V[:, :, t:t + n], bits)
+            t += n
+        assert_same_cache(oc, gc, 0)
+        check_attention(oc, gc, 0, q)
+        if bits == 16:
+            for _ in range(3):
+                assert gc.kvq_progressive_requant(0, segment=0) == oc.requant(0, segment=0)
+                assert_same_cache(oc, gc, 0)
+                check_attention(oc, gc, 0, q)
+        with pytest.raises(kq.KvqError) as e:
+            gc.kvq_cache_set_reparam(0, None)
+        assert e.value.status == kq.KVQ_E_STATE
+    # switched off again on an empty block: identical to a cache that never had factors
+    oc, gc = make_pair(1, B, H * g, H, 512, P)
+    gc.kvq_cache_set_reparam(0, dev(lam))
+    gc.kvq_cache_set_reparam(0, None)
+    append_both(oc, gc, 0, K, V, 4)
+    assert_same_cache(oc, gc, 0)
+    check_attention(oc, gc, 0, q)
+
+
 @pytest.mark.parametrize("group", [64, 128])
 def test_group_sizes_64_and_128(group):
     """Quantization groups of 64 and 128 channels (128 is the paper's setting, Sec. 4.1.2): ragged appends at every
