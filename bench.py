@@ -152,6 +152,49 @@ def compare_shift_strategies(kq, torch, kvq_synth):
     return out
 
 
+def reparam_effect(kq, torch, kvq_synth):
+    """Sec. 3.3 on the synthetic recipe (4 key channels per head x20): relative L2 error of decode attention over a
+    b-bit cache against the same library's attention over the 16-bit cache, without and with the channel-wise
+    reparameterization (lambda from 512 calibration tokens rotated at 64x interpolated positions, alpha = 0.5);
+    and what the extra multiply costs a bulk append."""
+    B, Hkv, Hq, T, P = 2, 8, 40, 8192, 256
+    K, V = kvq_synth.make_kv(14, 0, B, Hkv, 0, T)
+    # calibration keys: the same heads (same outlier channels), another block's values
+    Kc, _ = kvq_synth.make_kv(14, 1, B, Hkv, 0, 512, pos_scale=64.0)
+    q = torch.from_numpy(kvq_synth.make_q(14, 0, B, Hq, T - 1)).cuda()
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    lam = torch.empty((Hkv, 128), dtype=torch.float32, device="cuda")
+    kq.kvq_calibrate_lambda(torch.from_numpy(Kc).cuda(), 0.5, lam)
+    cfg = kq.KvqConfig(1, B, Hq, Hkv, T, page_tokens=P)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, int(T * B * Hkv * 512 * 1.2)), dtype=torch.uint8, device="cuda")
+
+    def run(bits, use_lambda, timed=False):
+        cache = kq.KvqCache(cfg, [1 << 60], [2], arena=arena)
+        if use_lambda:
+            cache.kvq_cache_set_reparam(0, lam)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        cache.kvq_quantize_append(0, Kd, Vd, bits)
+        e1.record()
+        out = torch.empty((B, Hq, 128), dtype=torch.float32, device="cuda")
+        cache.kvq_decode_attention(0, q, out)
+        torch.cuda.synchronize()
+        cache.close()
+        return out, e0.elapsed_time(e1)
+
+    exact, _ = run(16, False)
+    res = {}
+    for bits in (8, 4, 2):
+        row = {}
+        for name, use in (("plain", False), ("reparam", True)):
+            run(bits, use)                                   # warm-up of this variant
+            out, ms = run(bits, use)
+            row[name + "_rel_l2"] = float(f"{(torch.linalg.norm(out - exact) / torch.linalg.norm(exact)).item():.4e}")
+            row[name + "_append_ms"] = round(ms, 4)
+        res[f"{bits}bit"] = row
+    return res
+
+
 def measure_read_ceiling(kq, torch, cache):
     """Plain streaming-read kernel over 4 GiB (far beyond the last-level cache): the practical HBM read ceiling."""
     buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
@@ -322,6 +365,7 @@ def main():
     if not args.no_requant:
         result["requant"] = measure_requant(kq, torch)
         result["shift_strategies_mse"] = compare_shift_strategies(kq, torch, kvq_synth)
+        result["reparam_effect"] = reparam_effect(kq, torch, kvq_synth)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, KV, q_np)
     result["setup_seconds"] = {"generate_inputs": round(gen_s, 1)}
