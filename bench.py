@@ -195,6 +195,36 @@ def reparam_effect(kq, torch, kvq_synth):
     return res
 
 
+def allocation_demo(kq, torch, kvq_synth):
+    """Sec. 3.2 end to end on synthetic blocks: the library measures s_{i,b} (Eq. 5 with all-ones gradients) of 16
+    blocks whose keys differ in outlier strength, and solves Eq. 6 for a budget half-way between uniform 2 and uniform
+    4 bits (the situation of Sec. 3.2: uniform 2 bits wastes memory, uniform 4 bits does not fit)."""
+    B, Hkv, T, P, N, widths = 1, 8, 2048, 256, 16, (2, 4, 8)
+    cfg = kq.KvqConfig(1, B, 40, Hkv, T, page_tokens=P)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, int(T * B * Hkv * 512 * 1.2)), dtype=torch.uint8, device="cuda")
+    s, mem = [], []
+    for i in range(N):
+        K, V = kvq_synth.make_kv(14, i, B, Hkv, 0, T, outlier_gain=1.0 + 2.0 * i)
+        Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+        row = []
+        for b in widths:
+            cache = kq.KvqCache(cfg, [1 << 60], [2], arena=arena)
+            cache.kvq_quantize_append(0, Kd, Vd, b)
+            sk, sv = cache.kvq_cache_sensitivity(0, Kd, Vd)
+            row.append(sk + sv)
+            cache.close()
+        s.append(row)
+        mem.append([T * B * Hkv * kq.kvq_bytes_per_token_head(b) for b in widths])
+    budget = (sum(m[0] for m in mem) + sum(m[1] for m in mem)) // 2
+    t0 = time.perf_counter()
+    ch, cost, used = kq.kvq_allocate_bits(s, mem, budget)
+    solve_ms = (time.perf_counter() - t0) * 1e3
+    return {"blocks": N, "widths": list(widths), "budget_bytes": budget, "used_bytes": used,
+            "fbit": [widths[c] for c in ch], "total_sensitivity": float(f"{cost:.6e}"),
+            "uniform_2bit_sensitivity": float(f"{sum(r[0] for r in s):.6e}"),
+            "uniform_4bit_sensitivity": float(f"{sum(r[1] for r in s):.6e}"), "solve_ms": round(solve_ms, 3)}
+
+
 def measure_read_ceiling(kq, torch, cache):
     """Plain streaming-read kernel over 4 GiB (far beyond the last-level cache): the practical HBM read ceiling."""
     buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
@@ -366,6 +396,7 @@ def main():
         result["requant"] = measure_requant(kq, torch)
         result["shift_strategies_mse"] = compare_shift_strategies(kq, torch, kvq_synth)
         result["reparam_effect"] = reparam_effect(kq, torch, kvq_synth)
+        result["allocation"] = allocation_demo(kq, torch, kvq_synth)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, KV, q_np)
     result["setup_seconds"] = {"generate_inputs": round(gen_s, 1)}

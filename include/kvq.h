@@ -191,6 +191,27 @@ kvq_status_t kvq_calibrate_lambda(const void* k_calib_dev, int32_t batch, int32_
 kvq_status_t kvq_cache_sq_error(kvq_cache_t* cache, int32_t layer, const void* k_ref_dev, const void* v_ref_dev,
                                 double* sq_err_host, void* hip_stream);
 
+/* The two terms of the sensitivity of Sec. 3.2, Eq. 5, for a block as it is cached now:
+ * s_host[0] = || G_K * (K - K_hat) ||_1, s_host[1] = || G_V * (V - V_hat) ||_1 (* element-wise; K_hat = code * S + Z, raw
+ * value in the 16-bit tier); s_{i,b} of Eq. 5 is their sum for block i held at width b.  k_ref_dev, v_ref_dev as in
+ * kvq_cache_sq_error; gk_dev, gv_dev: device, fp32 [batch, n_kv_heads, n_tokens, 128], the gradients of the loss with
+ * respect to K and V, or NULL for all-ones (no model at hand: plain L1 reconstruction error).  For a block with
+ * reparameterization the stored keys are K Lambda^-1: pass references in that space.  fp32 inside a tile, fp64 across
+ * tiles.  Enqueues on the stream, then waits for it. */
+kvq_status_t kvq_cache_sensitivity(kvq_cache_t* cache, int32_t layer, const void* k_ref_dev, const void* v_ref_dev,
+                                   const float* gk_dev, const float* gv_dev, double* s_host, void* hip_stream);
+
+/* Block-wise memory allocation, the integer program of Sec. 3.2, Eq. 6, solved exactly on the host (multiple-choice
+ * knapsack by lists of non-dominated states): choose one width per block, choice_out[i] in [0, n_choices), minimising
+ * sum_i s[i][choice_i] subject to sum_i mem[i][choice_i] <= budget.  s: host, [n_blocks][n_choices], finite, >= 0 (the
+ * sensitivities s_{i,b}); mem: host, [n_blocks][n_choices] bytes (e.g. tokens * batch * n_kv_heads *
+ * kvq_bytes_per_token_head(b)).  Among equally cheap solutions the one using less memory is returned.  total_s_out,
+ * total_mem_out: optional.  The chosen widths and mem[i][choice_i] are the block_fbit / block_budget_bytes vectors of
+ * kvq_cache_create.  KVQ_E_BUDGET if no choice fits; KVQ_E_OOM beyond 4 M states; needs no GPU.
+ * 1 <= n_blocks <= 4096, 1 <= n_choices <= 16. */
+kvq_status_t kvq_allocate_bits(int32_t n_blocks, int32_t n_choices, const double* s, const uint64_t* mem,
+                               uint64_t budget, int32_t* choice_out, double* total_s_out, uint64_t* total_mem_out);
+
 /* Measurement aid, not part of the method: enqueues one plain streaming-read kernel (16-byte loads, no
  * arithmetic) over buf_dev[0, bytes) with n_workgroups workgroups of 256 threads.  Timed by the caller, it gives
  * the device's practical HBM read ceiling, next to which the attention kernel's bandwidth is reported.

@@ -60,6 +60,10 @@ _SIGNATURES = {
     "kvq_cache_arena_free_bytes": (C.c_uint64, [C.c_void_p]),
     "kvq_cache_set_reparam": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
     "kvq_calibrate_lambda": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]),
+    "kvq_cache_sensitivity": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.POINTER(C.c_double), C.c_void_p]),
+    "kvq_allocate_bits": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_uint64), C.c_uint64,
+                                    C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_uint64)]),
     "kvq_cache_sq_error": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
     "kvq_stream_read_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p]),
     "kvq_status_string": (C.c_char_p, [C.c_int]),
@@ -93,6 +97,19 @@ def kvq_status_string(status) -> str:
 
 def kvq_arena_bytes(cfg: KvqConfig, payload_bytes: int) -> int:
     return int(load_library().kvq_arena_bytes(C.byref(cfg), int(payload_bytes)))
+
+
+def kvq_allocate_bits(s, mem, budget):
+    """Eq. 6: s, mem [n_blocks][n_choices] (nested sequences or arrays); returns (choices list, total s, total bytes)."""
+    n, c = len(s), len(s[0])
+    sa = (C.c_double * (n * c))(*[float(x) for row in s for x in row])
+    ma = (C.c_uint64 * (n * c))(*[int(x) for row in mem for x in row])
+    ch = (C.c_int32 * n)()
+    ts, tm = C.c_double(), C.c_uint64()
+    st = load_library().kvq_allocate_bits(n, c, sa, ma, int(budget), ch, C.byref(ts), C.byref(tm))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_allocate_bits")
+    return list(ch), ts.value, tm.value
 
 
 def kvq_calibrate_lambda(k_calib, alpha, lam_out, stream=None):
@@ -218,6 +235,13 @@ class KvqCache:
         out = (C.c_double * 2)()
         self._check(self.lib.kvq_cache_sq_error(self.handle, layer, _ptr(k_ref), _ptr(v_ref), out, _stream(stream)),
                     "kvq_cache_sq_error")
+        return float(out[0]), float(out[1])
+
+    def kvq_cache_sensitivity(self, layer, k_ref, v_ref, gk=None, gv=None, stream=None):
+        """(|| G_K * (K - K_hat) ||_1, || G_V * (V - V_hat) ||_1); gradients fp32 device tensors or None (ones)."""
+        out = (C.c_double * 2)()
+        self._check(self.lib.kvq_cache_sensitivity(self.handle, layer, _ptr(k_ref), _ptr(v_ref), _ptr(gk), _ptr(gv), out,
+                                                   _stream(stream)), "kvq_cache_sensitivity")
         return float(out[0]), float(out[1])
 
     def kvq_stream_read_probe(self, buf, n_workgroups, stream=None):

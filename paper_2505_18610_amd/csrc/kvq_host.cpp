@@ -7,6 +7,7 @@
 #include <cstring>
 #include <new>
 #include <set>
+#include <limits>
 #include <vector>
 
 #include "../../include/kvq.h"
@@ -736,19 +737,80 @@ kvq_status_t kvq_calibrate_lambda(const void* k_calib_dev, int32_t batch, int32_
                                 as_stream(hip_stream)) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
 }
 
-kvq_status_t kvq_cache_sq_error(kvq_cache_t* c, int32_t layer, const void* k_ref_dev, const void* v_ref_dev,
-                                double* sq_err_host, void* hip_stream) {
-    if (!c || layer < 0 || layer >= c->cfg.n_layers || !k_ref_dev || !v_ref_dev || !sq_err_host) return KVQ_E_INVALID;
+namespace {
+kvq_status_t cache_error(kvq_cache_t* c, int32_t layer, bool l1, const void* k_ref_dev, const void* v_ref_dev,
+                         const float* gk_dev, const float* gv_dev, double* out_host, void* hip_stream) {
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || !k_ref_dev || !v_ref_dev || !out_host) return KVQ_E_INVALID;
     if (c->dry) return KVQ_E_STATE;
     const Layer& L = c->layers[(size_t)layer];
     if (L.T == 0) return KVQ_E_STATE;
     hipStream_t s = as_stream(hip_stream);
     double* err = reinterpret_cast<double*>(c->arena + c->flags_off + 16);  // two accumulators behind the flags
     if (kvq_launch_fill_u32(reinterpret_cast<uint32_t*>(err), 0u, 4, s) != hipSuccess) return KVQ_E_HIP;
-    if (kvq_launch_sq_error(c->arena, c->table_dev(layer), k_ref_dev, v_ref_dev, L.T, c->tpp, c->units, err, s) != hipSuccess)
+    if (kvq_launch_error(l1, c->arena, c->table_dev(layer), k_ref_dev, v_ref_dev, gk_dev, gv_dev, L.T, c->tpp, c->units,
+                         err, s) != hipSuccess)
         return KVQ_E_HIP;
-    if (hipMemcpyAsync(sq_err_host, err, 2 * sizeof(double), hipMemcpyDeviceToHost, s) != hipSuccess) return KVQ_E_HIP;
+    if (hipMemcpyAsync(out_host, err, 2 * sizeof(double), hipMemcpyDeviceToHost, s) != hipSuccess) return KVQ_E_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return KVQ_E_HIP;
+    return KVQ_OK;
+}
+}  // namespace
+
+kvq_status_t kvq_cache_sq_error(kvq_cache_t* c, int32_t layer, const void* k_ref_dev, const void* v_ref_dev,
+                                double* sq_err_host, void* hip_stream) {
+    return cache_error(c, layer, false, k_ref_dev, v_ref_dev, nullptr, nullptr, sq_err_host, hip_stream);
+}
+
+kvq_status_t kvq_cache_sensitivity(kvq_cache_t* c, int32_t layer, const void* k_ref_dev, const void* v_ref_dev,
+                                   const float* gk_dev, const float* gv_dev, double* s_host, void* hip_stream) {
+    return cache_error(c, layer, true, k_ref_dev, v_ref_dev, gk_dev, gv_dev, s_host, hip_stream);
+}
+
+// Eq. 6 of Sec. 3.2, exactly: multiple-choice knapsack by the list of non-dominated (memory, cost) states
+// (Nemhauser-Ullmann).  After block i the list holds, by increasing memory and strictly decreasing cost, every
+// total that no other choice of widths for blocks 0..i beats in both; a state remembers its predecessor and choice.
+kvq_status_t kvq_allocate_bits(int32_t n_blocks, int32_t n_choices, const double* s, const uint64_t* mem,
+                               uint64_t budget, int32_t* choice_out, double* total_s_out, uint64_t* total_mem_out) {
+    if (n_blocks < 1 || n_blocks > 4096 || n_choices < 1 || n_choices > 16 || !s || !mem || !choice_out) return KVQ_E_INVALID;
+    for (int64_t i = 0; i < (int64_t)n_blocks * n_choices; ++i)
+        if (!(s[i] >= 0.0) || !std::isfinite(s[i])) return KVQ_E_INVALID;
+    struct State { uint64_t m; double cost; int32_t prev; int32_t choice; };
+    const size_t kMaxStates = 1u << 22;
+    std::vector<std::vector<State>> layers((size_t)n_blocks);
+    std::vector<State> cur{State{0, 0.0, -1, -1}}, cand;
+    for (int i = 0; i < n_blocks; ++i) {
+        cand.clear();
+        for (int32_t p = 0; p < (int32_t)cur.size(); ++p)
+            for (int32_t ch = 0; ch < n_choices; ++ch) {
+                const uint64_t m = cur[(size_t)p].m + mem[(size_t)i * n_choices + ch];
+                if (m < cur[(size_t)p].m || m > budget) continue;  // overflow or over budget
+                cand.push_back(State{m, cur[(size_t)p].cost + s[(size_t)i * n_choices + ch], p, ch});
+            }
+        if (cand.empty()) return KVQ_E_BUDGET;
+        // by memory, then cost, then (for reproducible ties) predecessor and choice
+        std::sort(cand.begin(), cand.end(), [](const State& a, const State& b) {
+            if (a.m != b.m) return a.m < b.m;
+            if (a.cost != b.cost) return a.cost < b.cost;
+            if (a.prev != b.prev) return a.prev < b.prev;
+            return a.choice < b.choice;
+        });
+        std::vector<State>& keep = layers[(size_t)i];
+        double best = std::numeric_limits<double>::infinity();
+        for (const State& st : cand)
+            if (st.cost < best) { keep.push_back(st); best = st.cost; }
+        if (keep.size() > kMaxStates) return KVQ_E_OOM;
+        cur = keep;
+    }
+    // the cheapest state is the last one (largest memory within the budget)
+    int32_t at = (int32_t)layers[(size_t)n_blocks - 1].size() - 1;
+    const State fin = layers[(size_t)n_blocks - 1][(size_t)at];
+    for (int i = n_blocks - 1; i >= 0; --i) {
+        const State& st = layers[(size_t)i][(size_t)at];
+        choice_out[i] = st.choice;
+        at = st.prev;
+    }
+    if (total_s_out) *total_s_out = fin.cost;
+    if (total_mem_out) *total_mem_out = fin.m;
     return KVQ_OK;
 }
 

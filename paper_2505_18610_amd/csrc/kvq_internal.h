@@ -60,8 +60,9 @@ hipError_t kvq_launch_quant16(int dst_bits, uint8_t* arena, const KvqRequantJob*
 hipError_t kvq_launch_reparam_store(const float* lambda, float* dst, int n, hipStream_t s);
 hipError_t kvq_launch_calibrate(const void* k, int batch, int n_kv_heads, int n_tokens, float alpha, float floor_,
                                 float* lambda, hipStream_t s);
-hipError_t kvq_launch_sq_error(const uint8_t* arena, const KvqPageDesc* table, const void* k_ref, const void* v_ref,
-                               int n_tokens, int tiles_per_page, int units, double* err, hipStream_t s);
+hipError_t kvq_launch_error(bool l1, const uint8_t* arena, const KvqPageDesc* table, const void* k_ref,
+                            const void* v_ref, const float* gk, const float* gv, int n_tokens, int tiles_per_page,
+                            int units, double* err, hipStream_t s);
 hipError_t kvq_launch_stream_read(const void* buf, size_t bytes, int n_workgroups, uint32_t* sink, hipStream_t s);
 hipError_t kvq_launch_fill_u32(uint32_t* dst, uint32_t value, size_t n, hipStream_t s);
 

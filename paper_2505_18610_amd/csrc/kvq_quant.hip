@@ -708,14 +708,19 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
 }
 
 // --------------------------------------------------------------------------------- reconstruction error
-// grid.x = 2 * tiles (even: K tile, odd: V tile), grid.y = unit, 64 threads.  Adds, over the tile's stored
-// tokens, (x_hat - x)^2 with x_hat = code * S + Z (or the raw value of a 16-bit tile) and x the reference fp16
-// tensor [unit][token][128], into err[0] (K) or err[1] (V).  fp32 inside a tile, fp64 across tiles.
-__global__ __launch_bounds__(64) void kvq_sq_error_kernel(const uint8_t* __restrict__ arena,
-                                                          const KvqPageDesc* __restrict__ table,
-                                                          const uint16_t* __restrict__ k_ref,
-                                                          const uint16_t* __restrict__ v_ref, int n_tokens, int tpp,
-                                                          double* __restrict__ err) {
+// grid.x = 2 * tiles (even: K tile, odd: V tile), grid.y = unit, 64 threads.  Over the tile's stored tokens, with
+// x_hat = code * S + Z (or the raw value of a 16-bit tile) and x the reference fp16 tensor [unit][token][128]:
+//   L1 = false: adds (x_hat - x)^2                       into err[0] (K) or err[1] (V)
+//   L1 = true:  adds |g * (x_hat - x)| (g = 1 if no gradient tensor [unit][token][128] fp32 is given), the terms
+//               of the sensitivity of Sec. 3.2, Eq. 5
+// fp32 inside a tile, fp64 across tiles.
+template <bool L1>
+__global__ __launch_bounds__(64) void kvq_error_kernel(const uint8_t* __restrict__ arena,
+                                                       const KvqPageDesc* __restrict__ table,
+                                                       const uint16_t* __restrict__ k_ref,
+                                                       const uint16_t* __restrict__ v_ref,
+                                                       const float* __restrict__ gk, const float* __restrict__ gv,
+                                                       int n_tokens, int tpp, double* __restrict__ err) {
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1, tile = blockIdx.x >> 1, unit = blockIdx.y;
     const int page = tile / tpp, tip = tile - page * tpp;
@@ -725,7 +730,9 @@ __global__ __launch_bounds__(64) void kvq_sq_error_kernel(const uint8_t* __restr
     const uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * (uint32_t)B);
     const uint16_t* meta = reinterpret_cast<const uint16_t*>(arena + (uint64_t)pd.meta_off256 * 256u +
                                                              tslot * KVQ_META_TILE_BYTES);
-    const uint16_t* ref = (which ? v_ref : k_ref) + (uint64_t)unit * n_tokens * KVQ_D;
+    const uint64_t unit_base = (uint64_t)unit * n_tokens * KVQ_D;
+    const uint16_t* ref = (which ? v_ref : k_ref) + unit_base;
+    const float* grad = which ? gv : gk;
     const int tok0 = tile * KVQ_TILE_TOKENS;
     float acc = 0.f;
     for (int slot = 0; slot < 64; ++slot) {
@@ -752,8 +759,10 @@ __global__ __launch_bounds__(64) void kvq_sq_error_kernel(const uint8_t* __restr
             const int mi = which ? 256 + kvq_vmeta_index(t, g) : t * 4 + g;
             xh = (float)c * h2f(meta[mi]) + h2f(meta[mi + 128]);
         }
-        const float dx = xh - h2f(ref[(uint64_t)(tok0 + t) * KVQ_D + d]);
-        acc += dx * dx;
+        const uint64_t at_ref = (uint64_t)(tok0 + t) * KVQ_D + d;
+        const float dx = xh - h2f(ref[at_ref]);
+        if (L1) acc += fabsf(grad ? grad[unit_base + at_ref] * dx : dx);
+        else acc += dx * dx;
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
@@ -861,12 +870,15 @@ hipError_t kvq_launch_shrink(int dst_bits, int strategy, uint8_t* arena, const K
     return hipGetLastError();
 }
 
-hipError_t kvq_launch_sq_error(const uint8_t* arena, const KvqPageDesc* table, const void* k_ref, const void* v_ref,
-                               int n_tokens, int tiles_per_page, int units, double* err, hipStream_t s) {
+hipError_t kvq_launch_error(bool l1, const uint8_t* arena, const KvqPageDesc* table, const void* k_ref,
+                            const void* v_ref, const float* gk, const float* gv, int n_tokens, int tiles_per_page,
+                            int units, double* err, hipStream_t s) {
     const int n_tiles = (n_tokens + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
-    hipLaunchKernelGGL(kvq_sq_error_kernel, dim3(2 * n_tiles, units), dim3(64), 0, s, arena, table,
-                       static_cast<const uint16_t*>(k_ref), static_cast<const uint16_t*>(v_ref), n_tokens,
-                       tiles_per_page, err);
+    const dim3 grid(2 * n_tiles, units), block(64);
+    const uint16_t* k = static_cast<const uint16_t*>(k_ref);
+    const uint16_t* v = static_cast<const uint16_t*>(v_ref);
+    if (l1) hipLaunchKernelGGL(kvq_error_kernel<true>, grid, block, 0, s, arena, table, k, v, gk, gv, n_tokens, tiles_per_page, err);
+    else hipLaunchKernelGGL(kvq_error_kernel<false>, grid, block, 0, s, arena, table, k, v, gk, gv, n_tokens, tiles_per_page, err);
     return hipGetLastError();
 }
 

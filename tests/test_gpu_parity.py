@@ -208,6 +208,25 @@ def test_channel_reparameterization_matches_oracle():
     check_attention(oc, gc, 0, q)
 
 
+def test_sensitivity_terms_match_oracle():
+    """Sec. 3.2, Eq. 5: || G * (X - Q_b(X)) ||_1 for K and V of a block held at width b, with and without gradient
+    tensors, against the oracle (fp32 inside a tile, fp64 across: relative 1e-5); a ragged last tile is covered."""
+    from oracle import sensitivity
+    B, H, T, P = 2, 2, 427, 64
+    K, V = kvq_synth.make_kv(150, 0, B, H, 0, T)
+    rng = np.random.default_rng(150)
+    GK = rng.standard_normal(K.shape).astype(np.float32)
+    GV = (rng.standard_normal(V.shape) ** 2).astype(np.float32)
+    Kd, Vd, GKd, GVd = dev(K), dev(V), dev(GK), dev(GV)
+    for bits in (16, 8, 4, 2):
+        oc, gc = make_pair(1, B, 2 * H, H, 512, P)
+        append_both(oc, gc, 0, K, V, bits)
+        for gk, gv, gkd, gvd in ((None, None, None, None), (GK, GV, GKd, GVd)):
+            got, want = gc.kvq_cache_sensitivity(0, Kd, Vd, gkd, gvd), sensitivity(K, V, bits, 32, gk, gv)
+            assert got[0] == pytest.approx(want[0], rel=1e-5, abs=1e-12)
+            assert got[1] == pytest.approx(want[1], rel=1e-5, abs=1e-12)
+
+
 @pytest.mark.parametrize("group", [64, 128])
 def test_group_sizes_64_and_128(group):
     """Quantization groups of 64 and 128 channels (128 is the paper's setting, Sec. 4.1.2): ragged appends at every

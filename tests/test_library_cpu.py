@@ -187,3 +187,45 @@ def test_arena_accounting_and_reuse():
         c.kvq_progressive_requant(0, segment=0)
     assert e.value.status == kq.KVQ_E_OOM and c.kvq_cache_describe(0)[0] == [(0, 384, 16)]
     assert c.kvq_cache_arena_free_bytes() == 0
+
+
+# ------------------------------------------------------------------ block-wise memory allocation (Sec. 3.2, Eq. 6)
+def test_allocate_bits_matches_the_oracle_enumeration():
+    """The library's exact solver against the oracle's enumeration of Eq. 6 on random instances (structured and
+    unstructured costs, arbitrary and unit-multiple memory sizes, infeasible budgets), the hand-solved instance, and the
+    Fbit / budget vectors it yields for kvq_cache_create."""
+    from oracle import allocate_bits_bruteforce, allocate_bits_dp
+    rng = np.random.default_rng(5)
+    for trial in range(60):
+        N, C = int(rng.integers(1, 8)), int(rng.integers(1, 5))
+        mem = np.sort(rng.integers(1, 50, (N, C)), 1) * int(rng.choice([1, 7, 4096]))
+        s = -np.sort(-rng.uniform(0, 10, (N, C)), 1) if trial % 4 else rng.uniform(0, 10, (N, C))
+        budget = int(rng.integers(max(0, mem[:, 0].sum() - 3), mem[:, -1].sum() + 3))
+        want = allocate_bits_bruteforce(s, mem, budget)
+        if want[0] is None:
+            with pytest.raises(kq.KvqError) as e:
+                kq.kvq_allocate_bits(s, mem, budget)
+            assert e.value.status == kq.KVQ_E_BUDGET
+            continue
+        ch, cost, m = kq.kvq_allocate_bits(s, mem, budget)
+        assert cost == pytest.approx(want[1], rel=1e-12) and m == want[2] <= budget
+        assert cost == pytest.approx(sum(s[i, c] for i, c in enumerate(ch))) and m == sum(mem[i, c] for i, c in enumerate(ch))
+    s = [[9.0, 1.0], [5.0, 4.0], [7.0, 2.0]]
+    assert kq.kvq_allocate_bits(s, [[1, 2]] * 3, 5) == ([1, 0, 1], 8.0, 5)
+    # a 48-block instance (beyond enumeration) against the knapsack recurrence
+    N, widths = 48, (2, 4, 8)
+    T, units = 32768, 64
+    mem = np.array([[T * units * bytes_per_token_head(b, 128, 32, True) for b in widths]] * N)
+    s = np.stack([rng.uniform(1, 100, N) * f for f in (1.0, 0.22, 0.012)], 1)
+    budget = int(mem[:, 1].sum())                                   # as much memory as uniform 4 bits
+    ch, cost, m = kq.kvq_allocate_bits(s, mem, budget)
+    want = allocate_bits_dp(s, mem, budget)
+    assert cost == pytest.approx(want[1], rel=1e-12) and m <= budget
+    assert cost < s[:, 1].sum()                                      # better than uniform 4 bits
+    fbit = [widths[c] for c in ch]
+    cfg = kq.KvqConfig(N, 8, 40, 8, T, page_tokens=256)
+    cache = kq.KvqCache(cfg, [int(mem[i, c]) for i, c in enumerate(ch)], fbit, arena=None, arena_bytes=1 << 40)
+    cache.close()
+    for bad in (dict(s=[[float("nan")]], mem=[[1]]), dict(s=[[-1.0]], mem=[[1]])):
+        with pytest.raises(kq.KvqError):
+            kq.kvq_allocate_bits(bad["s"], bad["mem"], 10)
