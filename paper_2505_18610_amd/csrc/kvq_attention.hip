@@ -2,8 +2,8 @@
 //
 // One workgroup (8 wavefronts, one per compute unit) handles one (sequence, KV head) unit and one cost-balanced
 // range of 32-token tiles; its wavefronts claim two-tile chunks of the range from a counter in LDS, stream
-// them with 16-byte loads and keep their own online-softmax state.  Both contractions run on the matrix cores with the g <= 16 query heads of the unit
-// as the 16-wide N dimension:
+// them with 16-byte non-temporal loads and keep their own online-softmax state.  Both contractions run on the
+// matrix cores with the g <= 16 query heads of the unit as the 16-wide N dimension:
 //   scores^T[token, head] = sum_grp S[token,grp] * (codes[token, grp-channels] . q[head, grp-channels])
 //                           + sum_grp Z[token,grp] * sum(q[head, grp-channels])
 //   out^T[channel, head] += sum_token codes[token, channel] * (p[token, head] * S_v[token, grp(channel)])
@@ -875,7 +875,7 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
         ctx.n_chunks = (ctx.hi - ctx.lo + ctx.tpc - 1) / ctx.tpc;
         if (ctx.n_chunks <= 0) continue;
         // the first chunk of every wavefront is its own index (the counter starts behind them); from then on
-        // chunks are claimed, always two ahead of the arithmetic
+        // chunks are claimed one at a time
         ctx.next_static = P.deterministic ? wave + KVQ_ATTN_WAVES : -1;
         start_desc(ctx, wave);
         ctx.next = finish_desc(ctx);
