@@ -404,6 +404,26 @@ def test_split_count_and_merge_variant_invariance():
             assert np.abs(o - ref).max() <= 5e-4, (fused, n, np.abs(o - ref).max())
 
 
+def test_ranges_longer_than_the_descriptor_window():
+    """A workgroup keeps 256 page descriptors in LDS at a time; one split over 300 pages (and two over 150 + 150
+    with odd tile counts) walks several windows.  Mixed widths, odd pages of 96 tokens (three tiles: single-tile
+    chunks), deterministic and dynamic claiming."""
+    B, H, P, n_pages = 1, 1, 96, 300
+    T = P * n_pages - 17
+    K, V = kvq_synth.make_kv(160, 0, B, H, 0, T)
+    oc, gc = make_pair(1, B, 4 * H, H, P * n_pages, P)
+    t = 0
+    for n, bits in ((P * 90, 2), (P * 60, 4), (P * 100, 8), (T - P * 250, 16)):
+        append_both(oc, gc, 0, K[:, :, t:t + n], V[:, :, t:t + n], bits)
+        t += n
+    q = kvq_synth.make_q(160, 0, B, 4 * H, T - 1)
+    for det in (0, 1):
+        gc.kvq_cache_set_option(kq.KVQ_OPT_DETERMINISTIC, det)
+        for n in (1, 2, 3, 0):
+            gc.kvq_cache_set_option(kq.KVQ_OPT_SPLITS, n)
+            check_attention(oc, gc, 0, q)
+
+
 def test_softmax_scale_and_multi_layer():
     B, H, T, P = 1, 2, 300, 64
     oc, gc = make_pair(3, B, 2 * H, H, 512, P)
