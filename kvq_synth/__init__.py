@@ -38,6 +38,14 @@ def _unit_rng(seed: int, layer: int, b: int, h: int, stream: int) -> np.random.G
     return np.random.default_rng([int(seed), int(layer), int(b), int(h), int(stream)])
 
 
+def rope_tables(positions: np.ndarray, base: float, d: int = HEAD_DIM):
+    """cos(m theta_i), sin(m theta_i) as fp32 [len(positions), d/2], theta_i = base ** (-2 i / d) (Sec. 3.3, Eq. 9);
+    positions may be fractional (interpolated, Eq. 10).  Angles and functions are evaluated in fp64."""
+    i = np.arange(d // 2, dtype=np.float64)
+    ang = np.asarray(positions, np.float64)[:, None] * (base ** (-2.0 * i / d))[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
 def outlier_channels(seed: int, h: int, d: int = HEAD_DIM, n_out: int = 4) -> np.ndarray:
     """The seeded outlier channel set of KV head h (same set for every token and layer)."""
     return np.sort(np.random.default_rng([int(seed), 9001, int(h)]).choice(d, n_out, replace=False))

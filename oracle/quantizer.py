@@ -101,6 +101,23 @@ def reparam_queries(q: np.ndarray, lam: np.ndarray, n_kv_heads: int) -> np.ndarr
     return out
 
 
+def rope_rotate_keys(K: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+    """Rotary embedding of un-rotated keys (Sec. 3.3, Eq. 9), channel i paired with i + D/2:
+        K~_i       = K_i cos_i - K_{i+D/2} sin_i
+        K~_{i+D/2} = K_i sin_i + K_{i+D/2} cos_i
+    K: fp16 [batch, n_kv_heads, T, D]; cos, sin: fp32 [T, D/2], the values of cos(m theta_i), sin(m theta_i) for the
+    T token positions (inputs: whoever produces them decides positions, base and interpolation).  Every product
+    and the sum are separate IEEE fp32 operations (no fused multiply-add); the result is rounded to fp16."""
+    assert K.dtype == np.float16 and cos.dtype == np.float32 and sin.dtype == np.float32
+    half = K.shape[-1] // 2
+    assert cos.shape == sin.shape == (K.shape[2], half)
+    a, b = K[..., :half].astype(np.float32), K[..., half:].astype(np.float32)
+    c, s = cos[None, None], sin[None, None]
+    lo = (a * c).astype(np.float32) - (b * s).astype(np.float32)
+    hi = (a * s).astype(np.float32) + (b * c).astype(np.float32)
+    return np.concatenate([lo, hi], -1).astype(np.float16)
+
+
 SHIFT_EQUIVALENT, SHIFT_DIRECT, SHIFT_MODIFIED = 0, 1, 2
 
 

@@ -229,3 +229,26 @@ def test_shift_strategies_reconstruction_error_ordering_on_uniform_codes():
 def round_half_up(x):
     import math
     return math.floor(x + 0.5)
+
+
+# ------------------------------------------------------------------------------- rotary embedding of the keys (Eq. 9)
+def test_rope_rotation_of_keys():
+    """The fp32 rotation agrees with the fp64 rotation of the input generator to fp16 rounding, keeps the norm of
+    every (i, i + D/2) pair, is the identity at position 0, and a quarter turn swaps the pair with a sign."""
+    import kvq_synth
+    from oracle import rope_rotate_keys
+    rng = np.random.default_rng(9)
+    K = rng.standard_normal((1, 2, 40, 128)).astype(np.float16)
+    pos = np.arange(1000, 1040)
+    cos, sin = kvq_synth.rope_tables(pos, 1.0e4)
+    got = rope_rotate_keys(K, cos, sin).astype(np.float64)
+    want = kvq_synth.rope_rotate(K.astype(np.float64), pos, 1.0e4)
+    assert np.abs(got - want).max() <= 2.0 ** -10 * np.abs(want).max()
+    n0 = K.astype(np.float64)[..., :64] ** 2 + K.astype(np.float64)[..., 64:] ** 2
+    n1 = got[..., :64] ** 2 + got[..., 64:] ** 2
+    assert np.allclose(n0, n1, rtol=4e-3, atol=1e-5)
+    c0, s0 = kvq_synth.rope_tables(np.zeros(40), 1.0e4)
+    assert np.array_equal(rope_rotate_keys(K, c0, s0), K)
+    cq, sq = np.zeros((40, 64), np.float32), np.ones((40, 64), np.float32)      # quarter turn: (a, b) -> (-b, a)
+    r = rope_rotate_keys(K, cq, sq)
+    assert np.array_equal(r[..., :64], -K[..., 64:]) and np.array_equal(r[..., 64:], K[..., :64])
