@@ -102,6 +102,16 @@ void kvq_cache_destroy(kvq_cache_t* cache);
 kvq_status_t kvq_quantize_append(kvq_cache_t* cache, int32_t layer, const void* k_dev, const void* v_dev,
                                  int32_t n_new, int32_t entry_bits, void* hip_stream);
 
+/* kvq_quantize_append for keys that do not carry RoPE yet: the rotation of Sec. 3.3, Eq. 9 (channel i paired with
+ * i + 64) is applied to every new key inside the append kernel, before the reparameterization and Eq. 1-2:
+ *   K~_i = K_i cos_i - K_{i+64} sin_i,  K~_{i+64} = K_i sin_i + K_{i+64} cos_i    (i = 0..63),
+ * each product and the sum a separate fp32 operation, the result rounded to fp16 - exactly what the plain call stores
+ * when it is handed keys rotated that way.  cos_sin_dev: device, fp32 [n_new][128]: row r holds cos(m theta_i), i = 0..63,
+ * then sin(m theta_i), for the position m of the r-th new token (the caller chooses positions, base and any positional
+ * interpolation, Eq. 10).  NULL makes the call identical to kvq_quantize_append.  V is not rotated. */
+kvq_status_t kvq_quantize_append_rope(kvq_cache_t* cache, int32_t layer, const void* k_dev, const void* v_dev,
+                                      int32_t n_new, int32_t entry_bits, const float* cos_sin_dev, void* hip_stream);
+
 /* Progressive bit-width shrinking (Sec. 3.1 Eq. 3, appendix theorem):
  *   X_b = ((2^2b - 2^b + 1)(X_2b + 2^(b-1))) >> 3b,  S_b = fp16((2^b + 1) S_2b),  Z_b = Z_2b;
  *   pages still holding raw fp16 values are quantized directly to 8 bits (Eq. 1-2), which by the theorem

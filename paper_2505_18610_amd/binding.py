@@ -50,6 +50,8 @@ _SIGNATURES = {
                                    C.c_uint64, C.POINTER(C.c_void_p)]),
     "kvq_cache_destroy": (None, [C.c_void_p]),
     "kvq_quantize_append": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]),
+    "kvq_quantize_append_rope": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                           C.c_void_p, C.c_void_p]),
     "kvq_progressive_requant": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32)]),
     "kvq_decode_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]),
     "kvq_cache_describe": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(_SegmentInfo), C.c_int32, C.POINTER(C.c_int32),
@@ -181,6 +183,12 @@ class KvqCache:
             n_new = k.shape[2]
         self._check(self.lib.kvq_quantize_append(self.handle, layer, _ptr(k), _ptr(v), n_new, entry_bits,
                                                  _stream(stream)), "kvq_quantize_append")
+
+    def kvq_quantize_append_rope(self, layer, k, v, cos_sin, entry_bits=0, stream=None):
+        """k: un-rotated keys; cos_sin: fp32 device tensor [n_new, 128] (cos 64 | sin 64 per new token)."""
+        assert tuple(cos_sin.shape) == (k.shape[2], 128)
+        self._check(self.lib.kvq_quantize_append_rope(self.handle, layer, _ptr(k), _ptr(v), k.shape[2], entry_bits,
+                                                      _ptr(cos_sin), _stream(stream)), "kvq_quantize_append_rope")
 
     def kvq_progressive_requant(self, layer, segment=-1, reserve_tokens=0, stream=None) -> int:
         n = C.c_int32(0)

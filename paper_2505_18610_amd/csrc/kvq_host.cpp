@@ -418,6 +418,11 @@ void kvq_cache_destroy(kvq_cache_t* c) {
 
 kvq_status_t kvq_quantize_append(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev,
                                  int32_t n_new, int32_t entry_bits, void* hip_stream) {
+    return kvq_quantize_append_rope(c, layer, k_dev, v_dev, n_new, entry_bits, nullptr, hip_stream);
+}
+
+kvq_status_t kvq_quantize_append_rope(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev,
+                                      int32_t n_new, int32_t entry_bits, const float* cos_sin_dev, void* hip_stream) {
     if (!c || layer < 0 || layer >= c->cfg.n_layers || n_new < 0) return KVQ_E_INVALID;
     if (entry_bits != 0 && !valid_bits(entry_bits)) return KVQ_E_INVALID;
     if (n_new == 0) return KVQ_OK;
@@ -499,7 +504,8 @@ kvq_status_t kvq_quantize_append(kvq_cache_t* c, int32_t layer, const void* k_de
         }
         if (kvq_launch_append(e, c->arena, c->table_dev(layer), k_dev, v_dev, t_old, n_new, c->tpp, c->units,
                               by_arg ? two : nullptr, pg0, c->flags_dev(), c->cfg.group,
-                              L.reparam ? c->lambda_dev(layer) + c->cfg.n_kv_heads * KVQ_D : nullptr, c->cfg.n_kv_heads, s) != hipSuccess)
+                              L.reparam ? c->lambda_dev(layer) + c->cfg.n_kv_heads * KVQ_D : nullptr, c->cfg.n_kv_heads,
+                              cos_sin_dev, s) != hipSuccess)
             return KVQ_E_HIP;
     }
     if (!evicted.empty()) {

@@ -50,7 +50,7 @@ struct KvqAttnParams {
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
                              const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group,
-                             const float* rinv, int n_kv_heads, hipStream_t s);
+                             const float* rinv, int n_kv_heads, const float* rope, hipStream_t s);
 hipError_t kvq_launch_shrink(int dst_bits, int strategy, uint8_t* arena, const KvqRequantJob* jobs_dev,
                              const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
                              uint32_t* flags, hipStream_t s);

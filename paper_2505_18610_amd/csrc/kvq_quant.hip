@@ -29,6 +29,35 @@ __device__ inline u32x4 scale_keys8(u32x4 v, const float* rinv) {
                  scale_pair(v.w, r1.z, r1.w)};
 }
 
+// Rotary embedding (Sec. 3.3, Eq. 9) of 8 consecutive channels ch0 .. ch0+7 of one token: own = these channels,
+// partner = the channels ch0 +- 64 of the same token, cs = the token's table row [cos 64 | sin 64] (fp32).
+//   lower half (ch < 64):  own * cos - partner * sin        upper half:  own * cos + partner * sin
+// Every product and the sum are separate fp32 operations (the empty asm keeps them from being contracted or
+// fused with the conversion); the result is rounded to fp16.
+__device__ inline u32x4 rope8(u32x4 own, u32x4 partner, const float* cs, int ch0) {
+    const int i0 = ch0 & 63;
+    const bool upper = ch0 >= 64;
+    const uint32_t* o = reinterpret_cast<const uint32_t*>(&own);
+    const uint32_t* p = reinterpret_cast<const uint32_t*>(&partner);
+    u32x4 out;
+    uint32_t* r = reinterpret_cast<uint32_t*>(&out);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float res[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float c = cs[i0 + 2 * e + h], sn = cs[64 + i0 + 2 * e + h];
+            float p1 = h2f((uint16_t)(o[e] >> (16 * h))) * c, p2 = h2f((uint16_t)(p[e] >> (16 * h))) * sn;
+            asm volatile("" : "+v"(p1), "+v"(p2));
+            float sum = upper ? p1 + p2 : p1 - p2;
+            asm volatile("" : "+v"(sum));
+            res[h] = sum;
+        }
+        r[e] = (uint32_t)f2h_rn(res[0]) | ((uint32_t)f2h_rn(res[1]) << 16);
+    }
+    return out;
+}
+
 // (S, Z) of one group from its min and max (both exact fp16 values held as float), Eq. 2.
 __device__ inline void group_params(float mn, float mx, int levels, uint16_t* S, uint16_t* Z, float* Sf) {
     float s32 = (mx - mn) / (float)levels;  // one fp32 subtract, one correctly rounded fp32 divide
@@ -355,7 +384,8 @@ __global__ __launch_bounds__(64) void kvq_append_kernel(uint8_t* __restrict__ ar
                                                         const uint16_t* __restrict__ k_in,
                                                         const uint16_t* __restrict__ v_in, int t_old,
                                                         int n_new, int tpp, int tile0, KvqAppendPages ap,
-                                                        const float* __restrict__ rinv, int n_kv_heads) {
+                                                        const float* __restrict__ rinv, int n_kv_heads,
+                                                        const float* __restrict__ rope) {
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
     const int tile = tile0 + (blockIdx.x >> 1);
@@ -381,7 +411,11 @@ __global__ __launch_bounds__(64) void kvq_append_kernel(uint8_t* __restrict__ ar
             for (int grp = 0; grp < 4; ++grp) {
                 u32x4 v = {0u, 0u, 0u, 0u};
                 if (isnew) {
-                    v = *reinterpret_cast<const u32x4*>(in + (uint64_t)(tok - t_old) * KVQ_D + 32 * grp + 8 * j);
+                    const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
+                    v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * j);
+                    if (rope)
+                        v = rope8(v, *reinterpret_cast<const u32x4*>(row + ((32 * grp + 8 * j) ^ 64)),
+                                  rope + (uint64_t)(tok - t_old) * KVQ_D, 32 * grp + 8 * j);
                     if (rinv) v = scale_keys8(v, rinv + (unit % n_kv_heads) * KVQ_D + 32 * grp + 8 * j);
                 }
                 int s0 = (sub * 4 + grp) * 8;
@@ -472,7 +506,8 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
                                                           const uint16_t* __restrict__ v_in, int t_old,
                                                           int n_new, int tpp, int tile0, KvqAppendPages ap,
                                                           uint32_t* __restrict__ flags, int gspan,
-                                                          const float* __restrict__ rinv, int n_kv_heads) {
+                                                          const float* __restrict__ rinv, int n_kv_heads,
+                                                          const float* __restrict__ rope) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
@@ -496,7 +531,11 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
         for (int c = 0; c < 4; ++c) {
             u32x4 v = {0u, 0u, 0u, 0u};
             if (isnew) {
-                v = *reinterpret_cast<const u32x4*>(in + (uint64_t)(tok - t_old) * KVQ_D + 32 * grp + 8 * c);
+                const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
+                v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
+                if (rope && !which)
+                    v = rope8(v, *reinterpret_cast<const u32x4*>(row + ((32 * grp + 8 * c) ^ 64)),
+                              rope + (uint64_t)(tok - t_old) * KVQ_D, 32 * grp + 8 * c);
                 if (rinv && !which) v = scale_keys8(v, rinv + (unit % n_kv_heads) * KVQ_D + 32 * grp + 8 * c);
             }
             w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
@@ -820,7 +859,7 @@ __global__ void kvq_fill_u32_kernel(uint32_t* dst, uint32_t value, size_t n) {
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
                              const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group,
-                             const float* rinv, int n_kv_heads, hipStream_t s) {
+                             const float* rinv, int n_kv_heads, const float* rope, hipStream_t s) {
     const int gspan = group / KVQ_G;
     int tile0 = t_old / KVQ_TILE_TOKENS;
     int tile1 = (t_old + n_new + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
@@ -832,10 +871,10 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
     ap.d[0] = first_two ? first_two[0] : KvqPageDesc{0, 0, 0, 0};
     ap.d[1] = first_two ? first_two[1] : KvqPageDesc{0, 0, 0, 0};
     switch (bits) {
-        case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, rinv, n_kv_heads); break;
-        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads); break;
-        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads); break;
-        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads); break;
+        case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, rinv, n_kv_heads, rope); break;
+        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
+        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
+        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -227,6 +227,35 @@ def test_sensitivity_terms_match_oracle():
             assert got[1] == pytest.approx(want[1], rel=1e-5, abs=1e-12)
 
 
+def test_rope_fused_into_the_append():
+    """Un-rotated keys plus cos/sin rows of the new tokens' positions: the append kernels rotate (Sec. 3.3, Eq. 9)
+    before quantizing, bit-identically to the oracle's fp32 rotation followed by a plain append - at every width,
+    across ragged chunks, with the channel-wise reparameterization on top, and with interpolated positions."""
+    from oracle import rope_rotate_keys, calibrate_lambda
+    B, H, g, T, P = 2, 2, 2, 333, 64
+    rng = np.random.default_rng(170)
+    K0 = (rng.standard_normal((B, H, T, 128)) * np.where(np.arange(128) % 37 == 0, 12.0, 1.0)).astype(np.float16)
+    V = rng.standard_normal((B, H, T, 128)).astype(np.float16)
+    for scale, use_lambda in ((1.0, False), (7.5, True)):
+        cos, sin = kvq_synth.rope_tables(scale * np.arange(T), 1.0e6)
+        Krot = rope_rotate_keys(K0, cos, sin)
+        cs = dev(np.concatenate([cos, sin], 1))
+        lam = calibrate_lambda(Krot[:, :, :128], 0.5) if use_lambda else None
+        q = kvq_synth.make_q(170, 0, B, H * g, T - 1)
+        for bits in (16, 8, 4, 2):
+            oc, gc = make_pair(1, B, H * g, H, 512, P)
+            if use_lambda:
+                oc.set_reparam(0, lam)
+                gc.kvq_cache_set_reparam(0, dev(lam))
+            t = 0
+            for n in (1, 63, 200, 69):
+                oc.append(0, Krot[:, :, t:t + n], V[:, :, t:t + n], bits)
+                gc.kvq_quantize_append_rope(0, dev(K0[:, :, t:t + n]), dev(V[:, :, t:t + n]), cs[t:t + n].contiguous(), bits)
+                t += n
+            assert_same_cache(oc, gc, 0)
+            check_attention(oc, gc, 0, q)
+
+
 @pytest.mark.parametrize("group", [64, 128])
 def test_group_sizes_64_and_128(group):
     """Quantization groups of 64 and 128 channels (128 is the paper's setting, Sec. 4.1.2): ragged appends at every
