@@ -5,58 +5,14 @@
 // All kernels work directly in the tile layout described in kvq_layout.h: one wavefront owns one tile and
 // every lane quantizes the 64 slots it will later feed to the matrix cores.
 #include "kvq_internal.h"
+#include "kvq_append16.h"
 
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ inline float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
-__device__ inline uint16_t f2h_rn(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }  // RNE
-
-// K Lambda^{-1} of Eq. 7 on 8 consecutive channels (4 dwords of fp16 pairs): fp32 product with the channel's
-// reciprocal factor, rounded to nearest-even into fp16.
-// The product is rounded to fp32 first and to fp16 second, as two separate IEEE operations: the empty asm keeps the
-// compiler from fusing them into a mixed-precision instruction that rounds the exact product once (1 fp16 ulp apart
-// in about one element of 10^4).
-__device__ inline uint32_t scale_pair(uint32_t w, float r_lo, float r_hi) {
-    float lo = h2f((uint16_t)(w & 0xffff)) * r_lo, hi = h2f((uint16_t)(w >> 16)) * r_hi;
-    asm volatile("" : "+v"(lo), "+v"(hi));
-    return (uint32_t)f2h_rn(lo) | ((uint32_t)f2h_rn(hi) << 16);
-}
-__device__ inline u32x4 scale_keys8(u32x4 v, const float* rinv) {
-    const float4 r0 = *reinterpret_cast<const float4*>(rinv), r1 = *reinterpret_cast<const float4*>(rinv + 4);
-    return u32x4{scale_pair(v.x, r0.x, r0.y), scale_pair(v.y, r0.z, r0.w), scale_pair(v.z, r1.x, r1.y),
-                 scale_pair(v.w, r1.z, r1.w)};
-}
-
-// Rotary embedding (Sec. 3.3, Eq. 9) of 8 consecutive channels ch0 .. ch0+7 of one token: own = these channels,
-// partner = the channels ch0 +- 64 of the same token, cs = the token's table row [cos 64 | sin 64] (fp32).
-//   lower half (ch < 64):  own * cos - partner * sin        upper half:  own * cos + partner * sin
-// Every product and the sum are separate fp32 operations (the empty asm keeps them from being contracted or
-// fused with the conversion); the result is rounded to fp16.
-__device__ inline u32x4 rope8(u32x4 own, u32x4 partner, const float* cs, int ch0) {
-    const int i0 = ch0 & 63;
-    const bool upper = ch0 >= 64;
-    const uint32_t* o = reinterpret_cast<const uint32_t*>(&own);
-    const uint32_t* p = reinterpret_cast<const uint32_t*>(&partner);
-    u32x4 out;
-    uint32_t* r = reinterpret_cast<uint32_t*>(&out);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        float res[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const float c = cs[i0 + 2 * e + h], sn = cs[64 + i0 + 2 * e + h];
-            float p1 = h2f((uint16_t)(o[e] >> (16 * h))) * c, p2 = h2f((uint16_t)(p[e] >> (16 * h))) * sn;
-            asm volatile("" : "+v"(p1), "+v"(p2));
-            float sum = upper ? p1 + p2 : p1 - p2;
-            asm volatile("" : "+v"(sum));
-            res[h] = sum;
-        }
-        r[e] = (uint32_t)f2h_rn(res[0]) | ((uint32_t)f2h_rn(res[1]) << 16);
-    }
-    return out;
-}
+using kvq_dev::u32x4;
+using kvq_dev::h2f;
+using kvq_dev::f2h_rn;
+using kvq_dev::load_key8;
 
 // (S, Z) of one group from its min and max (both exact fp16 values held as float), Eq. 2.
 __device__ inline void group_params(float mn, float mx, int levels, uint16_t* S, uint16_t* Z, float* Sf) {
@@ -73,69 +29,6 @@ __device__ inline uint32_t code_of(float x, float mn, float Sf, int levels) {
     return (uint32_t)r;
 }
 
-// K tile: slot s = p*8 + i with p = sub*4 + grp; a group = the 8 slots of p in the 4 lanes that differ in j.
-template <int B>
-__device__ inline void quantize_k(const float (&x)[64], uint32_t (&str)[2 * B], uint16_t (&S)[8],
-                                  uint16_t (&Z)[8]) {
-    constexpr int levels = (1 << B) - 1;
-#pragma unroll
-    for (int d = 0; d < 2 * B; ++d) str[d] = 0u;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) {
-        float mn = x[p * 8], mx = x[p * 8];
-#pragma unroll
-        for (int i = 1; i < 8; ++i) {
-            mn = fminf(mn, x[p * 8 + i]);
-            mx = fmaxf(mx, x[p * 8 + i]);
-        }
-        mn = fminf(mn, __shfl_xor(mn, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mn = fminf(mn, __shfl_xor(mn, 32));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        float Sf;
-        group_params(mn, mx, levels, &S[p], &Z[p], &Sf);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            uint32_t c = code_of(x[p * 8 + i], mn, Sf, levels);
-            int bit = (p * 8 + i) * B;
-            str[bit >> 5] |= c << (bit & 31);
-        }
-    }
-}
-
-// V tile: slot s = nt*8 + i (token 8j+i, channel 16nt+n); group (i, g) = slots (2g, i), (2g+1, i) in the 16
-// lanes of one quarter.  S/Z index = i*4 + g.
-template <int B>
-__device__ inline void quantize_v(const float (&x)[64], uint32_t (&str)[2 * B], uint16_t (&S)[32],
-                                  uint16_t (&Z)[32]) {
-    constexpr int levels = (1 << B) - 1;
-#pragma unroll
-    for (int d = 0; d < 2 * B; ++d) str[d] = 0u;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            float a = x[(2 * g) * 8 + i], b = x[(2 * g + 1) * 8 + i];
-            float mn = fminf(a, b), mx = fmaxf(a, b);
-#pragma unroll
-            for (int m = 1; m < 16; m <<= 1) {
-                mn = fminf(mn, __shfl_xor(mn, m));
-                mx = fmaxf(mx, __shfl_xor(mx, m));
-            }
-            float Sf;
-            group_params(mn, mx, levels, &S[i * 4 + g], &Z[i * 4 + g], &Sf);
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                int nt = 2 * g + h;
-                uint32_t c = code_of(h ? b : a, mn, Sf, levels);
-                int bit = (nt * 8 + i) * B;
-                str[bit >> 5] |= c << (bit & 31);
-            }
-        }
-    }
-}
-
-// Mask of the bits of string dword `dw` of a V lane that belong to tokens flagged in kb (bit i = token 8j+i).
 template <int B>
 __device__ inline uint32_t v_token_mask(uint32_t kb, int dw) {
     constexpr int per = 32 / B;  // slots per dword
@@ -181,42 +74,6 @@ __device__ inline void store_chunks_stream(uint8_t* tile, int lane, const uint32
     for (int c = 0; c < B / 2; ++c) {
         u32x4 v = {str[4 * c], str[4 * c + 1], str[4 * c + 2], str[4 * c + 3]};
         __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(tile + (c * 64 + lane) * 16));
-    }
-}
-
-// keep_k: bit sub set = the token of sub-tile `sub` of this lane must keep its stored value
-__device__ inline void store_meta_k(uint8_t* meta, int lane, const uint16_t (&S)[8], const uint16_t (&Z)[8],
-                                    uint32_t keep_k) {
-    int j = lane >> 4, n = lane & 15;
-    uint16_t* ms = reinterpret_cast<uint16_t*>(meta);
-    uint16_t* mz = reinterpret_cast<uint16_t*>(meta + 256);
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-        if ((keep_k >> sub) & 1u) continue;
-        int t = 8 * (n >> 2) + 4 * sub + (n & 3);
-        uint16_t s = 0, z = 0;
-#pragma unroll
-        for (int grp = 0; grp < 4; ++grp)
-            if (grp == j) { s = S[sub * 4 + grp]; z = Z[sub * 4 + grp]; }
-        ms[t * 4 + j] = s;
-        mz[t * 4 + j] = z;
-    }
-}
-// keep_v: bit i set = token 8j+i keeps its stored value
-__device__ inline void store_meta_v(uint8_t* meta, int lane, const uint16_t (&S)[32], const uint16_t (&Z)[32],
-                                    uint32_t keep_v) {
-    int j = lane >> 4, n = lane & 15;
-    uint16_t* ms = reinterpret_cast<uint16_t*>(meta + 512);
-    uint16_t* mz = reinterpret_cast<uint16_t*>(meta + 768);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        if (n != i || ((keep_v >> i) & 1u)) continue;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            int idx = kvq_vmeta_index(8 * j + i, g);
-            ms[idx] = S[i * 4 + g];
-            mz[idx] = Z[i * 4 + g];
-        }
     }
 }
 
@@ -376,126 +233,25 @@ __device__ inline KvqPageDesc append_desc(const KvqPageDesc* table, const KvqApp
 }
 
 // grid.x = 2 * (tiles touched) (even: K tile, odd: V tile), grid.y = (sequence, KV head) unit, 64 threads.
-// Writes every slot of every touched tile: stored tokens keep their bits, new tokens are quantized (or
-// copied for B = 16), slots past the new end are zeroed so that partially filled tiles stay well defined.
-template <int B>
-__global__ __launch_bounds__(64) void kvq_append_kernel(uint8_t* __restrict__ arena,
-                                                        const KvqPageDesc* __restrict__ table,
-                                                        const uint16_t* __restrict__ k_in,
-                                                        const uint16_t* __restrict__ v_in, int t_old,
-                                                        int n_new, int tpp, int tile0, KvqAppendPages ap,
-                                                        const float* __restrict__ rinv, int n_kv_heads,
-                                                        const float* __restrict__ rope) {
-    const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
+// Append into the 16-bit tier: the new rows are copied into the tile layout.
+__global__ __launch_bounds__(64) void kvq_append16_kernel(uint8_t* __restrict__ arena,
+                                                          const KvqPageDesc* __restrict__ table,
+                                                          const uint16_t* __restrict__ k_in,
+                                                          const uint16_t* __restrict__ v_in, int t_old,
+                                                          int n_new, int tpp, int tile0, KvqAppendPages ap,
+                                                          const float* __restrict__ rinv, int n_kv_heads,
+                                                          const float* __restrict__ rope) {
+    const int lane = threadIdx.x;
     const int which = blockIdx.x & 1;
     const int tile = tile0 + (blockIdx.x >> 1);
     const int unit = blockIdx.y;
     const int page = tile / tpp, tip = tile - page * tpp;
     const KvqPageDesc pd = append_desc(table, ap, page);
     const uint64_t tslot = (uint64_t)unit * tpp + tip;
-    uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * B);
-    uint8_t* meta = arena + (uint64_t)pd.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
-    const int t_new = t_old + n_new, tok0 = tile * KVQ_TILE_TOKENS;
+    uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * 16);
     const uint16_t* in = (which ? v_in : k_in) + (uint64_t)unit * n_new * KVQ_D;
-    const bool has_old = tok0 < t_old;
-
-    uint16_t raw[64];
-    uint32_t keep = 0;  // K: per sub; V: per token of the quarter
-    if (!which) {
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            int tok = tok0 + 8 * (n >> 2) + 4 * sub + (n & 3);
-            bool isnew = tok >= t_old && tok < t_new;
-            if (tok < t_old) keep |= 1u << sub;
-#pragma unroll
-            for (int grp = 0; grp < 4; ++grp) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (isnew) {
-                    const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
-                    v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * j);
-                    if (rope)
-                        v = rope8(v, *reinterpret_cast<const u32x4*>(row + ((32 * grp + 8 * j) ^ 64)),
-                                  rope + (uint64_t)(tok - t_old) * KVQ_D, 32 * grp + 8 * j);
-                    if (rinv) v = scale_keys8(v, rinv + (unit % n_kv_heads) * KVQ_D + 32 * grp + 8 * j);
-                }
-                int s0 = (sub * 4 + grp) * 8;
-                raw[s0 + 0] = v.x & 0xffff; raw[s0 + 1] = v.x >> 16;
-                raw[s0 + 2] = v.y & 0xffff; raw[s0 + 3] = v.y >> 16;
-                raw[s0 + 4] = v.z & 0xffff; raw[s0 + 5] = v.z >> 16;
-                raw[s0 + 6] = v.w & 0xffff; raw[s0 + 7] = v.w >> 16;
-            }
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int tok = tok0 + 8 * j + i;
-            bool isnew = tok >= t_old && tok < t_new;
-            if (tok < t_old) keep |= 1u << i;
-#pragma unroll
-            for (int nt = 0; nt < 8; ++nt)
-                raw[nt * 8 + i] = isnew ? in[(uint64_t)(tok - t_old) * KVQ_D + 16 * nt + n] : (uint16_t)0;
-        }
-    }
-
-    uint32_t str[2 * B];
-    if constexpr (B == 16) {
-#pragma unroll
-        for (int d = 0; d < 32; ++d) str[d] = (uint32_t)raw[2 * d] | ((uint32_t)raw[2 * d + 1] << 16);
-    } else {
-        float x[64];
-#pragma unroll
-        for (int s = 0; s < 64; ++s) x[s] = h2f(raw[s]);
-        if (!which) {
-            uint16_t S[8], Z[8];
-            quantize_k<B>(x, str, S, Z);
-            store_meta_k(meta, lane, S, Z, keep);
-        } else {
-            uint16_t S[32], Z[32];
-            quantize_v<B>(x, str, S, Z);
-            store_meta_v(meta, lane, S, Z, keep);
-        }
-    }
-    if constexpr (B == 16) {
-        if (has_old) {
-            // the tile was written in full (zero tail included) when its first token arrived: store only the
-            // new tokens' elements -- whole 16-byte chunks for K, single fp16 values for V
-            if (!which) {
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub) {
-                    const int tok = tok0 + 8 * (n >> 2) + 4 * sub + (n & 3);
-                    if (tok >= t_old && tok < t_new) {
-#pragma unroll
-                        for (int c = 4 * sub; c < 4 * sub + 4; ++c)
-                            *reinterpret_cast<u32x4*>(code + (c * 64 + lane) * 16) =
-                                u32x4{str[4 * c], str[4 * c + 1], str[4 * c + 2], str[4 * c + 3]};
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int tok = tok0 + 8 * j + i;
-                    if (tok >= t_old && tok < t_new) {
-#pragma unroll
-                        for (int nt = 0; nt < 8; ++nt) {
-                            const int slot = nt * 8 + i;  // 2 bytes at string offset 2*slot
-                            *reinterpret_cast<uint16_t*>(code + kvq_tile_byte(lane, 2u * slot)) = raw[slot];
-                        }
-                    }
-                }
-            }
-            return;
-        }
-    }
-    if (has_old && keep) {
-        uint32_t old[2 * B];
-        load_chunks<B>(code, lane, old);
-#pragma unroll
-        for (int d = 0; d < 2 * B; ++d) {
-            uint32_t m = which ? v_token_mask<B>(keep, d) : (((keep >> (d / B)) & 1u) ? 0xffffffffu : 0u);
-            str[d] = (old[d] & m) | (str[d] & ~m);
-        }
-    }
-    store_chunks<B>(code, lane, str);
+    kvq_dev::append16_tile(code, in, which, tile * KVQ_TILE_TOKENS, t_old, t_old + n_new, lane, which ? nullptr : rope,
+                           (rinv && !which) ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
 }
 
 // Quantizing append (B = 8, 4, 2): same grid and contract as kvq_append_kernel, built on the row-owner core.
@@ -532,11 +288,9 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
             u32x4 v = {0u, 0u, 0u, 0u};
             if (isnew) {
                 const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
-                v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
-                if (rope && !which)
-                    v = rope8(v, *reinterpret_cast<const u32x4*>(row + ((32 * grp + 8 * c) ^ 64)),
-                              rope + (uint64_t)(tok - t_old) * KVQ_D, 32 * grp + 8 * c);
-                if (rinv && !which) v = scale_keys8(v, rinv + (unit % n_kv_heads) * KVQ_D + 32 * grp + 8 * c);
+                if (which) v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
+                else v = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr,
+                                   rinv ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
             }
             w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
         }
@@ -871,7 +625,7 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
     ap.d[0] = first_two ? first_two[0] : KvqPageDesc{0, 0, 0, 0};
     ap.d[1] = first_two ? first_two[1] : KvqPageDesc{0, 0, 0, 0};
     switch (bits) {
-        case 16: hipLaunchKernelGGL(kvq_append_kernel<16>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, rinv, n_kv_heads, rope); break;
+        case 16: hipLaunchKernelGGL(kvq_append16_kernel, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, rinv, n_kv_heads, rope); break;
         case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
         case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
         case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
