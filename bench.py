@@ -281,6 +281,8 @@ def main():
     ap.add_argument("--workload", default="32b", choices=["7b", "14b", "32b", "70b"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-requant", action="store_true")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="step = kvq_quantize_append + kvq_decode_attention (two launches) instead of the fused call")
     ap.add_argument("--fused-merge", type=int, default=None)
     ap.add_argument("--splits", type=int, default=0)
     args = ap.parse_args()
@@ -315,13 +317,17 @@ def main():
         # HIP events bracket a rotating sample of the attention launches (every 16th block): recording an event
         # costs several microseconds of stream time, so timing every launch would distort the step itself
         for layer in range(L):
-            cache.kvq_quantize_append(layer, new_k[i], new_v[i], 0, stream)
             timed = events is not None and (layer + i) % 16 == 0
+            if args.separate_calls:
+                cache.kvq_quantize_append(layer, new_k[i], new_v[i], 0, stream)
             if timed:
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
-            cache.kvq_decode_attention(layer, q, outs[layer], 0.0, stream)
+            if args.separate_calls:
+                cache.kvq_decode_attention(layer, q, outs[layer], 0.0, stream)
+            else:   # the same step in one launch: the attention kernel writes the new token itself
+                cache.kvq_append_decode_attention(layer, new_k[i], new_v[i], q, outs[layer], None, 0.0, stream)
             if timed:
                 e1.record(stream)
                 events.append((e0, e1))
@@ -381,7 +387,9 @@ def main():
         "config": {"workload": f"{w.name}-shaped: {L} blocks, {Hq}q/{Hkv}kv heads, head_dim 128, batch {B}, "
                                f"{w.n_tokens} cached tokens, tiers (tokens,bits) {list(w.tiers_of_layer(0))}, group 32, "
                                f"page {w.page_tokens} tokens",
-                   "step": "per block: append 1 token + decode attention", "layers_share_values": True},
+                   "step": "per block: append 1 token + decode attention" +
+                           (" (two calls)" if args.separate_calls else " (kvq_append_decode_attention, one launch)"),
+                   "layers_share_values": True},
         "hbm_GBps_whole_step": round(bytes_per_launch * L / (ms_per_step * 1e-3) / 1e9, 1),
         "hbm_frac_whole_step": round(bytes_per_launch * L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "roofline": roofline,

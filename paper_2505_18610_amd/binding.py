@@ -54,6 +54,8 @@ _SIGNATURES = {
                                            C.c_void_p, C.c_void_p]),
     "kvq_progressive_requant": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32)]),
     "kvq_decode_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]),
+    "kvq_append_decode_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_int32, C.c_float, C.c_void_p]),
     "kvq_cache_describe": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(_SegmentInfo), C.c_int32, C.POINTER(C.c_int32),
                                      C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "kvq_cache_export_segment": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
@@ -200,6 +202,12 @@ class KvqCache:
         out_is_fp32 = 1 if out.dtype.itemsize == 4 else 0
         self._check(self.lib.kvq_decode_attention(self.handle, layer, _ptr(q), _ptr(out), out_is_fp32,
                                                   float(softmax_scale), _stream(stream)), "kvq_decode_attention")
+
+    def kvq_append_decode_attention(self, layer, k, v, q, out, cos_sin=None, softmax_scale=0.0, stream=None):
+        out_is_fp32 = 1 if out.dtype.itemsize == 4 else 0
+        self._check(self.lib.kvq_append_decode_attention(self.handle, layer, _ptr(k), _ptr(v), _ptr(cos_sin), _ptr(q),
+                                                         _ptr(out), out_is_fp32, float(softmax_scale), _stream(stream)),
+                    "kvq_append_decode_attention")
 
     def kvq_cache_describe(self, layer):
         """Returns (segments [(token_begin, token_end, bits)], bytes_used, n_tokens, current_bits)."""

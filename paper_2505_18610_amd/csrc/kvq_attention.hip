@@ -13,6 +13,7 @@
 // the softmax denominator come out of one extra MFMA each.  Wavefront partials are merged through LDS,
 // split partials through global memory (a second small kernel, or the last-arriving workgroup).
 #include "kvq_internal.h"
+#include "kvq_append16.h"
 
 namespace {
 
@@ -471,7 +472,8 @@ struct RunCtx {
     int lo, hi;              // tile range of the current descriptor window
     int tpc;                 // tiles per chunk
     int n_chunks;
-    int next_static;         // >= 0: deterministic mode, this wavefront takes chunks next_static, +8, +16, ...
+    int next_static;         // >= 0: deterministic mode, this wavefront takes chunks next_static, + static_stride, ...
+    int static_stride;
     float scale_log2;
     uint32_t lane_off;       // 16 * lane
     Claim next;
@@ -483,7 +485,7 @@ struct RunCtx {
 __device__ inline void start_claim(RunCtx& c) {
     if (c.next_static >= 0) {
         c.claim_v = c.next_static;
-        c.next_static = __builtin_amdgcn_readfirstlane(c.next_static + KVQ_ATTN_WAVES);  // provably uniform
+        c.next_static = __builtin_amdgcn_readfirstlane(c.next_static + c.static_stride);  // provably uniform
         return;
     }
     int v = 0;
@@ -498,7 +500,7 @@ __device__ inline int page_of_tile(const RunCtx& c, int tile) {
 __device__ inline void start_desc(RunCtx& c, int chunk) {
     chunk = __builtin_amdgcn_readfirstlane(chunk);
     c.desc_chunk = chunk;
-    const int tile = c.lo + min(chunk, c.n_chunks - 1) * c.tpc;  // past the end: any valid slot, ignored later
+    const int tile = c.lo + max(0, min(chunk, c.n_chunks - 1)) * c.tpc;  // past the end: any valid slot, ignored later
     c.desc_v = c.desc_lds[page_of_tile(c, tile) - c.page0];
 }
 __device__ inline Claim finish_desc(const RunCtx& c) {
@@ -837,8 +839,28 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
         *reinterpret_cast<u32x4*>(&q_lds[head * KVQ_D + c16 * 8]) = qv;
         desc_lds[tid] = dv;
     }
-    if (tid == 0) claim_ctr = KVQ_ATTN_WAVES;  // the first chunk of every wavefront is its own index
+    // A one-token append fused into this launch: the workgroup whose range ends with the new token's tile writes
+    // the token.  Its wavefront 0 does that after the staging barrier, waits until the stores have reached L2 and
+    // takes the chunk that holds the tile as its first one (nobody else can claim it); the other seven wavefronts
+    // start on the rest of the range meanwhile.
+    const int tile_new = P.app_t_old >= 0 ? P.app_t_old / KVQ_TILE_TOKENS : -1;
+    const bool appends = tile_new >= t_begin && tile_new < t_end;
+    const bool one_window = p_last - p_first <= KVQ_DESC_CACHE;
+    // the first chunk of every wavefront is fixed (see below); the counter starts behind them
+    if (tid == 0) claim_ctr = (appends && one_window) ? KVQ_ATTN_WAVES - 1 : KVQ_ATTN_WAVES;
     __syncthreads();
+    if (appends && wave == 0) {
+        const int tip = tile_new - (tile_new / tpp) * tpp;
+        const uint64_t tslot = (uint64_t)unit * tpp + tip;
+        uint8_t* code = const_cast<uint8_t*>(P.arena) + (uint64_t)P.app_desc.code_off256 * 256u + tslot * 2 * (512u * 16);
+        const uint16_t* in_k = static_cast<const uint16_t*>(P.app_k) + (size_t)unit * KVQ_D;
+        const uint16_t* in_v = static_cast<const uint16_t*>(P.app_v) + (size_t)unit * KVQ_D;
+        kvq_dev::append16_tile(code, in_k, 0, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1, lane, P.app_rope,
+                               P.app_rinv ? P.app_rinv + hk * KVQ_D : nullptr);
+        kvq_dev::append16_tile(code + 512u * 16, in_v, 1, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1, lane,
+                               nullptr, nullptr);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     KVQ_STAMP(1);
     QOps Q;
     Q.cls = -1;
@@ -863,22 +885,44 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
     if (lane < 8) reinterpret_cast<uint32_t*>(my_meta + KVQ_WAVE_LDS_CONST)[lane] = lane < 4 ? 0x3c003c00u : 0u;
     for (int pc = p_first; pc < p_last; pc += KVQ_DESC_CACHE) {
         const int pn = min(KVQ_DESC_CACHE, p_last - pc);
+        const bool reserve = appends && pc + KVQ_DESC_CACHE >= p_last;  // the window that ends with the new tile
         if (pc != p_first) {  // further descriptor windows of a very long range
             __syncthreads();
             if (tid < pn) desc_lds[tid] = reinterpret_cast<const u32x4*>(P.table)[pc + tid];
-            if (tid == 0) claim_ctr = KVQ_ATTN_WAVES;
+            if (tid == 0) claim_ctr = reserve ? KVQ_ATTN_WAVES - 1 : KVQ_ATTN_WAVES;
             __syncthreads();
         }
         ctx.page0 = pc;
         ctx.lo = max(t_begin, pc * tpp);
         ctx.hi = min(t_end, (pc + pn) * tpp);
-        ctx.n_chunks = (ctx.hi - ctx.lo + ctx.tpc - 1) / ctx.tpc;
-        if (ctx.n_chunks <= 0) continue;
-        // the first chunk of every wavefront is its own index (the counter starts behind them); from then on
-        // chunks are claimed one at a time
-        ctx.next_static = P.deterministic ? wave + KVQ_ATTN_WAVES : -1;
-        start_desc(ctx, wave);
+        const int n_all = (ctx.hi - ctx.lo + ctx.tpc - 1) / ctx.tpc;
+        if (n_all <= 0) continue;
+        // The first chunk of every wavefront is fixed, from then on chunks are claimed one at a time.  Normally it
+        // is the wavefront's own index.  With a fused append the last chunk is kept out of the claimable range:
+        // wavefront 0 starts with it, wavefronts 1..7 with chunks 0..6.
+        int first;
+        if (!reserve) {
+            ctx.n_chunks = n_all;
+            first = wave;
+            ctx.static_stride = KVQ_ATTN_WAVES;
+            ctx.next_static = P.deterministic ? wave + KVQ_ATTN_WAVES : -1;
+            start_desc(ctx, first);
+        } else {
+            ctx.static_stride = KVQ_ATTN_WAVES - 1;
+            if (wave == 0) {
+                first = n_all - 1;
+                ctx.next_static = P.deterministic ? 0x3fffff00 : -1;  // deterministic mode: nothing after it
+                ctx.n_chunks = n_all;
+                start_desc(ctx, first);
+            } else {
+                first = wave - 1;
+                ctx.next_static = P.deterministic ? wave - 1 + (KVQ_ATTN_WAVES - 1) : -1;
+                ctx.n_chunks = n_all - 1;
+                start_desc(ctx, first);
+            }
+        }
         ctx.next = finish_desc(ctx);
+        ctx.n_chunks = reserve ? n_all - 1 : n_all;
         while (ctx.next.bits != 0u) {
             switch (ctx.next.bits) {
                 case 16: run_chunks<16, 1, 2, false>(st, Q, q_lds, ctx, my_meta, lane); break;

@@ -416,13 +416,21 @@ void kvq_cache_destroy(kvq_cache_t* c) {
     delete c;
 }
 
-kvq_status_t kvq_quantize_append(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev,
-                                 int32_t n_new, int32_t entry_bits, void* hip_stream) {
-    return kvq_quantize_append_rope(c, layer, k_dev, v_dev, n_new, entry_bits, nullptr, hip_stream);
-}
+}  // extern "C"
 
-kvq_status_t kvq_quantize_append_rope(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev,
-                                      int32_t n_new, int32_t entry_bits, const float* cos_sin_dev, void* hip_stream) {
+namespace {
+
+// What a deferred single-token append into the 16-bit tier leaves for the attention launch to do.
+struct DeferredAppend {
+    bool active = false;
+    int t_old = 0;
+    KvqPageDesc desc{};
+};
+
+// The append entry points.  defer != nullptr: a one-token append into the 16-bit tier is not launched but described
+// in *defer (bookkeeping, page allocation, table upload and window evictions happen as usual).
+kvq_status_t append_impl(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev, int32_t n_new,
+                         int32_t entry_bits, const float* cos_sin_dev, void* hip_stream, DeferredAppend* defer) {
     if (!c || layer < 0 || layer >= c->cfg.n_layers || n_new < 0) return KVQ_E_INVALID;
     if (entry_bits != 0 && !valid_bits(entry_bits)) return KVQ_E_INVALID;
     if (n_new == 0) return KVQ_OK;
@@ -493,7 +501,11 @@ kvq_status_t kvq_quantize_append_rope(kvq_cache_t* c, int32_t layer, const void*
     L.version++;
     st = upload_table(c, layer, (int)old_pages, (int)L.pages.size(), s);
     if (st != KVQ_OK) return st;
-    if (!c->dry) {
+    if (!c->dry && defer && n_new == 1 && e == 16) {
+        defer->active = true;
+        defer->t_old = t_old;
+        defer->desc = c->desc(L.pages[(size_t)(t_old / P)]);
+    } else if (!c->dry) {
         // short appends (at most two pages touched) carry the page descriptors in the kernel arguments
         const int pg0 = t_old / P, pg1 = (T - 1) / P;
         KvqPageDesc two[2];
@@ -515,6 +527,20 @@ kvq_status_t kvq_quantize_append_rope(kvq_cache_t* c, int32_t layer, const void*
         if (st != KVQ_OK) return st;
     }
     return KVQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+kvq_status_t kvq_quantize_append(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev,
+                                 int32_t n_new, int32_t entry_bits, void* hip_stream) {
+    return append_impl(c, layer, k_dev, v_dev, n_new, entry_bits, nullptr, hip_stream, nullptr);
+}
+
+kvq_status_t kvq_quantize_append_rope(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev,
+                                      int32_t n_new, int32_t entry_bits, const float* cos_sin_dev, void* hip_stream) {
+    return append_impl(c, layer, k_dev, v_dev, n_new, entry_bits, cos_sin_dev, hip_stream, nullptr);
 }
 
 kvq_status_t kvq_progressive_requant(kvq_cache_t* c, int32_t layer, int32_t segment, int32_t reserve_tokens,
@@ -570,8 +596,13 @@ kvq_status_t kvq_progressive_requant(kvq_cache_t* c, int32_t layer, int32_t segm
     return KVQ_OK;
 }
 
-kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_dev, void* out_dev,
-                                  int32_t out_is_fp32, float softmax_scale, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+kvq_status_t attention_impl(kvq_cache_t* c, int32_t layer, const void* q_dev, void* out_dev, int32_t out_is_fp32,
+                            float softmax_scale, void* hip_stream, const DeferredAppend* app, const void* k_new,
+                            const void* v_new, const float* cos_sin_dev) {
     if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_dev || !out_dev) return KVQ_E_INVALID;
     if (c->dry) return KVQ_E_STATE;
     Layer& L = c->layers[(size_t)layer];
@@ -621,7 +652,37 @@ kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_d
     p.scale_log2 = scale * 1.44269504088896340736f;
     std::memcpy(p.split_begin, L.split_begin, sizeof(int32_t) * (size_t)(n_splits + 1));
     for (int i = n_splits + 1; i <= KVQ_MAX_SPLITS; ++i) p.split_begin[i] = n_tiles;
+    p.app_t_old = -1;
+    if (app && app->active) {
+        p.app_t_old = app->t_old;
+        p.app_desc = app->desc;
+        p.app_k = k_new;
+        p.app_v = v_new;
+        p.app_rope = cos_sin_dev;
+        p.app_rinv = L.reparam ? c->lambda_dev(layer) + c->cfg.n_kv_heads * KVQ_D : nullptr;
+    }
     return kvq_launch_attention(p, c->units, s) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_dev, void* out_dev,
+                                  int32_t out_is_fp32, float softmax_scale, void* hip_stream) {
+    return attention_impl(c, layer, q_dev, out_dev, out_is_fp32, softmax_scale, hip_stream, nullptr, nullptr, nullptr,
+                          nullptr);
+}
+
+kvq_status_t kvq_append_decode_attention(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev,
+                                         const float* cos_sin_dev, const void* q_dev, void* out_dev,
+                                         int32_t out_is_fp32, float softmax_scale, void* hip_stream) {
+    if (!q_dev || !out_dev) return KVQ_E_INVALID;  // nothing may be appended when the attention cannot follow
+    if (c && c->dry) return KVQ_E_STATE;
+    DeferredAppend app;
+    kvq_status_t st = append_impl(c, layer, k_dev, v_dev, 1, 0, cos_sin_dev, hip_stream, &app);
+    if (st != KVQ_OK) return st;
+    return attention_impl(c, layer, q_dev, out_dev, out_is_fp32, softmax_scale, hip_stream, &app, k_dev, v_dev, cos_sin_dev);
 }
 
 kvq_status_t kvq_cache_describe(const kvq_cache_t* c, int32_t layer, kvq_segment_info_t* segs_host, int32_t cap,

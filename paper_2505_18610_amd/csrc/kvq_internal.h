@@ -44,6 +44,13 @@ struct KvqAttnParams {
     int32_t deterministic;     // 1: static chunk-to-wavefront assignment (bit-reproducible summation order)
     float scale_log2;          // softmax scale * log2(e)
     int32_t split_begin[KVQ_MAX_SPLITS + 1];  // tile index where each split starts
+    // a one-token append into the 16-bit tier done by the workgroup that owns the last tile (app_t_old < 0: none)
+    int32_t app_t_old;         // tokens before the append; n_tokens already counts the new one
+    KvqPageDesc app_desc;      // page of the new token
+    const void* app_k;         // fp16 [batch, n_kv_heads, 1, 128]
+    const void* app_v;
+    const float* app_rope;     // [1][128] cos | sin of the new position, or null
+    const float* app_rinv;     // [n_kv_heads][128] reciprocal reparameterization factors, or null
 };
 
 // kvq_quant.hip
