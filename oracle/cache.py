@@ -17,6 +17,8 @@ from .attention import decode_attention_fp64
 
 POLICY_PAPER = 0
 POLICY_OLDEST_FIRST = 1
+TIER16_FP16 = 0    # 16-bit tokens are the raw fp16 values
+TIER16_INT16 = 1   # 16-bit tokens are 16-bit integer codes with (S, Z) per group: the INT16 format of Sec. 4.1.2
 
 
 class BudgetError(Exception):
@@ -42,14 +44,15 @@ class CacheConfig:
     policy: int = POLICY_PAPER
     count_metadata_in_budget: int = 1
     shift_strategy: int = SHIFT_EQUIVALENT   # how 2b -> b steps treat codes, S and Z (Sec. 4.3.1)
+    tier16: int = TIER16_FP16                # what a 16-bit token is; INT16 makes 16 -> 8 a step of Eq. 3 too
 
 
 class _Page:
     def __init__(self, bits):
         self.bits = bits
         self.n = 0
-        self.k = self.v = None                     # 16-bit: fp16 [B,H,n,D]
-        self.kc = self.ks = self.kz = None         # quantized: codes uint8 [B,H,n,D], S/Z fp16 [B,H,n,D/G]
+        self.k = self.v = None                     # 16-bit, fp16 tier: fp16 [B,H,n,D]
+        self.kc = self.ks = self.kz = None         # quantized: codes uint8 (uint16 in the INT16 tier) [B,H,n,D], S/Z fp16 [B,H,n,D/G]
         self.vc = self.vs = self.vz = None
 
 
@@ -86,7 +89,8 @@ class OracleCache:
     # ---------------------------------------------------------------- bookkeeping
     def _bpth(self, bits):
         c = self.cfg
-        return bytes_per_token_head(bits, c.head_dim, c.group, bool(c.count_metadata_in_budget))
+        return bytes_per_token_head(bits, c.head_dim, c.group, bool(c.count_metadata_in_budget),
+                                    c.tier16 == TIER16_INT16)
 
     def bytes_used(self, layer):
         c = self.cfg
@@ -194,7 +198,7 @@ class OracleCache:
 
     def _store(self, pg, k, v):
         G = self.cfg.group
-        if pg.bits == 16:
+        if pg.bits == 16 and self.cfg.tier16 == TIER16_FP16:
             pg.k, pg.v = _cat(pg.k, k), _cat(pg.v, v)
         else:
             kc, ks, kz = quantize(k, pg.bits, G)
@@ -210,17 +214,21 @@ class OracleCache:
         From 16 bits: direct quantization of the stored fp16 values (Eq. 1-2); by the
         appendix theorem this is what an integer 16-bit tier followed by Eq. 3 would give.
         From 2b to b bits: Eq. 3 on the codes, S_b = (2^b + 1) S_2b, Z unchanged (or one of the two
-        ablation strategies of Sec. 4.3.1 when the configuration asks for it).
+        ablation strategies of Sec. 4.3.1 when the configuration asks for it).  A page of the integer 16-bit
+        tier goes down the same way, one halving at a time (16 -> 8 -> ... -> target_bits).
         """
         G = self.cfg.group
-        if pg.bits == 16:
+        if pg.bits == 16 and self.cfg.tier16 == TIER16_FP16:
             pg.kc, pg.ks, pg.kz = quantize(pg.k, target_bits, G)
             pg.vc, pg.vs, pg.vz = quantize(pg.v, target_bits, G)
             pg.k = pg.v = None
         else:
-            assert target_bits * 2 == pg.bits
-            pg.kc, pg.ks, pg.kz = shrink_step(pg.kc, pg.ks, pg.kz, target_bits, self.cfg.shift_strategy)
-            pg.vc, pg.vs, pg.vz = shrink_step(pg.vc, pg.vs, pg.vz, target_bits, self.cfg.shift_strategy)
+            assert target_bits * 2 == pg.bits or (pg.bits == 16 and target_bits in (8, 4, 2))
+            b = pg.bits
+            while b > target_bits:
+                b //= 2
+                pg.kc, pg.ks, pg.kz = shrink_step(pg.kc, pg.ks, pg.kz, b, self.cfg.shift_strategy)
+                pg.vc, pg.vs, pg.vz = shrink_step(pg.vc, pg.vs, pg.vz, b, self.cfg.shift_strategy)
         pg.bits = target_bits
 
     def requant(self, layer, segment=-1, reserve_tokens=0):
@@ -273,7 +281,7 @@ class OracleCache:
         G = self.cfg.group
         ks, vs = [], []
         for p in self.layers[layer].pages:
-            if p.bits == 16:
+            if p.k is not None:
                 ks.append(p.k.astype(np.float64)); vs.append(p.v.astype(np.float64))
             else:
                 ks.append(dequantize(p.kc, p.ks, p.kz, G)); vs.append(dequantize(p.vc, p.vs, p.vz, G))
@@ -296,12 +304,13 @@ class OracleCache:
         return decode_attention_fp64(q, K, V, scale)
 
     def export_segment(self, layer, segment, which):
-        """Canonical export of one run.  16 bits: (fp16 values [B,H,n,D], None, None).
-        Quantized: (packed codes uint8 [B,H,n,D*b/8], S fp16 [B,H,n,D/G], Z fp16 [B,H,n,D/G])."""
+        """Canonical export of one run.  16 bits, fp16 tier: (fp16 values [B,H,n,D], None, None).
+        Quantized (and 16 bits of the INT16 tier): (packed codes uint8 [B,H,n,D*b/8], S fp16 [B,H,n,D/G],
+        Z fp16 [B,H,n,D/G])."""
         P = self.cfg.page_tokens
         t0, t1, b = self.segments(layer)[segment]
         pages = self.layers[layer].pages[t0 // P:(t1 + P - 1) // P]
-        if b == 16:
+        if b == 16 and self.cfg.tier16 == TIER16_FP16:
             return np.concatenate([p.k if which == "K" else p.v for p in pages], 2), None, None
         pre = "k" if which == "K" else "v"
         codes = np.concatenate([getattr(p, pre + "c") for p in pages], 2)

@@ -7,7 +7,7 @@ from __future__ import annotations
 
 import numpy as np
 
-LEVELS = {8: 255, 4: 15, 2: 3}
+LEVELS = {16: 65535, 8: 255, 4: 15, 2: 3}
 
 
 def quantize(x: np.ndarray, b: int, group: int):
@@ -19,6 +19,11 @@ def quantize(x: np.ndarray, b: int, group: int):
     to nearest-even into fp16; the codes are round-to-nearest-even of (X - Z) / S in fp32
     with the *stored* S, clamped to [0, 2^b - 1].  A group with S == 0 has all codes 0.
     Returns (codes uint8 [..., D], S fp16 [..., D/group], Z fp16 [..., D/group]).
+
+    b = 16 is the integer 16-bit tier (the "INT16 format" of Sec. 4.1.2, the X_2b of the appendix theorem at
+    b = 8): same formulas with 2^16 - 1 levels, codes uint16.  With S held in fp16 the clamp is essential there:
+    S rounded down by up to 2^-11 puts (max - Z) / S as far as ~32 above 65535, and below a group range of ~4 the
+    scale is an fp16 subnormal with fewer significant bits still.
     """
     assert x.dtype == np.float16 and b in LEVELS and x.shape[-1] % group == 0
     assert np.all(np.isfinite(x))
@@ -33,12 +38,12 @@ def quantize(x: np.ndarray, b: int, group: int):
     with np.errstate(divide="ignore", invalid="ignore"):
         r = np.rint(num / Sf)
     r = np.where(Sf == 0, np.float32(0), r)
-    codes = np.clip(r, 0, LEVELS[b]).astype(np.uint8)
+    codes = np.clip(r, 0, LEVELS[b]).astype(np.uint16 if b == 16 else np.uint8)
     return codes.reshape(x.shape), S, Z
 
 
 def dequantize(codes: np.ndarray, S: np.ndarray, Z: np.ndarray, group: int) -> np.ndarray:
-    """X_hat = X_b * S + Z in fp64 (exact: <= 8-bit code times 11-bit significand)."""
+    """X_hat = X_b * S + Z in fp64 (the product is exact: a code of at most 16 bits times an 11-bit significand)."""
     ng = codes.shape[-1] // group
     c = codes.reshape(codes.shape[:-1] + (ng, group)).astype(np.float64)
     out = c * S.astype(np.float64)[..., None] + Z.astype(np.float64)[..., None]
@@ -48,13 +53,14 @@ def dequantize(codes: np.ndarray, S: np.ndarray, Z: np.ndarray, group: int) -> n
 def shrink_codes(x2b: np.ndarray, b: int) -> np.ndarray:
     """Equivalent Right Shift (Sec. 3.1, Eq. 3): X_b = ((2^{2b} - 2^b + 1)(X_{2b} + 2^{b-1})) >> 3b.
 
-    x2b holds 2b-bit codes; b is the target width.  Evaluated in unsigned 64-bit integers.
+    x2b holds 2b-bit codes; b is the target width.  Evaluated in unsigned 64-bit integers.  The result keeps the
+    dtype of x2b, except that 16-bit codes (uint16) come back as the uint8 every narrower width is held in.
     """
     assert b in (8, 4, 2)
     x = x2b.astype(np.uint64)
     mult = np.uint64((1 << (2 * b)) - (1 << b) + 1)
     y = (mult * (x + np.uint64(1 << (b - 1)))) >> np.uint64(3 * b)
-    return y.astype(x2b.dtype)
+    return y.astype(np.uint8 if x2b.dtype == np.uint16 else x2b.dtype)
 
 
 def shrink_scale(S2b: np.ndarray, b: int) -> np.ndarray:
@@ -137,7 +143,7 @@ def shrink_step(x2b: np.ndarray, S2b: np.ndarray, Z2b: np.ndarray, b: int, strat
     Sf, Zf = S2b.astype(np.float32), Z2b.astype(np.float32)
     if strategy == SHIFT_EQUIVALENT:
         return shrink_codes(x2b, b), shrink_scale(S2b, b), Z2b.copy()
-    xb = (x2b.astype(np.uint64) >> np.uint64(b)).astype(x2b.dtype)
+    xb = (x2b.astype(np.uint64) >> np.uint64(b)).astype(np.uint8 if x2b.dtype == np.uint16 else x2b.dtype)
     if strategy == SHIFT_DIRECT:
         return xb, shrink_scale(S2b, b), Z2b.copy()
     Sb32 = Sf * np.float32(1 << b)
@@ -148,7 +154,11 @@ def shrink_step(x2b: np.ndarray, S2b: np.ndarray, Z2b: np.ndarray, b: int, strat
 
 
 def pack_codes(codes: np.ndarray, b: int) -> np.ndarray:
-    """Canonical packing: element i of a row sits at bit offset (i*b) mod 8 of byte (i*b)//8, low bits first."""
+    """Canonical packing: element i of a row sits at bit offset (i*b) mod 8 of byte (i*b)//8, low bits first
+    (16-bit codes: two bytes, low byte first)."""
+    if b == 16:
+        c = codes.astype(np.uint16)
+        return np.stack([(c & 0xff).astype(np.uint8), (c >> 8).astype(np.uint8)], -1).reshape(c.shape[:-1] + (2 * c.shape[-1],))
     per = 8 // b
     c = codes.reshape(codes.shape[:-1] + (codes.shape[-1] // per, per)).astype(np.uint16)
     out = np.zeros(c.shape[:-1], np.uint16)
@@ -158,6 +168,9 @@ def pack_codes(codes: np.ndarray, b: int) -> np.ndarray:
 
 
 def unpack_codes(packed: np.ndarray, b: int) -> np.ndarray:
+    if b == 16:
+        p = packed.reshape(packed.shape[:-1] + (packed.shape[-1] // 2, 2)).astype(np.uint16)
+        return p[..., 0] | (p[..., 1] << 8)
     per = 8 // b
     out = np.empty(packed.shape + (per,), np.uint8)
     for j in range(per):
@@ -165,13 +178,13 @@ def unpack_codes(packed: np.ndarray, b: int) -> np.ndarray:
     return out.reshape(packed.shape[:-1] + (packed.shape[-1] * per,))
 
 
-def bytes_per_token_head(bits: int, head_dim: int, group: int, count_metadata: bool) -> int:
+def bytes_per_token_head(bits: int, head_dim: int, group: int, count_metadata: bool, int16_tier: bool = False) -> int:
     """Bytes one cached token of one KV head occupies, K and V together.
 
     Codes: 2 * head_dim * bits / 8.  Quantized widths also carry one fp16 (S, Z) pair per
-    group for K and for V when metadata is counted.
+    group for K and for V when metadata is counted; 16-bit tokens do when the 16-bit tier holds integer codes.
     """
     n = 2 * head_dim * bits // 8
-    if count_metadata and bits < 16:
+    if count_metadata and (bits < 16 or int16_tier):
         n += 2 * (head_dim // group) * 4
     return n
