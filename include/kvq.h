@@ -72,9 +72,11 @@ typedef struct {
 uint64_t kvq_arena_bytes(const kvq_config_t* cfg, uint64_t payload_bytes);
 
 /* Bytes one cached token of one KV head occupies at `bits`, K and V together (codes, plus one fp16
- * scale/zero pair per group for K and for V when count_metadata != 0).  This is the Mem(.) of Sec. 3.2
- * as the library accounts it.  Returns 0 for bits outside {16,8,4,2}. */
-uint64_t kvq_bytes_per_token_head(int32_t bits, int32_t head_dim, int32_t group, int32_t count_metadata);
+ * scale/zero pair per group for K and for V when count_metadata != 0; 16-bit tokens carry such pairs only when
+ * int16_tier != 0, see KVQ_OPT_TIER16).  This is the Mem(.) of Sec. 3.2 as the library accounts it.  Returns 0 for
+ * bits outside {16,8,4,2}. */
+uint64_t kvq_bytes_per_token_head(int32_t bits, int32_t head_dim, int32_t group, int32_t count_metadata,
+                                  int32_t int16_tier);
 
 /* Create a cache over a caller-owned device arena (Sec. 3.1: per-block Fbit and byte budget).
  *   block_budget_bytes_host[n_layers], block_fbit_host[n_layers] (each 16, 8, 4 or 2): host arrays, copied.
@@ -115,7 +117,8 @@ kvq_status_t kvq_quantize_append_rope(kvq_cache_t* cache, int32_t layer, const v
 /* Progressive bit-width shrinking (Sec. 3.1 Eq. 3, appendix theorem):
  *   X_b = ((2^2b - 2^b + 1)(X_2b + 2^(b-1))) >> 3b,  S_b = fp16((2^b + 1) S_2b),  Z_b = Z_2b;
  *   pages still holding raw fp16 values are quantized directly to 8 bits (Eq. 1-2), which by the theorem
- *   is what an integer 16-bit tier followed by Eq. 3 would give.
+ *   is what an integer 16-bit tier followed by Eq. 3 would give; with KVQ_TIER16_INT16 the 16-bit pages are that
+ *   integer tier and 16 -> 8 is Eq. 3 at b = 8 (multiplier 65281, offset 128, shift 24, in unsigned 32-bit).
  *   segment >= 0: lower every page of that run (kvq_cache_describe order) one step; KVQ_E_STATE if it is
  *   already at 2 bits or does not exist.
  *   segment == -1, KVQ_POLICY_PAPER: halve the block's current width: every page at that width outside the
@@ -129,7 +132,8 @@ kvq_status_t kvq_progressive_requant(kvq_cache_t* cache, int32_t layer, int32_t 
 
 /* Single-token GQA decode attention over the block's whole cache (no mask; append the current token first):
  *   out[b, h, :] = softmax_t( q[b, h, :] . K_hat[b, h/g, t, :] * softmax_scale ) V_hat[b, h/g, t, :]
- *   with X_hat = code * S + Z (or the raw fp16 value).  fp16 operands, fp32 accumulation.
+ *   with X_hat = code * S + Z (or the raw fp16 value).  fp16 operands, fp32 accumulation (16-bit codes enter the
+ *   matrix cores as their high and low bytes, both exact).
  *   q_dev: fp16 [batch, n_q_heads, head_dim]; out_dev: [batch, n_q_heads, head_dim], fp32 if out_is_fp32
  *   else fp16; softmax_scale 0 means 1/sqrt(head_dim).  KVQ_E_STATE if the block is empty. */
 kvq_status_t kvq_decode_attention(kvq_cache_t* cache, int32_t layer, const void* q_dev, void* out_dev,
@@ -137,7 +141,7 @@ kvq_status_t kvq_decode_attention(kvq_cache_t* cache, int32_t layer, const void*
 
 /* One decode step of a block in one launch: kvq_quantize_append_rope of one token (n_new = 1, entry_bits = 0; k_dev,
  * v_dev: fp16 [batch, n_kv_heads, 1, 128]; cos_sin_dev: fp32 [1][128] or NULL for keys that already carry RoPE)
- * followed by kvq_decode_attention over the block including that token.  When the token enters the 16-bit tier
+ * followed by kvq_decode_attention over the block including that token.  When the token enters the raw fp16 tier
  * (a window is configured, the policy is OLDEST_FIRST, or the block is still at 16 bits) it is written by the attention
  * kernel itself - by the workgroup that owns the last tile, which reads it back only after its stores have
  * completed - so the small append launch and its gap disappear; otherwise the two kernels are launched one after the
@@ -157,7 +161,8 @@ kvq_status_t kvq_cache_describe(const kvq_cache_t* cache, int32_t layer, kvq_seg
 
 /* Copies one run of K (which = KVQ_WHICH_K) or V to the host in the canonical format, synchronising the
  * stream.  n = token_end - token_begin, D = head_dim, G = group:
- *   16-bit run: codes_host receives fp16 [batch, n_kv_heads, n, D]; scales/zeros are not written.
+ *   16-bit run: codes_host receives fp16 [batch, n_kv_heads, n, D]; scales/zeros are not written.  With
+ *               KVQ_TIER16_INT16 it is a b-bit run with b = 16: two bytes per code, low byte first, and metadata.
  *   b-bit run : codes_host uint8 [batch, n_kv_heads, n, D*b/8], element i of a row at bit (i*b)%8 of byte
  *               (i*b)/8, low bits first; scales_host and zeros_host fp16 [batch, n_kv_heads, n, D/G]. */
 kvq_status_t kvq_cache_export_segment(kvq_cache_t* cache, int32_t layer, int32_t segment, int32_t which,
@@ -175,16 +180,25 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* cache, int32_t layer, int32_t
  *   KVQ_OPT_TILE_COST_{2,4,8,16}BIT: relative time one 32-token tile of that width costs the attention kernel
  *                   (1..1000000); the token range of a (sequence, KV head) is cut into splits of equal cost.
  *   KVQ_OPT_SHIFT_STRATEGY: how later 2b -> b steps of kvq_progressive_requant treat codes, S and Z, for the
- *                   comparison of Sec. 4.3.1 (the step from the 16-bit tier is Eq. 1-2 under every strategy):
+ *                   comparison of Sec. 4.3.1 (the step from raw fp16 values is Eq. 1-2 under every strategy):
  *                   KVQ_SHIFT_EQUIVALENT (default, Eq. 3): X_b = ((2^2b - 2^b + 1)(X_2b + 2^(b-1))) >> 3b,
  *                       S_b = (2^b + 1) S_2b, Z kept;
  *                   KVQ_SHIFT_DIRECT:   X_b = X_2b >> b, S_b = (2^b + 1) S_2b, Z kept;
  *                   KVQ_SHIFT_MODIFIED: X_b = X_2b >> b, S_b = 2^b S_2b, Z_b = Z_2b + (S_b - S_2b) / 2.
- *                   S_b and Z_b are formed in fp32 and rounded to nearest-even into fp16. */
+ *                   S_b and Z_b are formed in fp32 and rounded to nearest-even into fp16.
+ *   KVQ_OPT_TIER16: what a 16-bit token is.  Only while every block is empty (else KVQ_E_STATE).
+ *                   KVQ_TIER16_FP16 (default): the raw fp16 values, no metadata.
+ *                   KVQ_TIER16_INT16: the INT16 format of Sec. 4.1.2, the X_2b of the appendix theorem at b = 8:
+ *                       Eq. 1-2 with 2^16 - 1 levels, fp16 S and Z per group (the clamp to 65535 matters: S rounded
+ *                       down puts the group maximum up to ~32 codes higher, more for subnormal S), 16-bit codes
+ *                       exported as two bytes, low byte first.  Such tokens carry metadata in the byte accounting,
+ *                       pages leaving the window go 16 -> 8 -> ... by successive shift steps instead of a direct
+ *                       quantization, and the shift strategy applies to the 16 -> 8 step as well. */
 enum { KVQ_OPT_SPLITS = 0, KVQ_OPT_FUSED_MERGE = 1, KVQ_OPT_DETERMINISTIC = 2, KVQ_OPT_TILE_COST_2BIT = 3,
        KVQ_OPT_TILE_COST_4BIT = 4, KVQ_OPT_TILE_COST_8BIT = 5, KVQ_OPT_TILE_COST_16BIT = 6,
-       KVQ_OPT_SHIFT_STRATEGY = 7 };
+       KVQ_OPT_SHIFT_STRATEGY = 7, KVQ_OPT_TIER16 = 8 };
 enum { KVQ_SHIFT_EQUIVALENT = 0, KVQ_SHIFT_DIRECT = 1, KVQ_SHIFT_MODIFIED = 2 };
+enum { KVQ_TIER16_FP16 = 0, KVQ_TIER16_INT16 = 1 };
 kvq_status_t kvq_cache_set_option(kvq_cache_t* cache, int32_t option, int32_t value);
 
 /* Channel-wise reparameterization of one block (Sec. 3.3, Eq. 7): P = (Q Lambda) Q((K Lambda^-1)^T).  After this call

@@ -11,4 +11,5 @@ from .binding import (  # noqa: F401
     KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE, KVQ_OPT_DETERMINISTIC,
     KVQ_OPT_TILE_COST_2BIT, KVQ_OPT_TILE_COST_4BIT, KVQ_OPT_TILE_COST_8BIT, KVQ_OPT_TILE_COST_16BIT,
     KVQ_OPT_SHIFT_STRATEGY, KVQ_SHIFT_EQUIVALENT, KVQ_SHIFT_DIRECT, KVQ_SHIFT_MODIFIED,
+    KVQ_OPT_TIER16, KVQ_TIER16_FP16, KVQ_TIER16_INT16,
 )

@@ -13,6 +13,8 @@ KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE, KVQ_OPT_DETERMINISTIC = 0, 1, 2
 KVQ_OPT_TILE_COST_2BIT, KVQ_OPT_TILE_COST_4BIT, KVQ_OPT_TILE_COST_8BIT, KVQ_OPT_TILE_COST_16BIT = 3, 4, 5, 6
 KVQ_OPT_SHIFT_STRATEGY = 7
 KVQ_SHIFT_EQUIVALENT, KVQ_SHIFT_DIRECT, KVQ_SHIFT_MODIFIED = 0, 1, 2
+KVQ_OPT_TIER16 = 8
+KVQ_TIER16_FP16, KVQ_TIER16_INT16 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -45,7 +47,7 @@ def library_path() -> str:
 
 _SIGNATURES = {
     "kvq_arena_bytes": (C.c_uint64, [C.POINTER(KvqConfig), C.c_uint64]),
-    "kvq_bytes_per_token_head": (C.c_uint64, [C.c_int32] * 4),
+    "kvq_bytes_per_token_head": (C.c_uint64, [C.c_int32] * 5),
     "kvq_cache_create": (C.c_int, [C.POINTER(KvqConfig), C.POINTER(C.c_uint64), C.POINTER(C.c_uint8), C.c_void_p,
                                    C.c_uint64, C.POINTER(C.c_void_p)]),
     "kvq_cache_destroy": (None, [C.c_void_p]),
@@ -125,8 +127,8 @@ def kvq_calibrate_lambda(k_calib, alpha, lam_out, stream=None):
         raise KvqError(st, "kvq_calibrate_lambda")
 
 
-def kvq_bytes_per_token_head(bits, head_dim=128, group=32, count_metadata=1) -> int:
-    return int(load_library().kvq_bytes_per_token_head(bits, head_dim, group, count_metadata))
+def kvq_bytes_per_token_head(bits, head_dim=128, group=32, count_metadata=1, int16_tier=0) -> int:
+    return int(load_library().kvq_bytes_per_token_head(bits, head_dim, group, count_metadata, int16_tier))
 
 
 def _ptr(t):
@@ -220,12 +222,12 @@ class KvqCache:
                 used.value, T.value, cur.value)
 
     def kvq_cache_export_segment(self, layer, segment, which, stream=None):
-        """Returns (codes, scales, zeros) numpy arrays in the canonical format (scales/zeros None for 16-bit)."""
+        """Returns (codes, scales, zeros) numpy arrays in the canonical format (scales/zeros None for raw fp16 runs)."""
         segs, _, _, _ = self.kvq_cache_describe(layer)
         t0, t1, b = segs[segment]
         c = self.cfg
         n = t1 - t0
-        if b == 16:
+        if b == 16 and not getattr(self, "_tier16", 0):
             codes = np.empty((c.batch, c.n_kv_heads, n, c.head_dim), np.float16)
             S = Z = None
             sp = zp = None
@@ -240,6 +242,8 @@ class KvqCache:
 
     def kvq_cache_set_option(self, option, value):
         self._check(self.lib.kvq_cache_set_option(self.handle, option, value), "kvq_cache_set_option")
+        if option == KVQ_OPT_TIER16:
+            self._tier16 = value   # decides the shape of exported 16-bit runs
 
     def kvq_cache_set_reparam(self, layer, lam, stream=None):
         """lam: fp32 device tensor [n_kv_heads, 128], or None to switch the reparameterization off."""

@@ -120,6 +120,24 @@ __device__ inline half8 dq_piece_denorm(const uint32_t* w, int p) {
     return as_half8(r0, r1, r2, r3);
 }
 
+// Width tag 17 stands for a tile of the integer 16-bit tier: 16 bits per code, held as a high-byte and a low-byte
+// plane of 8-bit strings, with metadata.  (A template tag only: page descriptors say 16 for both kinds, and a
+// cache has one kind.)
+#define KVQ_I16 17
+template <int B> constexpr int code_bits() { return B == KVQ_I16 ? 16 : B; }
+template <int B> constexpr bool has_meta() { return B != 16; }
+template <int B> constexpr int q_class() { return B == KVQ_I16 ? 8 : B; }  // arrangement of the query operands
+
+// Piece p of a low-byte plane as exact fp16 fractions c / 256 (the high bytes enter as the integers c).
+__device__ inline half8 dq_piece_frac(const uint32_t* w, int p) {
+    const uint32_t w0 = w[2 * p], w1 = w[2 * p + 1];
+    const uint32_t r0 = pk_fma(__builtin_amdgcn_perm(w1, w0, 0x0c040c00u) | KVQ_MAGIC, 0.00390625f, -4.f);
+    const uint32_t r1 = pk_fma(__builtin_amdgcn_perm(w1, w0, 0x0c050c01u) | KVQ_MAGIC, 0.00390625f, -4.f);
+    const uint32_t r2 = pk_fma(__builtin_amdgcn_perm(w1, w0, 0x0c060c02u) | KVQ_MAGIC, 0.00390625f, -4.f);
+    const uint32_t r3 = pk_fma(__builtin_amdgcn_perm(w1, w0, 0x0c070c03u) | KVQ_MAGIC, 0.00390625f, -4.f);
+    return as_half8(r0, r1, r2, r3);
+}
+
 // The cache is read exactly once per launch: streaming (non-temporal) loads, which measurably raise the HBM
 // rate of a pure read of this size.
 __device__ inline u32x4 load_stream16(const uint8_t* p) {
@@ -225,7 +243,7 @@ struct Stage {
 // K half: scores^T (scaled to log2 units) of the 32 tokens of one tile for the 16 head columns.
 // meta_lds: this tile's 1 KiB metadata, already redistributed through LDS.
 template <int B>
-__device__ inline void scores_tile(const QOps& Q, const uint32_t (&kw)[2 * B], const uint8_t* meta_lds,
+__device__ inline void scores_tile(const QOps& Q, const uint32_t (&kw)[2 * code_bits<B>()], const uint8_t* meta_lds,
                                    float scale_log2, int lane, float (&s)[2][4]) {
     const int j = lane >> 4, n = lane & 15;
     const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
@@ -263,9 +281,12 @@ __device__ inline void scores_tile(const QOps& Q, const uint32_t (&kw)[2 * B], c
             float4v acc = zero4;
 #pragma unroll
             for (int grp = 0; grp < 4; ++grp) {
-                half8 a = dq_piece_denorm<B>(kw, sub * 4 + grp);
                 half8 b = as_half8(Q.q[grp][0], Q.q[grp][1], Q.q[grp][2], Q.q[grp][3]);
-                float4v part = mfma(a, b, zero4);
+                float4v part;
+                if constexpr (B == KVQ_I16)  // (c_hi + c_lo / 256) . q: both planes are exact fp16 operands
+                    part = mfma(dq_piece_frac(kw + 16, sub * 4 + grp), b, mfma(dq_piece<8>(kw, sub * 4 + grp), b, zero4));
+                else
+                    part = mfma(dq_piece_denorm<B>(kw, sub * 4 + grp), b, zero4);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     int tk = 4 * sub + i;  // token 8j + tk: dwords 2*tk, 2*tk+1 hold its four scales
@@ -273,9 +294,11 @@ __device__ inline void scores_tile(const QOps& Q, const uint32_t (&kw)[2 * B], c
                     acc[i] = fmaf(sc, part[i], acc[i]);
                 }
             }
+            // 8, 4, 2 bits: the code operands were denormals, 2^24 restores the sum of S * (c . q); integer 16-bit
+            // tier: the operands were codes / 256
+            const float restore = B == KVQ_I16 ? 256.0f : 16777216.0f;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)  // the code operands were denormals: 2^24 restores the sum of S * (c . q)
-                s[sub][i] = fmaf(acc[i], scale_log2 * 16777216.0f, zacc[i]);
+            for (int i = 0; i < 4; ++i) s[sub][i] = fmaf(acc[i], scale_log2 * restore, zacc[i]);
         }
     }
 }
@@ -286,7 +309,7 @@ __device__ inline void scores_tile(const QOps& Q, const uint32_t (&kw)[2 * B], c
 // add true values.
 template <int B>
 __device__ inline int v_exponent(int safe_v) {
-    if (B == 16 || safe_v) return 0;
+    if (B == 16 || B == KVQ_I16 || safe_v) return 0;
     return B == 2 ? 6 - 24 : B == 4 ? 4 - 24 : -24;
 }
 __device__ inline void set_accumulator_exponent(WaveState& st, int e) {
@@ -303,7 +326,7 @@ __device__ inline void set_accumulator_exponent(WaveState& st, int e) {
 // stay below the fp16 maximum: caches whose quantizer ever produced a V scale >= 256 take the other path, which
 // builds exact fp16 integers from the codes instead (two ops per two codes) and adds true values.
 template <int B, bool SAFE>
-__device__ inline void accumulate_tile(WaveState& st, const uint32_t (&vw)[2 * B], const uint8_t* meta_lds,
+__device__ inline void accumulate_tile(WaveState& st, const uint32_t (&vw)[2 * code_bits<B>()], const uint8_t* meta_lds,
                                        const uint8_t* const_lds, const uint32_t (&pop)[4], int lane) {
     const int j = lane >> 4, n = lane & 15;
     const half8 pb = as_half8(pop[0], pop[1], pop[2], pop[3]);
@@ -321,7 +344,22 @@ __device__ inline void accumulate_tile(WaveState& st, const uint32_t (&vw)[2 * B
         const uint8_t* zsrc = (n < 4) ? meta_lds + 768 + n * 64 + j * 16 : const_lds + (n == 4 ? 0 : 16);
         u32x4 zv = *reinterpret_cast<const u32x4*>(zsrc);
         st.zl = mfma(as_half8(zv.x, zv.y, zv.z, zv.w), pb, st.zl);
-        if constexpr (SAFE) {
+        if constexpr (B == KVQ_I16) {
+            // true values: (c_hi + c_lo / 256) * (p * 256 S_v); 256 S_v is exact and at most 512
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x4 sv = *reinterpret_cast<const u32x4*>(meta_lds + 512 + g * 64 + j * 16);
+                const uint32_t k256 = 0x5c005c00u;  // two fp16 256.0
+                half8 pg = as_half8(pk_mul(pop[0], pk_mul(sv.x, k256)), pk_mul(pop[1], pk_mul(sv.y, k256)),
+                                    pk_mul(pop[2], pk_mul(sv.z, k256)), pk_mul(pop[3], pk_mul(sv.w, k256)));
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    int nt = 2 * g + h;
+                    st.o[nt] = mfma(dq_piece<8>(vw, nt), pg, st.o[nt]);
+                    st.o[nt] = mfma(dq_piece_frac(vw + 16, nt), pg, st.o[nt]);
+                }
+            }
+        } else if constexpr (SAFE) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 u32x4 sv = *reinterpret_cast<const u32x4*>(meta_lds + 512 + g * 64 + j * 16);
@@ -556,21 +594,22 @@ __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds,
                                   int lane) {
     set_accumulator_exponent(st, v_exponent<B>(SAFE));
     if constexpr (B >= 8) {
-        // wide tiles (8 and 16 KiB): one register stage, tile by tile, K and V staggered (V loads fly during
+        // wide tiles (8 and 16 KiB, the latter raw fp16 or integer byte planes): one register stage, tile by tile, K and V staggered (V loads fly during
         // the K product, the next tile's K and metadata loads during the V product)
-        uint32_t kw[2 * B], vw[2 * B];
+        constexpr int W = code_bits<B>();
+        uint32_t kw[2 * W], vw[2 * W];
         u32x4 mreg = {0u, 0u, 0u, 0u};
         Claim cur = c.next;
         int k = 0;
-        load_string<2 * B>(cur.code, c.lane_off, kw);
-        if constexpr (B < 16) mreg = load_stream16(cur.meta + c.lane_off);
-        load_string<2 * B>(cur.code + 512u * B, c.lane_off, vw);
-        if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);
+        load_string<2 * W>(cur.code, c.lane_off, kw);
+        if constexpr (has_meta<B>()) mreg = load_stream16(cur.meta + c.lane_off);
+        load_string<2 * W>(cur.code + 512u * W, c.lane_off, vw);
+        if (Q.cls != q_class<B>()) load_q_ops(Q, q_lds, lane, q_class<B>(), c.scale_log2);
         for (;;) {
             float s[1][2][4];
             uint32_t pop[1][4];
             const int tok0[1] = {(cur.tile + k) * KVQ_TILE_TOKENS};
-            if constexpr (B < 16) {
+            if constexpr (has_meta<B>()) {
                 *reinterpret_cast<u32x4*>(meta_lds + lane * 16) = mreg;
                 wave_lds_sync();
             }
@@ -579,27 +618,27 @@ __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds,
             bool more;
             if (k + 1 < cur.nt) {  // next tile of the same chunk
                 ++k;
-                code = cur.code + k * (1024u * B);
+                code = cur.code + k * (1024u * W);
                 meta = cur.meta + k * KVQ_META_TILE_BYTES;
                 more = true;
             } else {  // a wide tile takes long enough to claim its successor only now
                 advance_begin(c);
                 advance_end(c);
-                more = c.next.bits == B;
+                more = c.next.bits == (uint32_t)W;
                 if (more) { cur = c.next; k = 0; code = cur.code; meta = cur.meta; }
             }
             if (!more) {  // last tile of the run
                 softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
                 accumulate_tile<B, SAFE>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
-                if constexpr (B < 16) wave_lds_sync();
+                if constexpr (has_meta<B>()) wave_lds_sync();
                 return;
             }
-            load_string<2 * B>(code, c.lane_off, kw);
-            if constexpr (B < 16) mreg = load_stream16(meta + c.lane_off);
+            load_string<2 * W>(code, c.lane_off, kw);
+            if constexpr (has_meta<B>()) mreg = load_stream16(meta + c.lane_off);
             softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
             accumulate_tile<B, SAFE>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
-            if constexpr (B < 16) wave_lds_sync();
-            load_string<2 * B>(code + 512u * B, c.lane_off, vw);
+            if constexpr (has_meta<B>()) wave_lds_sync();
+            load_string<2 * W>(code + 512u * W, c.lane_off, vw);
         }
     } else {
         // narrow tiles: a ring of N register stages of TPI tiles each, N - 1 of them in flight
@@ -791,8 +830,10 @@ struct AttnShared {
 
 static_assert(4 * 16 * KVQ_OPAD >= KVQ_MERGE_LDS_FLOATS, "the reduction slab doubles as merge scratch");
 
-// The whole kernel for one of the two V paths (SAFE: overflow-proof, see accumulate_tile).
-template <bool SAFE>
+// The whole kernel for one of the two V paths (SAFE: overflow-proof, see accumulate_tile) and one of the two kinds
+// of 16-bit tier (I16: integer codes in byte planes; else raw fp16, which is also the kind a one-token append can
+// be fused into).  A cache has one kind only, so each kernel carries the code of one.
+template <bool SAFE, bool I16>
 __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShared& sh) {
     _Float16* const q_lds = sh.q;
     float (*const red_o)[16 * KVQ_OPAD] = sh.red_o;
@@ -843,13 +884,13 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
     // the token.  Its wavefront 0 does that after the staging barrier, waits until the stores have reached L2 and
     // takes the chunk that holds the tile as its first one (nobody else can claim it); the other seven wavefronts
     // start on the rest of the range meanwhile.
-    const int tile_new = P.app_t_old >= 0 ? P.app_t_old / KVQ_TILE_TOKENS : -1;
+    const int tile_new = (!I16 && P.app_t_old >= 0) ? P.app_t_old / KVQ_TILE_TOKENS : -1;
     const bool appends = tile_new >= t_begin && tile_new < t_end;
     const bool one_window = p_last - p_first <= KVQ_DESC_CACHE;
     // the first chunk of every wavefront is fixed (see below); the counter starts behind them
     if (tid == 0) claim_ctr = (appends && one_window) ? KVQ_ATTN_WAVES - 1 : KVQ_ATTN_WAVES;
     __syncthreads();
-    if (appends && wave == 0) {
+    if (!I16 && appends && wave == 0) {
         const int tip = tile_new - (tile_new / tpp) * tpp;
         const uint64_t tslot = (uint64_t)unit * tpp + tip;
         uint8_t* code = const_cast<uint8_t*>(P.arena) + (uint64_t)P.app_desc.code_off256 * 256u + tslot * 2 * (512u * 16);
@@ -925,7 +966,10 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
         ctx.n_chunks = reserve ? n_all - 1 : n_all;
         while (ctx.next.bits != 0u) {
             switch (ctx.next.bits) {
-                case 16: run_chunks<16, 1, 2, false>(st, Q, q_lds, ctx, my_meta, lane); break;
+                case 16:
+                    if constexpr (I16) run_chunks<KVQ_I16, 1, 2, false>(st, Q, q_lds, ctx, my_meta, lane);
+                    else run_chunks<16, 1, 2, false>(st, Q, q_lds, ctx, my_meta, lane);
+                    break;
                 case 8: run_chunks<8, 1, 2, SAFE>(st, Q, q_lds, ctx, my_meta, lane); break;
                 case 4: run_chunks<4, 2, KVQ_RING_4BIT, SAFE>(st, Q, q_lds, ctx, my_meta, lane); break;
                 default: run_chunks<2, 2, KVQ_RING_2BIT, SAFE>(st, Q, q_lds, ctx, my_meta, lane); break;
@@ -1027,8 +1071,15 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
 // grid = (splits, units); 512 threads = 8 wavefronts, one workgroup per compute unit.
 __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const KvqAttnParams P) {
     __shared__ AttnShared sh;
-    if (__builtin_amdgcn_readfirstlane(P.flags[0] & 1u)) attention_body<true>(P, sh);
-    else attention_body<false>(P, sh);
+    if (__builtin_amdgcn_readfirstlane(P.flags[0] & 1u)) attention_body<true, false>(P, sh);
+    else attention_body<false, false>(P, sh);
+}
+
+// The same for a cache whose 16-bit tier holds integer codes.
+__global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_i16_kernel(const KvqAttnParams P) {
+    __shared__ AttnShared sh;
+    if (__builtin_amdgcn_readfirstlane(P.flags[0] & 1u)) attention_body<true, true>(P, sh);
+    else attention_body<false, true>(P, sh);
 }
 
 // Same thread count as the attention kernel, so both merge variants add in the same order.
@@ -1046,7 +1097,8 @@ extern "C" int kvq_debug_read(unsigned long long* host) {
 #endif
 
 hipError_t kvq_launch_attention(const KvqAttnParams& p, int units, hipStream_t s) {
-    hipLaunchKernelGGL(kvq_attention_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
+    if (p.int16_tier) hipLaunchKernelGGL(kvq_attention_i16_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
+    else hipLaunchKernelGGL(kvq_attention_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.n_splits > 1 && !p.fused_merge) {

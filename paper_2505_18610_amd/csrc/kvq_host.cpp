@@ -68,7 +68,7 @@ struct Page {
     int bits = 16;
     int n = 0;              // tokens stored
     uint32_t code_unit = 0; // allocation offsets in units
-    uint32_t meta_unit = 0; // valid when bits < 16
+    uint32_t meta_unit = 0; // valid when the page has metadata (bits < 16, or the integer 16-bit tier)
 };
 
 struct Layer {
@@ -104,19 +104,22 @@ struct kvq_cache {
     int fused_merge = 1;
     int deterministic = 0;
     int shift_strategy = KVQ_SHIFT_EQUIVALENT;  // how 2b -> b steps treat codes, S and Z (Sec. 4.3.1)
+    int tier16 = KVQ_TIER16_FP16;               // what a 16-bit token is: raw fp16, or 16-bit codes with (S, Z)
+    bool int16() const { return tier16 == KVQ_TIER16_INT16; }
+    bool has_meta(int bits) const { return bits < 16 || int16(); }
     int tile_cost[4] = {100, 145, 250, 300};  // relative kernel time of one 2/4/8/16-bit tile (measured)
     int target_workgroups = 256;
 
     uint64_t bpth(int bits) const {
-        return kvq_bytes_per_token_head(bits, cfg.head_dim, cfg.group, cfg.count_metadata_in_budget);
+        return kvq_bytes_per_token_head(bits, cfg.head_dim, cfg.group, cfg.count_metadata_in_budget, int16() ? 1 : 0);
     }
     uint64_t unit_off_bytes(uint32_t unit) const { return pages_off + (uint64_t)unit * unit_bytes; }
     KvqPageDesc desc(const Page& p) const {
         KvqPageDesc d;
         d.code_off256 = (uint32_t)(unit_off_bytes(p.code_unit) / 256);
-        d.meta_off256 = p.bits < 16 ? (uint32_t)(unit_off_bytes(p.meta_unit) / 256) : 0u;
+        d.meta_off256 = has_meta(p.bits) ? (uint32_t)(unit_off_bytes(p.meta_unit) / 256) : 0u;
         d.bits = (uint32_t)p.bits;
-        d.pad = 0;
+        d.int16 = (p.bits == 16 && int16()) ? 1u : 0u;
         return d;
     }
     float* lambda_dev(int layer) const {  // lambda of the block; its reciprocals follow
@@ -231,17 +234,18 @@ struct Lowering {  // one page to lower and the blocks allocated for it
     uint32_t new_code = 0, new_meta = 0;
 };
 
-// Allocate destination blocks for a set of lowerings; on failure release what was taken.
+// Allocate destination blocks for a set of lowerings (a metadata block too when the source page has none); on
+// failure release what was taken.
 bool alloc_lowerings(kvq_cache* c, std::vector<Lowering>& low) {
     for (size_t i = 0; i < low.size(); ++i) {
         bool ok = c->buddy.alloc(order_of_bits(low[i].to), &low[i].new_code);
         bool ok2 = true;
-        if (ok && low[i].from == 16) ok2 = c->buddy.alloc(0, &low[i].new_meta);
+        if (ok && !c->has_meta(low[i].from)) ok2 = c->buddy.alloc(0, &low[i].new_meta);
         if (!ok || !ok2) {
             if (ok) c->buddy.release(low[i].new_code, order_of_bits(low[i].to));
             for (size_t k = 0; k < i; ++k) {
                 c->buddy.release(low[k].new_code, order_of_bits(low[k].to));
-                if (low[k].from == 16) c->buddy.release(low[k].new_meta, 0);
+                if (!c->has_meta(low[k].from)) c->buddy.release(low[k].new_meta, 0);
             }
             return false;
         }
@@ -249,11 +253,13 @@ bool alloc_lowerings(kvq_cache* c, std::vector<Lowering>& low) {
     return true;
 }
 
-// Enqueue the kernels for lowerings that all share (from, to), then commit the host tables.
-kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, hipStream_t s) {
+// Enqueue the kernel for lowerings that all share (from, to) -- one halving, or fp16 values to any width -- then
+// commit the host tables.
+kvq_status_t run_lowering_step(kvq_cache* c, int layer, std::vector<Lowering>& low, hipStream_t s) {
     if (low.empty()) return KVQ_OK;
     Layer& L = c->layers[(size_t)layer];
     const int from = low[0].from, to = low[0].to;
+    const bool fresh_meta = !c->has_meta(from);  // raw fp16 pages carry no metadata yet
     if (!alloc_lowerings(c, low)) return KVQ_E_OOM;
     if (!c->dry) {
         std::vector<KvqRequantJob> jobs(low.size());
@@ -261,7 +267,7 @@ kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, 
             const Page& p = L.pages[(size_t)low[i].page];
             jobs[i].src_code_off256 = (uint32_t)(c->unit_off_bytes(p.code_unit) / 256);
             jobs[i].dst_code_off256 = (uint32_t)(c->unit_off_bytes(low[i].new_code) / 256);
-            jobs[i].meta_off256 = (uint32_t)(c->unit_off_bytes(from == 16 ? low[i].new_meta : p.meta_unit) / 256);
+            jobs[i].meta_off256 = (uint32_t)(c->unit_off_bytes(fresh_meta ? low[i].new_meta : p.meta_unit) / 256);
             jobs[i].pad = 0;
         }
         KvqRequantJob* jd = reinterpret_cast<KvqRequantJob*>(c->arena + c->jobs_off);
@@ -270,13 +276,13 @@ kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, 
         hipError_t e = hipSuccess;
         if (st == KVQ_OK) {
             const KvqRequantJob* jh = by_arg ? jobs.data() : nullptr;
-            e = (from == 16) ? kvq_launch_quant16(to, c->arena, jd, jh, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), c->cfg.group, s)
+            e = fresh_meta ? kvq_launch_quant16(to, c->arena, jd, jh, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), c->cfg.group, s)
                              : kvq_launch_shrink(to, c->shift_strategy, c->arena, jd, jh, (int)jobs.size(), c->tpp, c->units, c->flags_dev(), s);
         }
         if (st != KVQ_OK || e != hipSuccess) {
             for (auto& w : low) {
                 c->buddy.release(w.new_code, order_of_bits(w.to));
-                if (w.from == 16) c->buddy.release(w.new_meta, 0);
+                if (fresh_meta) c->buddy.release(w.new_meta, 0);
             }
             return st != KVQ_OK ? st : KVQ_E_HIP;
         }
@@ -286,13 +292,27 @@ kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, 
         Page& p = L.pages[(size_t)w.page];
         c->buddy.release(p.code_unit, order_of_bits(p.bits));  // reused only by work enqueued later
         p.code_unit = w.new_code;
-        if (from == 16) p.meta_unit = w.new_meta;
+        if (fresh_meta) p.meta_unit = w.new_meta;
         p.bits = to;
         lo = std::min(lo, w.page);
         hi = std::max(hi, w.page + 1);
     }
     L.version++;
     return upload_table(c, layer, lo, hi, s);
+}
+
+// Lower a set of pages that share (from, to).  Pages of the integer 16-bit tier go down one halving at a time
+// (16 -> 8 -> 4 -> 2 by the configured shift strategy); raw fp16 pages are quantized to the target width directly.
+kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, hipStream_t s) {
+    if (low.empty()) return KVQ_OK;
+    const int from = low[0].from, to = low[0].to;
+    if (!(c->int16() && from == 16 && to < 8)) return run_lowering_step(c, layer, low, s);
+    for (int b = 8; b >= to; b /= 2) {
+        for (auto& w : low) { w.from = 2 * b; w.to = b; w.new_code = w.new_meta = 0; }
+        kvq_status_t st = run_lowering_step(c, layer, low, s);
+        if (st != KVQ_OK) return st;  // the pages stay at the width they reached
+    }
+    return KVQ_OK;
 }
 
 void build_segments(const kvq_cache* c, const Layer& L, std::vector<kvq_segment_info_t>& out) {
@@ -347,10 +367,11 @@ void plan_splits(kvq_cache* c, Layer& L, int n_tiles, int n_splits) {
 
 extern "C" {
 
-uint64_t kvq_bytes_per_token_head(int32_t bits, int32_t head_dim, int32_t group, int32_t count_metadata) {
+uint64_t kvq_bytes_per_token_head(int32_t bits, int32_t head_dim, int32_t group, int32_t count_metadata,
+                                  int32_t int16_tier) {
     if (!valid_bits(bits) || head_dim <= 0 || group <= 0) return 0;
     uint64_t n = 2ull * head_dim * bits / 8;
-    if (count_metadata && bits < 16) n += 2ull * (head_dim / group) * 4;
+    if (count_metadata && (bits < 16 || int16_tier)) n += 2ull * (head_dim / group) * 4;
     return n;
 }
 
@@ -481,12 +502,12 @@ kvq_status_t append_impl(kvq_cache_t* c, int32_t layer, const void* k_dev, const
         p.bits = e;
         bool ok = c->buddy.alloc(order_of_bits(e), &p.code_unit);
         bool ok2 = true;
-        if (ok && e < 16) ok2 = c->buddy.alloc(0, &p.meta_unit);
+        if (ok && c->has_meta(e)) ok2 = c->buddy.alloc(0, &p.meta_unit);
         if (!ok || !ok2) {
             if (ok) c->buddy.release(p.code_unit, order_of_bits(e));
             for (Page& q : fresh) {
                 c->buddy.release(q.code_unit, order_of_bits(e));
-                if (e < 16) c->buddy.release(q.meta_unit, 0);
+                if (c->has_meta(e)) c->buddy.release(q.meta_unit, 0);
             }
             return KVQ_E_OOM;
         }
@@ -501,7 +522,7 @@ kvq_status_t append_impl(kvq_cache_t* c, int32_t layer, const void* k_dev, const
     L.version++;
     st = upload_table(c, layer, (int)old_pages, (int)L.pages.size(), s);
     if (st != KVQ_OK) return st;
-    if (!c->dry && defer && n_new == 1 && e == 16) {
+    if (!c->dry && defer && n_new == 1 && e == 16 && !c->int16()) {
         defer->active = true;
         defer->t_old = t_old;
         defer->desc = c->desc(L.pages[(size_t)(t_old / P)]);
@@ -517,7 +538,7 @@ kvq_status_t append_impl(kvq_cache_t* c, int32_t layer, const void* k_dev, const
         if (kvq_launch_append(e, c->arena, c->table_dev(layer), k_dev, v_dev, t_old, n_new, c->tpp, c->units,
                               by_arg ? two : nullptr, pg0, c->flags_dev(), c->cfg.group,
                               L.reparam ? c->lambda_dev(layer) + c->cfg.n_kv_heads * KVQ_D : nullptr, c->cfg.n_kv_heads,
-                              cos_sin_dev, s) != hipSuccess)
+                              cos_sin_dev, c->int16(), s) != hipSuccess)
             return KVQ_E_HIP;
     }
     if (!evicted.empty()) {
@@ -648,6 +669,7 @@ kvq_status_t attention_impl(kvq_cache_t* c, int32_t layer, const void* q_dev, vo
     p.out_fp32 = out_is_fp32 ? 1 : 0;
     p.fused_merge = c->fused_merge;
     p.deterministic = c->deterministic;
+    p.int16_tier = c->int16() ? 1 : 0;
     const float scale = softmax_scale != 0.f ? softmax_scale : 1.0f / std::sqrt((float)c->cfg.head_dim);
     p.scale_log2 = scale * 1.44269504088896340736f;
     std::memcpy(p.split_begin, L.split_begin, sizeof(int32_t) * (size_t)(n_splits + 1));
@@ -710,12 +732,13 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* c, int32_t layer, int32_t seg
     if (segment >= (int)segs.size()) return KVQ_E_STATE;
     const kvq_segment_info_t sg = segs[(size_t)segment];
     const int b = sg.bits, P = c->cfg.page_tokens, tpp = c->tpp;
-    if (b < 16 && (!scales_host || !zeros_host)) return KVQ_E_INVALID;
+    const bool meta_out = c->has_meta(b), planes = b == 16 && c->int16();
+    if (meta_out && (!scales_host || !zeros_host)) return KVQ_E_INVALID;
     hipStream_t s = as_stream(hip_stream);
     const int n_seg = sg.token_end - sg.token_begin;
     const size_t row_bytes = (size_t)KVQ_D * b / 8;
     const size_t code_block = (size_t)c->unit_bytes * b;
-    std::vector<uint8_t> code(code_block), meta(b < 16 ? (size_t)c->unit_bytes : 0);
+    std::vector<uint8_t> code(code_block), meta(meta_out ? (size_t)c->unit_bytes : 0);
     uint8_t* oc = static_cast<uint8_t*>(codes_host);
     uint16_t* os = static_cast<uint16_t*>(scales_host);
     uint16_t* oz = static_cast<uint16_t*>(zeros_host);
@@ -723,7 +746,7 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* c, int32_t layer, int32_t seg
         const Page& p = L.pages[(size_t)pg];
         if (hipMemcpyAsync(code.data(), c->arena + c->unit_off_bytes(p.code_unit), code_block, hipMemcpyDeviceToHost, s) != hipSuccess)
             return KVQ_E_HIP;
-        if (b < 16 && hipMemcpyAsync(meta.data(), c->arena + c->unit_off_bytes(p.meta_unit), meta.size(), hipMemcpyDeviceToHost, s) != hipSuccess)
+        if (meta_out && hipMemcpyAsync(meta.data(), c->arena + c->unit_off_bytes(p.meta_unit), meta.size(), hipMemcpyDeviceToHost, s) != hipSuccess)
             return KVQ_E_HIP;
         if (hipStreamSynchronize(s) != hipSuccess) return KVQ_E_HIP;
         for (int u = 0; u < c->units; ++u) {
@@ -739,7 +762,10 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* c, int32_t layer, int32_t seg
                     if (which == KVQ_WHICH_K) kvq_k_slot(t, d, &lane, &slot);
                     else kvq_v_slot(t, d, &lane, &slot);
                     const uint32_t bit = (uint32_t)slot * b;
-                    if (b == 16) {
+                    if (planes) {  // high-byte plane, then low-byte plane, each laid out like an 8-bit tile
+                        row[2 * d] = tile[512u * 8 + kvq_tile_byte(lane, (uint32_t)slot)];
+                        row[2 * d + 1] = tile[kvq_tile_byte(lane, (uint32_t)slot)];
+                    } else if (b == 16) {
                         const uint8_t* src = tile + kvq_tile_byte(lane, bit / 8);
                         row[2 * d] = src[0];
                         row[2 * d + 1] = src[1];
@@ -748,7 +774,7 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* c, int32_t layer, int32_t seg
                         row[(size_t)d * b / 8] |= (uint8_t)(v << ((d * b) % 8));
                     }
                 }
-                if (b < 16) {
+                if (meta_out) {
                     const uint16_t* m = reinterpret_cast<const uint16_t*>(meta.data() + tslot * KVQ_META_TILE_BYTES);
                     // the device keeps one (S, Z) per run of 32 channels (a group of 64 or 128 channels repeats
                     // its pair); the canonical format has one per group
@@ -782,6 +808,12 @@ kvq_status_t kvq_cache_set_option(kvq_cache_t* c, int32_t option, int32_t value)
         case KVQ_OPT_SHIFT_STRATEGY:
             if (value != KVQ_SHIFT_EQUIVALENT && value != KVQ_SHIFT_DIRECT && value != KVQ_SHIFT_MODIFIED) return KVQ_E_INVALID;
             c->shift_strategy = value;
+            return KVQ_OK;
+        case KVQ_OPT_TIER16:
+            if (value != KVQ_TIER16_FP16 && value != KVQ_TIER16_INT16) return KVQ_E_INVALID;
+            for (const auto& L : c->layers)
+                if (L.T != 0) return KVQ_E_STATE;  // the tier decides what every 16-bit page holds
+            c->tier16 = value;
             return KVQ_OK;
         case KVQ_OPT_TILE_COST_2BIT:
         case KVQ_OPT_TILE_COST_4BIT:

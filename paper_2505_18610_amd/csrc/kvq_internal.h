@@ -9,7 +9,7 @@
 struct KvqRequantJob {        // one page to re-quantize
     uint32_t src_code_off256; // source code block
     uint32_t dst_code_off256; // destination code block
-    uint32_t meta_off256;     // metadata block (updated in place for 2b -> b, written for 16 -> b)
+    uint32_t meta_off256;     // metadata block (updated in place for 2b -> b, written for fp16 -> b)
     uint32_t pad;
 };
 
@@ -42,6 +42,7 @@ struct KvqAttnParams {
     int32_t out_fp32;
     int32_t fused_merge;
     int32_t deterministic;     // 1: static chunk-to-wavefront assignment (bit-reproducible summation order)
+    int32_t int16_tier;        // 1: 16-bit pages hold integer codes in byte planes (selects the kernel)
     float scale_log2;          // softmax scale * log2(e)
     int32_t split_begin[KVQ_MAX_SPLITS + 1];  // tile index where each split starts
     // a one-token append into the 16-bit tier done by the workgroup that owns the last tile (app_t_old < 0: none)
@@ -57,7 +58,7 @@ struct KvqAttnParams {
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
                              const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group,
-                             const float* rinv, int n_kv_heads, const float* rope, hipStream_t s);
+                             const float* rinv, int n_kv_heads, const float* rope, bool int16, hipStream_t s);
 hipError_t kvq_launch_shrink(int dst_bits, int strategy, uint8_t* arena, const KvqRequantJob* jobs_dev,
                              const KvqRequantJob* jobs_host, int n_jobs, int tiles_per_page, int units,
                              uint32_t* flags, hipStream_t s);

@@ -16,7 +16,12 @@
 // is cut into 16-byte chunks and chunk c of lane l is stored at byte (c*64 + l)*16 of the tile, so every
 // 16-byte load of a wavefront is one contiguous kilobyte.  A tile of width b takes 512*b bytes.
 //
-// Per tile 1 KiB of metadata (fp16), quantized widths only:
+// A tile of the integer 16-bit tier (16-bit codes with scales and zero points, the INT16 format of Sec. 4.1.2)
+// is two 8-bit tiles back to back: first the high bytes of the 64 codes of every lane, laid out exactly like an
+// 8-bit tile (4 KiB), then the low bytes (4 KiB).  Bytes are exact fp16 integers, so the matrix cores can take
+// the two planes separately, and the Direct and Modified Right Shift to 8 bits are a copy of the first plane.
+//
+// Per tile 1 KiB of metadata (fp16), quantized widths and the integer 16-bit tier only:
 //   [   0, 256) K scales  S[token][grp]            [ 256, 512) K zero points, same order
 //   [ 512, 768) V scales  S[grp][8*j + 2*v + hi]  for token 8*j + v + 4*hi   (the pairing of MFMA operand
 //   [ 768,1024) V zero points, same order           registers: register v holds slots v and v+4)
@@ -44,9 +49,9 @@
 
 struct KvqPageDesc {       // one entry of a block's device page table
     uint32_t code_off256;  // code block offset from the arena base, in 256-byte units
-    uint32_t meta_off256;  // metadata block offset, in 256-byte units (unused for 16-bit pages)
+    uint32_t meta_off256;  // metadata block offset, in 256-byte units (unused for raw fp16 pages)
     uint32_t bits;         // 16, 8, 4, 2
-    uint32_t pad;
+    uint32_t int16;        // 1: a 16-bit page of the integer tier (two byte planes and metadata); else 0
 };
 
 KVQ_HD uint32_t kvq_tile_code_bytes(int bits) { return 512u * (uint32_t)bits; }   // one K or V tile

@@ -114,6 +114,14 @@ __device__ inline void quantize_owner(const uint32_t (&w)[16], float (&codes)[32
     if (gspan >= 4) { mn = fminf(mn, __shfl_xor(mn, 2)); mx = fmaxf(mx, __shfl_xor(mx, 2)); }
     float Sf;
     group_params(mn, mx, levels, S, Z, &Sf);
+    if constexpr (B == 16) {  // codes up to 65535: the reciprocal shortcut is not accurate enough, divide
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            const float x = h2f((uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffff)));
+            codes[e] = (float)code_of(x, mn, Sf, levels);
+        }
+        return;
+    }
     const float rcp = (Sf == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(Sf);
     float worst = 0.0f;
 #pragma unroll
@@ -327,6 +335,87 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
     store_chunks<B>(code, lane, str);
 }
 
+// Append into the integer 16-bit tier: Eq. 1-2 with 2^16 - 1 levels by the same owner lanes; the high and the low
+// bytes of the codes then travel through LDS and into the tile's two byte planes like two 8-bit tiles.
+__global__ __launch_bounds__(64) void kvq_append_i16_kernel(uint8_t* __restrict__ arena,
+                                                            const KvqPageDesc* __restrict__ table,
+                                                            const uint16_t* __restrict__ k_in,
+                                                            const uint16_t* __restrict__ v_in, int t_old,
+                                                            int n_new, int tpp, int tile0, KvqAppendPages ap,
+                                                            int gspan, const float* __restrict__ rinv,
+                                                            int n_kv_heads, const float* __restrict__ rope) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2][KVQ_LDS_CODES];
+    const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
+    const int which = blockIdx.x & 1;
+    const int tile = tile0 + (blockIdx.x >> 1);
+    const int unit = blockIdx.y;
+    const int page = tile / tpp, tip = tile - page * tpp;
+    const KvqPageDesc pd = append_desc(table, ap, page);
+    const uint64_t tslot = (uint64_t)unit * tpp + tip;
+    uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * 16);
+    uint8_t* meta = arena + (uint64_t)pd.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
+    const int t_new = t_old + n_new, tok0 = tile * KVQ_TILE_TOKENS;
+    const uint16_t* in = (which ? v_in : k_in) + (uint64_t)unit * n_new * KVQ_D;
+    const int grp = lane & 3;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tl = 16 * pass + (lane >> 2);
+        const int tok = tok0 + tl;
+        const bool isnew = tok >= t_old && tok < t_new;
+        uint32_t w[16];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (isnew) {
+                const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
+                if (which) v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
+                else v = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr,
+                                   rinv ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
+            }
+            w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+        }
+        float codes[32], lo[32];
+        uint16_t S, Z;
+        quantize_owner<16>(w, codes, &S, &Z, gspan);
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {  // exact: integers below 2^16
+            const float hi = floorf(codes[e] * 0.00390625f);
+            lo[e] = codes[e] - 256.0f * hi;
+            codes[e] = hi;
+        }
+        scatter_codes(lds[0], which, tl, grp, codes);
+        scatter_codes(lds[1], which, tl, grp, lo);
+        if (tok >= t_old) store_meta_owner(meta, which, tl, grp, S, Z);
+    }
+    wave_sync_lds();
+    uint32_t keep = 0;  // stored tokens keep their bits
+    if (!which) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+            if (tok0 + 8 * (n >> 2) + 4 * sub + (n & 3) < t_old) keep |= 1u << sub;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (tok0 + 8 * j + i < t_old) keep |= 1u << i;
+    }
+#pragma unroll
+    for (int plane = 0; plane < 2; ++plane) {
+        uint32_t str[16];
+        gather_string<8>(lds[plane], which, lane, str);
+        uint8_t* dst = code + plane * (512u * 8);
+        if (tok0 < t_old && keep) {
+            uint32_t old[16];
+            load_chunks<8>(dst, lane, old);
+#pragma unroll
+            for (int d = 0; d < 16; ++d) {
+                uint32_t m = which ? v_token_mask<8>(keep, d) : (((keep >> (d / 8)) & 1u) ? 0xffffffffu : 0u);
+                str[d] = (old[d] & m) | (str[d] & ~m);
+            }
+        }
+        store_chunks<8>(dst, lane, str);
+    }
+}
+
 // ------------------------------------------------------------------------------------- fp16 page -> b bits
 // grid.x = 2 * n_jobs * tiles_per_page, grid.y = unit, 64 threads.  Direct quantization (Eq. 1-2) of a page
 // that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by
@@ -397,7 +486,8 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
 
 // ------------------------------------------------------------------------------- Equivalent Right Shift
 // Eq. 3 on packed codes, slot order preserved, several codes per 32-bit multiply (no carry can cross a field:
-// 13*(15+2) < 2^8 and 241*(255+8) < 2^16).
+// 13*(15+2) < 2^8 and 241*(255+8) < 2^16).  From the integer 16-bit tier the product 65281 * (X + 128) needs all 32
+// bits of an unsigned multiply (largest value 4,286,546,303), so that step takes one multiply per code.
 __device__ inline uint32_t shrink_4_to_2(uint32_t w) {  // 8 nibbles -> 8 two-bit codes (16 bits)
     uint32_t e = w & 0x0f0f0f0fu, o = (w >> 4) & 0x0f0f0f0fu;
     e = (((e + 0x02020202u) * 13u) >> 6) & 0x03030303u;
@@ -405,6 +495,15 @@ __device__ inline uint32_t shrink_4_to_2(uint32_t w) {  // 8 nibbles -> 8 two-bi
     uint32_t c = e | (o << 2);
     c = (c | (c >> 4)) & 0x00ff00ffu;
     return (c | (c >> 8)) & 0xffffu;
+}
+__device__ inline uint32_t shrink_16_to_8(uint32_t hi, uint32_t lo) {  // 4 high bytes, 4 low bytes -> 4 bytes
+    uint32_t out = 0u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t x = (((hi >> (8 * k)) & 0xffu) << 8) | ((lo >> (8 * k)) & 0xffu);
+        out |= ((65281u * (x + 128u)) >> 24) << (8 * k);
+    }
+    return out;
 }
 __device__ inline uint32_t shrink_8_to_4(uint32_t w) {  // 4 bytes -> 4 nibbles (16 bits)
     uint32_t e = w & 0x00ff00ffu, o = (w >> 8) & 0x00ff00ffu;
@@ -433,7 +532,7 @@ __device__ inline uint32_t trunc_8_to_4(uint32_t w) {  // 4 bytes -> their upper
 
 // grid.x = n_jobs * tiles_per_page, grid.y = unit, 64 threads; one wavefront shrinks the K and the V tile of
 // one (page, unit, tile) from 2B to B bits and rewrites its 256 scales (and, for the Modified strategy, zero
-// points) in place.
+// points) in place.  B = 8 is the step out of the integer 16-bit tier.
 //   STRAT 0, Equivalent Right Shift (Eq. 3):  codes by Eq. 3, S <- (2^B + 1) S, Z kept
 //   STRAT 1, Direct Right Shift:              codes >> B,     S <- (2^B + 1) S, Z kept
 //   STRAT 2, Modified Right Shift:            codes >> B,     S <- 2^B S,       Z <- Z + (2^B S - S) / 2
@@ -466,7 +565,10 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
         uint32_t out[2 * B];
 #pragma unroll
         for (int d = 0; d < 2 * B; ++d) {
-            if constexpr (STRAT == KVQ_SHIFT_EQUIVALENT_) {
+            if constexpr (B == 8) {  // source: high-byte plane in[0..15], low-byte plane in[16..31]
+                if constexpr (STRAT == KVQ_SHIFT_EQUIVALENT_) out[d] = shrink_16_to_8(in[d], in[16 + d]);
+                else out[d] = in[d];
+            } else if constexpr (STRAT == KVQ_SHIFT_EQUIVALENT_) {
                 if constexpr (B == 2) out[d] = shrink_4_to_2(in[2 * d]) | (shrink_4_to_2(in[2 * d + 1]) << 16);
                 else out[d] = shrink_8_to_4(in[2 * d]) | (shrink_8_to_4(in[2 * d + 1]) << 16);
             } else {
@@ -544,16 +646,22 @@ __global__ __launch_bounds__(64) void kvq_error_kernel(const uint8_t* __restrict
         if (tok0 + t >= n_tokens) continue;
         const uint32_t bit = (uint32_t)slot * (uint32_t)B;
         const uint8_t* at = code + kvq_tile_byte(lane, bit >> 3);
-        float xh;
-        if (B == 16) {
-            xh = h2f(*reinterpret_cast<const uint16_t*>(at));
+        // x_hat - x = code * S + (Z - x): the difference of two fp16 numbers is exact in fp32 and the fused
+        // multiply-add rounds once, so large codes times large scales lose nothing before the subtraction
+        const uint64_t at_ref = (uint64_t)(tok0 + t) * KVQ_D + d;
+        const float x = h2f(ref[at_ref]);
+        const int mi = which ? 256 + kvq_vmeta_index(t, g) : t * 4 + g;
+        float dx;
+        if (B == 16 && pd.int16) {  // byte planes: slot s of the lane's high-byte string, then of its low-byte string
+            const uint32_t c = ((uint32_t)code[kvq_tile_byte(lane, (uint32_t)slot)] << 8) |
+                               (uint32_t)code[512u * 8 + kvq_tile_byte(lane, (uint32_t)slot)];
+            dx = fmaf((float)c, h2f(meta[mi]), h2f(meta[mi + 128]) - x);
+        } else if (B == 16) {
+            dx = h2f(*reinterpret_cast<const uint16_t*>(at)) - x;
         } else {
             const uint32_t c = ((uint32_t)*at >> (bit & 7u)) & ((1u << B) - 1u);
-            const int mi = which ? 256 + kvq_vmeta_index(t, g) : t * 4 + g;
-            xh = (float)c * h2f(meta[mi]) + h2f(meta[mi + 128]);
+            dx = fmaf((float)c, h2f(meta[mi]), h2f(meta[mi + 128]) - x);
         }
-        const uint64_t at_ref = (uint64_t)(tok0 + t) * KVQ_D + d;
-        const float dx = xh - h2f(ref[at_ref]);
         if (L1) acc += fabsf(grad ? grad[unit_base + at_ref] * dx : dx);
         else acc += dx * dx;
     }
@@ -613,7 +721,7 @@ __global__ void kvq_fill_u32_kernel(uint32_t* dst, uint32_t value, size_t n) {
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
                              const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group,
-                             const float* rinv, int n_kv_heads, const float* rope, hipStream_t s) {
+                             const float* rinv, int n_kv_heads, const float* rope, bool int16, hipStream_t s) {
     const int gspan = group / KVQ_G;
     int tile0 = t_old / KVQ_TILE_TOKENS;
     int tile1 = (t_old + n_new + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
@@ -624,7 +732,8 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
     ap.first_page = first_two ? first_page : -1;
     ap.d[0] = first_two ? first_two[0] : KvqPageDesc{0, 0, 0, 0};
     ap.d[1] = first_two ? first_two[1] : KvqPageDesc{0, 0, 0, 0};
-    switch (bits) {
+    switch (bits + (int16 && bits == 16 ? 1 : 0)) {
+        case 17: hipLaunchKernelGGL(kvq_append_i16_kernel, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, gspan, rinv, n_kv_heads, rope); break;
         case 16: hipLaunchKernelGGL(kvq_append16_kernel, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, rinv, n_kv_heads, rope); break;
         case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
         case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
@@ -651,6 +760,9 @@ hipError_t kvq_launch_shrink(int dst_bits, int strategy, uint8_t* arena, const K
 #define KVQ_SHRINK_CASE(B_, S_) \
     hipLaunchKernelGGL((kvq_shrink_kernel<B_, S_>), grid, block, 0, s, arena, jobs_dev, tiles_per_page, flags, ja)
     switch (dst_bits * 4 + strategy) {
+        case 8 * 4 + 0: KVQ_SHRINK_CASE(8, 0); break;
+        case 8 * 4 + 1: KVQ_SHRINK_CASE(8, 1); break;
+        case 8 * 4 + 2: KVQ_SHRINK_CASE(8, 2); break;
         case 4 * 4 + 0: KVQ_SHRINK_CASE(4, 0); break;
         case 4 * 4 + 1: KVQ_SHRINK_CASE(4, 1); break;
         case 4 * 4 + 2: KVQ_SHRINK_CASE(4, 2); break;

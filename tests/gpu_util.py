@@ -14,11 +14,12 @@ def dev(x: np.ndarray) -> torch.Tensor:
 
 
 def make_pair(n_layers, B, Hq, Hkv, max_tokens, P, budgets=None, fbits=None, window=0, n_sink=0, policy=0,
-              meta=1, payload_bytes=None, group=32, shift_strategy=0):
+              meta=1, payload_bytes=None, group=32, shift_strategy=0, tier16=0):
     budgets = budgets or [1 << 50] * n_layers
     fbits = fbits or [2] * n_layers
     ocfg = CacheConfig(n_layers, B, Hq, Hkv, page_tokens=P, max_tokens=max_tokens, window=window, n_sink=n_sink,
-                       policy=policy, count_metadata_in_budget=meta, group=group, shift_strategy=shift_strategy)
+                       policy=policy, count_metadata_in_budget=meta, group=group, shift_strategy=shift_strategy,
+                       tier16=tier16)
     oc = OracleCache(ocfg, budgets, fbits)
     cfg = kq.KvqConfig(n_layers, B, Hq, Hkv, max_tokens, page_tokens=P, window=window, n_sink=n_sink, policy=policy,
                        count_metadata_in_budget=meta, group=group)
@@ -29,6 +30,8 @@ def make_pair(n_layers, B, Hq, Hkv, max_tokens, P, budgets=None, fbits=None, win
     gc = kq.KvqCache(cfg, budgets, fbits, arena=arena)
     if shift_strategy:
         gc.kvq_cache_set_option(kq.KVQ_OPT_SHIFT_STRATEGY, shift_strategy)
+    if tier16:
+        gc.kvq_cache_set_option(kq.KVQ_OPT_TIER16, tier16)
     return oc, gc
 
 
@@ -46,8 +49,8 @@ def assert_same_cache(oc, gc, layer):
         for which, name in ((kq.KVQ_WHICH_K, "K"), (kq.KVQ_WHICH_V, "V")):
             gcodes, gS, gZ = gc.kvq_cache_export_segment(layer, si, which)
             ocodes, oS, oZ = oc.export_segment(layer, si, name)
-            if segs[si][2] == 16:
-                assert np.array_equal(gcodes.view(np.uint16), ocodes.view(np.uint16)), (si, name)
+            if oS is None:
+                assert gS is None and np.array_equal(gcodes.view(np.uint16), ocodes.view(np.uint16)), (si, name)
             else:
                 assert np.array_equal(gcodes, ocodes), (si, name, segs[si])
                 assert np.array_equal(gS.view(np.uint16), oS.view(np.uint16)), (si, name, "scales")

@@ -1,0 +1,155 @@
+"""GPU parity of the integer 16-bit tier (KVQ_TIER16_INT16) against the oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import kvq_synth
+import paper_2505_18610_amd as kq
+from oracle import BudgetError, POLICY_PAPER, POLICY_OLDEST_FIRST, TIER16_INT16, bytes_per_token_head
+from gpu_util import dev, make_pair, append_both, assert_same_cache, check_attention, attention_errors, MAX_ABS, REL_L2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("group", [32, 128])
+def test_int16_append_bit_exact_ragged_chunks_and_token_by_token(group):
+    """16-bit codes, scales and zero points of ragged appends (inside tiles, across tiles and pages) equal the
+    oracle's; appending token by token gives the same cache as one shot."""
+    B, H, T, P = 2, 2, 427, 128
+    K, V = kvq_synth.make_kv(301, 0, B, H, 0, T)
+    K[0, 0, 5, :32] = np.float16(0.25)            # a constant group: S = 0, codes 0
+    K[1, 1, 40:44] *= np.float16(300.0)           # large ranges (S around 1)
+    oc, gc = make_pair(1, B, 2 * H, H, 1024, P, group=group, tier16=TIER16_INT16)
+    t = 0
+    for n in (1, 31, 32, 100, 7, 129, 64, 63):
+        append_both(oc, gc, 0, K[:, :, t:t + n], V[:, :, t:t + n])
+        t += n
+    assert t == T and gc.kvq_cache_describe(0)[0] == [(0, T, 16)]
+    assert_same_cache(oc, gc, 0)
+    assert gc.kvq_cache_describe(0)[1] == T * B * H * bytes_per_token_head(16, 128, group, True, True)
+    _, gc2 = make_pair(1, B, 2 * H, H, 1024, P, group=group, tier16=TIER16_INT16)
+    for t in range(150):
+        gc2.kvq_quantize_append(0, dev(K[:, :, t:t + 1]), dev(V[:, :, t:t + 1]))
+    a, b = gc2.kvq_cache_export_segment(0, 0, kq.KVQ_WHICH_K), gc.kvq_cache_export_segment(0, 0, kq.KVQ_WHICH_K)
+    for x, y in zip(a, b):
+        assert np.array_equal(x.view(np.uint16) if x.dtype == np.float16 else x,
+                              (y[:, :, :150]).view(np.uint16) if y.dtype == np.float16 else y[:, :, :150])
+
+
+@pytest.mark.parametrize("strategy", [0, 1, 2])
+def test_int16_shrink_chain_bit_exact(strategy):
+    """16 -> 8 -> 4 -> 2 from the integer tier under the three shift strategies of Sec. 4.3.1: Eq. 3 at b = 8 needs
+    the unsigned 32-bit product; codes, S and Z after every step equal the oracle's, and so does the reported
+    reconstruction error."""
+    B, H, T, P = 2, 2, 448, 64
+    K, V = kvq_synth.make_kv(310 + strategy, 0, B, H, 0, T)
+    V[0, 1, 7, 32:64] = np.linspace(-60000, 60000, 32).astype(np.float16)   # codes near 65535 with a large scale
+    Kd, Vd = dev(K), dev(V)
+    oc, gc = make_pair(1, B, 3 * H, H, 512, P, shift_strategy=strategy, tier16=TIER16_INT16)
+    append_both(oc, gc, 0, K, V)
+    assert_same_cache(oc, gc, 0)
+    got, want = gc.kvq_cache_sq_error(0, Kd, Vd), oc.reconstruction_sq_error(0, K, V)
+    assert got[0] == pytest.approx(want[0], rel=1e-4) and got[1] == pytest.approx(want[1], rel=1e-4)
+    for want_bits in (8, 4, 2):
+        assert gc.kvq_progressive_requant(0, segment=0) == oc.requant(0, segment=0)
+        assert gc.kvq_cache_describe(0)[0] == [(0, T, want_bits)]
+        assert_same_cache(oc, gc, 0)
+        got, want = gc.kvq_cache_sq_error(0, Kd, Vd), oc.reconstruction_sq_error(0, K, V)
+        assert got[0] == pytest.approx(want[0], rel=1e-5) and got[1] == pytest.approx(want[1], rel=1e-5)
+
+
+@pytest.mark.parametrize("gqa,T", [(1, 33), (5, 700), (8, 257), (16, 96)])
+def test_int16_attention(gqa, T):
+    """Attention over a cache that is INT16 throughout, and against the exact attention over the fp16 tensors: the
+    integer tier stays within a few 1e-3 of it (the outlier channels' groups have scales whose fp16 rounding clamps
+    their largest values)."""
+    from oracle import decode_attention_fp64
+    B, H, P = 2, 2, 64
+    K, V = kvq_synth.make_kv(320 + gqa, 0, B, H, 0, T)
+    oc, gc = make_pair(1, B, gqa * H, H, 1024, P, tier16=TIER16_INT16)
+    append_both(oc, gc, 0, K, V)
+    q = kvq_synth.make_q(320 + gqa, 0, B, gqa * H, T - 1)
+    for splits in (0, 1, 3):
+        gc.kvq_cache_set_option(kq.KVQ_OPT_SPLITS, splits)
+        check_attention(oc, gc, 0, q)
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    gc.kvq_decode_attention(0, dev(q), out)
+    exact = decode_attention_fp64(q, K.astype(np.float64), V.astype(np.float64))
+    mx, rl = attention_errors(out.cpu().numpy(), exact)
+    fmt = float(np.abs(oc.attention(0, q) - exact).max())      # what the format itself costs (fp16 scales, clamp)
+    assert fmt <= 8e-3 and mx <= fmt + MAX_ABS and rl <= 2e-3, (mx, rl, fmt)
+    check_attention(oc, gc, 0, q, out_dtype=torch.float16)
+
+
+@pytest.mark.parametrize("policy,W,sink,fbit", [(POLICY_PAPER, 64, 32, 2), (POLICY_PAPER, 0, 0, 4),
+                                                (POLICY_OLDEST_FIRST, 32, 32, 2)])
+def test_int16_progressive_decode_run(policy, W, sink, fbit):
+    """A decode loop under a byte budget with an INT16 sink and window: pages leaving the window go down by chained
+    shift steps; state (bit-exact) and outputs match the oracle at every shrink event and at the end.  The fused
+    step entry point is used for the single-token appends (it falls back to two launches for this tier)."""
+    P, B, H, Tmax = 32, 1, 2, 640
+    per16 = bytes_per_token_head(16, 128, 32, True, True)
+    budget = B * H * (420 * bytes_per_token_head(fbit, 128, 32, True) + (W + sink + 2 * P) * per16)
+    oc, gc = make_pair(1, B, 2 * H, H, Tmax, P, budgets=[budget], fbits=[fbit], window=W, n_sink=sink, policy=policy,
+                       tier16=TIER16_INT16)
+    K, V = kvq_synth.make_kv(330, 0, B, H, 0, Tmax)
+    rng = np.random.default_rng(6)
+    out = torch.empty((B, 2 * H, 128), dtype=torch.float32, device="cuda")
+    t, events = 0, 0
+    while t < Tmax:
+        n = 1 if t % 3 == 0 else min(int(rng.integers(1, 24)), Tmax - t)
+        try:
+            oc.append(0, K[:, :, t:t + n], V[:, :, t:t + n])
+        except BudgetError:
+            with pytest.raises(kq.KvqError) as e:
+                gc.kvq_quantize_append(0, dev(K[:, :, t:t + n]), dev(V[:, :, t:t + n]))
+            assert e.value.status == kq.KVQ_E_BUDGET
+            try:
+                done = oc.requant(0, reserve_tokens=n)
+            except BudgetError:
+                with pytest.raises(kq.KvqError) as e:
+                    gc.kvq_progressive_requant(0, reserve_tokens=n)
+                assert e.value.status == kq.KVQ_E_BUDGET
+                break
+            assert gc.kvq_progressive_requant(0, reserve_tokens=n) == done
+            events += 1
+            assert_same_cache(oc, gc, 0)
+            check_attention(oc, gc, 0, kvq_synth.make_q(330, 0, B, 2 * H, t))
+            continue
+        if n == 1:
+            q = kvq_synth.make_q(330, 0, B, 2 * H, t)
+            gc.kvq_append_decode_attention(0, dev(K[:, :, t:t + 1]), dev(V[:, :, t:t + 1]), dev(q), out)
+            if t % 48 == 0:
+                torch.cuda.synchronize()
+                mx, rl = attention_errors(out.cpu().numpy(), oc.attention(0, q))
+                assert mx <= MAX_ABS and rl <= REL_L2, (t, mx, rl)
+        else:
+            gc.kvq_quantize_append(0, dev(K[:, :, t:t + n]), dev(V[:, :, t:t + n]))
+        t += n
+    assert events >= 2
+    assert_same_cache(oc, gc, 0)
+    widths = {b for _, _, b in gc.kvq_cache_describe(0)[0]}
+    assert 16 in widths or W + sink == 0
+    check_attention(oc, gc, 0, kvq_synth.make_q(330, 0, B, 2 * H, t))
+
+
+def test_int16_with_rope_and_reparameterization():
+    """Un-rotated keys with the rotation (Eq. 9) and K Lambda^-1 (Eq. 7) applied inside the quantizing append of the
+    integer tier."""
+    from oracle import rope_rotate_keys, calibrate_lambda
+    B, H, T, P = 2, 2, 200, 64
+    K, V = kvq_synth.make_kv(340, 0, B, H, 0, T, rope_base=None)
+    cos, sin = kvq_synth.rope_tables(np.arange(T), 1.0e6)
+    Krot = rope_rotate_keys(K, cos, sin)
+    lam = calibrate_lambda(Krot[:, :, :64], 0.5)
+    oc, gc = make_pair(1, B, 2 * H, H, 256, P, tier16=TIER16_INT16)
+    oc.set_reparam(0, lam)
+    gc.kvq_cache_set_reparam(0, dev(lam))
+    cs = dev(np.concatenate([cos, sin], 1))
+    t = 0
+    for n in (70, 1, 1, 128):
+        oc.append(0, Krot[:, :, t:t + n], V[:, :, t:t + n])
+        gc.kvq_quantize_append_rope(0, dev(K[:, :, t:t + n]), dev(V[:, :, t:t + n]), cos_sin=cs[t:t + n].contiguous())
+        t += n
+    assert_same_cache(oc, gc, 0)
+    check_attention(oc, gc, 0, kvq_synth.make_q(340, 0, B, 2 * H, T - 1))

@@ -10,7 +10,7 @@ import pytest
 import kvq_synth
 import paper_2505_18610_amd as kq
 from oracle import (OracleCache, CacheConfig, BudgetError, StateError, POLICY_PAPER, POLICY_OLDEST_FIRST,
-                    bytes_per_token_head)
+                    bytes_per_token_head, TIER16_INT16)
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 pytestmark = pytest.mark.skipif(not os.path.exists(kq.library_path()), reason="libkvq.so not built")
@@ -30,6 +30,8 @@ def test_bytes_per_token_head_matches_oracle_and_paper_shapes():
         for G in (32, 64, 128):
             for m in (0, 1):
                 assert kq.kvq_bytes_per_token_head(b, 128, G, m) == bytes_per_token_head(b, 128, G, bool(m))
+                assert kq.kvq_bytes_per_token_head(b, 128, G, m, 1) == bytes_per_token_head(b, 128, G, bool(m), True)
+    assert kq.kvq_bytes_per_token_head(16, 128, 32, 1, 1) == 544
     assert kq.kvq_bytes_per_token_head(3) == 0
 
 
@@ -64,13 +66,15 @@ def test_invalid_configs_and_arguments():
     assert kq.kvq_status_string(kq.KVQ_E_OOM) != kq.kvq_status_string(kq.KVQ_OK)
 
 
-def _pair(policy, P, W, sink, budget, fbit, meta=1, Tmax=4096, B=2, H=2, group=32):
+def _pair(policy, P, W, sink, budget, fbit, meta=1, Tmax=4096, B=2, H=2, group=32, tier16=0):
     ocfg = CacheConfig(1, B, 2 * H, H, page_tokens=P, max_tokens=Tmax, window=W, n_sink=sink, policy=policy,
-                       count_metadata_in_budget=meta, group=group)
+                       count_metadata_in_budget=meta, group=group, tier16=tier16)
     oc = OracleCache(ocfg, [budget], [fbit])
     cfg = kq.KvqConfig(1, B, 2 * H, H, Tmax, page_tokens=P, window=W, n_sink=sink, policy=policy,
                        count_metadata_in_budget=meta, group=group)
     gc = kq.KvqCache(cfg, [budget], [fbit], arena=None, arena_bytes=1 << 30)
+    if tier16:
+        gc.kvq_cache_set_option(kq.KVQ_OPT_TIER16, tier16)
     return oc, gc
 
 
@@ -82,14 +86,18 @@ def _same_state(oc, gc):
     assert cur == oc.current_bits(0)
 
 
-@pytest.mark.parametrize("policy,W,sink,fbit", [(POLICY_PAPER, 0, 0, 2), (POLICY_PAPER, 64, 32, 2),
-                                                (POLICY_PAPER, 64, 0, 4), (POLICY_OLDEST_FIRST, 32, 0, 2),
-                                                (POLICY_OLDEST_FIRST, 0, 32, 4)])
-def test_bookkeeping_matches_oracle_on_random_decode_runs(policy, W, sink, fbit):
+@pytest.mark.parametrize("policy,W,sink,fbit,tier16", [(POLICY_PAPER, 0, 0, 2, 0), (POLICY_PAPER, 64, 32, 2, 0),
+                                                       (POLICY_PAPER, 64, 0, 4, 0), (POLICY_OLDEST_FIRST, 32, 0, 2, 0),
+                                                       (POLICY_OLDEST_FIRST, 0, 32, 4, 0),
+                                                       (POLICY_PAPER, 64, 32, 2, TIER16_INT16),
+                                                       (POLICY_PAPER, 0, 0, 4, TIER16_INT16),
+                                                       (POLICY_OLDEST_FIRST, 32, 32, 2, TIER16_INT16)])
+def test_bookkeeping_matches_oracle_on_random_decode_runs(policy, W, sink, fbit, tier16):
     P, B, H = 32, 2, 2
     rng = np.random.default_rng(hash((policy, W, sink, fbit)) % 2 ** 32)
-    budget = B * H * (500 * bytes_per_token_head(fbit, 128, 32, True) + (W + sink + 2 * P) * 512)
-    oc, gc = _pair(policy, P, W, sink, budget, fbit, Tmax=1024, B=B, H=H)
+    per16 = bytes_per_token_head(16, 128, 32, True, bool(tier16))
+    budget = B * H * (500 * bytes_per_token_head(fbit, 128, 32, True) + (W + sink + 2 * P) * per16)
+    oc, gc = _pair(policy, P, W, sink, budget, fbit, Tmax=1024, B=B, H=H, tier16=tier16)
     K, V = kvq_synth.make_kv(77, 0, B, H, 0, 1024, rope_base=None)
     t = 0
     exhausted = False
@@ -229,3 +237,21 @@ def test_allocate_bits_matches_the_oracle_enumeration():
     for bad in (dict(s=[[float("nan")]], mem=[[1]]), dict(s=[[-1.0]], mem=[[1]])):
         with pytest.raises(kq.KvqError):
             kq.kvq_allocate_bits(bad["s"], bad["mem"], 10)
+
+
+def test_tier16_option_only_on_empty_caches():
+    cfg = kq.KvqConfig(2, 1, 2, 1, 1024, page_tokens=32)
+    c = kq.KvqCache(cfg, [1 << 30] * 2, [2, 2], arena=None, arena_bytes=1 << 26)
+    with pytest.raises(kq.KvqError) as e:
+        c.kvq_cache_set_option(kq.KVQ_OPT_TIER16, 2)
+    assert e.value.status == kq.KVQ_E_INVALID
+    c.kvq_cache_set_option(kq.KVQ_OPT_TIER16, kq.KVQ_TIER16_INT16)
+    c.kvq_quantize_append(1, None, None, n_new=40)
+    assert c.kvq_cache_describe(1)[1] == 40 * 544
+    with pytest.raises(kq.KvqError) as e:
+        c.kvq_cache_set_option(kq.KVQ_OPT_TIER16, kq.KVQ_TIER16_FP16)
+    assert e.value.status == kq.KVQ_E_STATE
+    # 16 -> 8 of the whole run by segment, then the arena accounting: one 8-bit code block and one metadata block per page
+    free0 = c.kvq_cache_arena_free_bytes()
+    assert c.kvq_progressive_requant(1, segment=0) == 2 and c.kvq_cache_describe(1)[0] == [(0, 40, 8)]
+    assert c.kvq_cache_arena_free_bytes() - free0 == 2 * 32 * 32 * 8      # each page gave back half of its code block
