@@ -126,6 +126,88 @@ def measure_requant(kq, torch):
     return out
 
 
+def int16_tier(kq, torch, kvq_synth):
+    """The integer 16-bit tier (INT16 format of Sec. 4.1.2) beside the raw fp16 tier.
+    requant_16to8: Eq. 3 at b = 8 on 14B-shaped blocks of 16,384 tokens (64 units), six blocks behind one event pair as
+    in measure_requant; algorithmic bytes per element: 2 read + 1 written + 0.125 of scales re-written (group 32).
+    bulk_append: Eq. 1-2 with 65,535 levels, 2 read + 2 written + 0.125 metadata per element.
+    attention: trains of launches over 8 blocks of a 7B-shaped block (32,256 4-bit tokens + a 512-token 16-bit window,
+    64 units), window raw fp16 against window INT16; and the error of the two outputs against each other."""
+    B, Hkv, T, P, L = 8, 8, 16384, 256, 6
+    units = B * Hkv
+    cfg = kq.KvqConfig(L, B, 40, Hkv, T, page_tokens=P)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, int(L * T * units * 544 * 1.7)), dtype=torch.uint8, device="cuda")
+    cache = kq.KvqCache(cfg, [1 << 60] * L, [2] * L, arena=arena)
+    cache.kvq_cache_set_option(kq.KVQ_OPT_TIER16, kq.KVQ_TIER16_INT16)
+    g = torch.Generator(device="cuda").manual_seed(16)
+    k = torch.randn((B, Hkv, T, 128), device="cuda", generator=g).half()
+    v = torch.randn((B, Hkv, T, 128), device="cuda", generator=g).half()
+    filler = QueueFiller(torch, cache)
+    elems = T * units * 256
+    out = {}
+    cache.kvq_quantize_append(0, k, v)                      # first launch of the kernel stays out of the timing
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    filler()
+    e0.record()
+    for layer in range(1, L):
+        cache.kvq_quantize_append(layer, k, v)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / (L - 1)
+    out["bulk_append"] = {"ms": round(ms, 4), "GBps": round(elems * 4.125 / ms / 1e6, 1)}
+    del k, v
+    cache.kvq_progressive_requant(0, segment=0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    filler()
+    e0.record()
+    for layer in range(1, L):
+        cache.kvq_progressive_requant(layer, segment=0)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / (L - 1)
+    gbps = elems * 3.125 / ms / 1e6
+    out["requant_16to8"] = {"ms": round(ms, 4), "GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+    cache.close()
+    del arena, filler
+
+    B, Hkv, Hq, Tb, W, P, L = 16, 4, 28, 32256, 512, 256, 8
+    units = B * Hkv
+    K, V = kvq_synth.make_kv(7, 0, B, Hkv, 0, Tb + W)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    q = torch.from_numpy(kvq_synth.make_q(7, 0, B, Hq, Tb + W - 1)).cuda()
+    cfg = kq.KvqConfig(L, B, Hq, Hkv, Tb + W, page_tokens=P, policy=kq.KVQ_POLICY_OLDEST_FIRST)
+    res = {}
+    for name, tier in (("fp16_window", kq.KVQ_TIER16_FP16), ("int16_window", kq.KVQ_TIER16_INT16)):
+        arena = torch.empty(kq.kvq_arena_bytes(cfg, int(L * units * (Tb * 160 + W * 544) * 1.1) + (64 << 20)),
+                            dtype=torch.uint8, device="cuda")
+        cache = kq.KvqCache(cfg, [1 << 60] * L, [2] * L, arena=arena)
+        cache.kvq_cache_set_option(kq.KVQ_OPT_TIER16, tier)
+        for layer in range(L):
+            cache.kvq_quantize_append(layer, Kd[:, :, :Tb].contiguous(), Vd[:, :, :Tb].contiguous(), 4)
+            cache.kvq_quantize_append(layer, Kd[:, :, Tb:].contiguous(), Vd[:, :, Tb:].contiguous(), 16)
+        o = torch.empty((B, Hq, 128), dtype=torch.float32, device="cuda")
+        trains = []
+        for rep in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for layer in range(L):
+                cache.kvq_decode_attention(layer, q, o)
+            e1.record()
+            trains.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = float(np.mean([a.elapsed_time(b) for a, b in trains[1:]])) / L
+        nbytes = cache.kvq_cache_describe(0)[1]
+        res[name] = {"us_per_launch": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1), "out": o.clone()}
+        cache.close()
+        del arena
+    a, b = res["fp16_window"].pop("out"), res["int16_window"].pop("out")
+    res["rel_l2_between_outputs"] = float(f"{(torch.linalg.norm(a - b) / torch.linalg.norm(a)).item():.3e}")
+    out["attention_7b_block"] = res
+    return out
+
+
 def compare_shift_strategies(kq, torch, kvq_synth):
     """Sec. 4.3.1 without a model: mean squared reconstruction error of K and V after the 16 -> 8 -> 4 -> 2 chain under
     the three bit-width shrinking strategies, on a 14B-shaped slice of the synthetic recipe (8 KV heads, 2 sequences,
@@ -405,6 +487,7 @@ def main():
         result["shift_strategies_mse"] = compare_shift_strategies(kq, torch, kvq_synth)
         result["reparam_effect"] = reparam_effect(kq, torch, kvq_synth)
         result["allocation"] = allocation_demo(kq, torch, kvq_synth)
+        result["int16_tier"] = int16_tier(kq, torch, kvq_synth)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, KV, q_np)
     result["setup_seconds"] = {"generate_inputs": round(gen_s, 1)}
