@@ -34,10 +34,10 @@ from .quantizer import (quantize, dequantize, pack_codes, unpack_codes, shrink_c
 from .attention import decode_attention_fp64
 from .allocation import sensitivity, allocate_bits_bruteforce, allocate_bits_dp
 from .cache import (OracleCache, CacheConfig, BudgetError, StateError, POLICY_PAPER, POLICY_OLDEST_FIRST,
-                    TIER16_FP16, TIER16_INT16)
+                    TIER16_FP16, TIER16_INT16, decode_step_batch)
 
 __all__ = ["quantize", "dequantize", "pack_codes", "unpack_codes", "shrink_codes", "shrink_scale", "shrink_step",
            "SHIFT_EQUIVALENT", "SHIFT_DIRECT", "SHIFT_MODIFIED", "calibrate_lambda", "reparam_keys",
            "reparam_queries", "LAMBDA_FLOOR", "sensitivity", "allocate_bits_bruteforce", "allocate_bits_dp", "rope_rotate_keys",
            "bytes_per_token_head", "LEVELS", "decode_attention_fp64", "OracleCache", "CacheConfig",
-           "BudgetError", "StateError", "POLICY_PAPER", "POLICY_OLDEST_FIRST", "TIER16_FP16", "TIER16_INT16"]
+           "BudgetError", "StateError", "POLICY_PAPER", "POLICY_OLDEST_FIRST", "TIER16_FP16", "TIER16_INT16", "decode_step_batch"]

@@ -131,29 +131,17 @@ class OracleCache:
             return 16
         return self.current_bits(layer)
 
-    def append(self, layer, k, v, entry_bits=0):
-        """Append n_new tokens (k, v fp16 [B, Hkv, n_new, D], keys already rotated).
-
-        entry_bits 0 = the policy's entry width; 16/8/4/2 = store at that width (state
-        construction).  Raises BudgetError, leaving the cache unchanged, if the block's
-        bytes after the append (and after the window evictions it causes) exceed the budget.
-        """
+    def _plan_append(self, layer, n_new, entry_bits):
+        """Bookkeeping of an append of n_new tokens, without touching the cache: (entry width, pages evicted from
+        the window, width they go to).  Raises StateError / BudgetError exactly where append would."""
         c, L, P = self.cfg, self.layers[layer], self.cfg.page_tokens
-        n_new = k.shape[2]
-        assert k.dtype == np.float16 and v.dtype == np.float16 and k.shape == v.shape
-        assert k.shape == (c.batch, c.n_kv_heads, n_new, c.head_dim)
         assert entry_bits in (0, 2, 4, 8, 16)
-        if n_new == 0:
-            return
         if L.T + n_new > c.max_tokens:
             raise StateError("max_tokens exceeded")
-        if self.lam[layer] is not None:
-            k = reparam_keys(k, self.lam[layer])
         e = self._entry_bits(layer, entry_bits)
         if L.T % P != 0 and L.pages[-1].bits != e:
             raise StateError("width change inside a page")
         evict = (entry_bits == 0 and c.policy == POLICY_PAPER and c.window > 0)
-        # simulate the bookkeeping first
         bits = [p.bits for p in L.pages]
         cnt = [p.n for p in L.pages]
         T = L.T
@@ -163,7 +151,7 @@ class OracleCache:
                 bits.append(e); cnt.append(0)
             take = min(left, P - cnt[-1])
             cnt[-1] += take; T += take; left -= take
-        evicted = []
+        evicted, bcur = [], 16
         if evict:
             bcur = min([b for i, b in enumerate(bits) if i >= c.n_sink // P] or [16])
             if bcur < 16:
@@ -176,7 +164,25 @@ class OracleCache:
         used = sum(n * c.batch * c.n_kv_heads * self._bpth(b) for n, b in zip(cnt, bits))
         if used > L.budget:
             raise BudgetError("append exceeds block budget")
-        # commit: store the tokens
+        return e, evicted, bcur
+
+    def append(self, layer, k, v, entry_bits=0):
+        """Append n_new tokens (k, v fp16 [B, Hkv, n_new, D], keys already rotated).
+
+        entry_bits 0 = the policy's entry width; 16/8/4/2 = store at that width (state
+        construction).  Raises BudgetError, leaving the cache unchanged, if the block's
+        bytes after the append (and after the window evictions it causes) exceed the budget.
+        """
+        c, L, P = self.cfg, self.layers[layer], self.cfg.page_tokens
+        n_new = k.shape[2]
+        assert k.dtype == np.float16 and v.dtype == np.float16 and k.shape == v.shape
+        assert k.shape == (c.batch, c.n_kv_heads, n_new, c.head_dim)
+        if n_new == 0:
+            assert entry_bits in (0, 2, 4, 8, 16)
+            return
+        e, evicted, bcur = self._plan_append(layer, n_new, entry_bits)
+        if self.lam[layer] is not None:
+            k = reparam_keys(k, self.lam[layer])
         off = 0
         while off < n_new:
             if L.T % P == 0:
@@ -317,3 +323,16 @@ class OracleCache:
         S = np.concatenate([getattr(p, pre + "s") for p in pages], 2)
         Z = np.concatenate([getattr(p, pre + "z") for p in pages], 2)
         return pack_codes(codes, b), S, Z
+
+
+def decode_step_batch(caches, layer, ks, vs, qs, scale=None):
+    """One decode step of block `layer` for a ragged batch: sequence (group) i has its own cache caches[i] -- its own
+    length, widths and budget -- receives one new token ks[i], vs[i] (fp16 [B_i, Hkv, 1, D]) and attends with qs[i]
+    (fp16 [B_i, Hq, D]) over its own cache only.  All or nothing: if any cache cannot take its token (BudgetError,
+    StateError) the error is raised before any cache has changed.  Returns the list of fp64 outputs [B_i, Hq, D]."""
+    assert len(caches) == len(ks) == len(vs) == len(qs)
+    for c in caches:
+        c._plan_append(layer, 1, 0)
+    for c, k, v in zip(caches, ks, vs):
+        c.append(layer, k, v)
+    return [c.attention(layer, q, scale) for c, q in zip(caches, qs)]
