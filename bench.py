@@ -208,6 +208,72 @@ def int16_tier(kq, torch, kvq_synth):
     return out
 
 
+def ragged_batch(kq, torch, kvq_synth):
+    """Sixteen 7B-shaped sequences (28 q / 4 KV heads) of different lengths, 2,048 ... 32,768 tokens (4-bit bulk + a
+    512-token raw window), every sequence in a cache of its own, 8 blocks each: decode attention of one block of all
+    sequences as sixteen single-cache launches against one kvq_decode_attention_batch launch, and the whole decode
+    step (one new token per sequence + attention) the same two ways; trains over the 8 blocks, HIP events."""
+    Hq, Hkv, P, L, W = 28, 4, 256, 8, 512
+    lengths = [2048 * (i + 1) for i in range(16)]
+    Tmax = max(lengths)
+    K, V = kvq_synth.make_kv(7, 0, 1, Hkv, 0, Tmax + 64)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    caches, arenas = [], []
+    for T in lengths:
+        cfg = kq.KvqConfig(L, 1, Hq, Hkv, T + 64, page_tokens=P, policy=kq.KVQ_POLICY_OLDEST_FIRST)
+        arena = torch.empty(kq.kvq_arena_bytes(cfg, int(L * Hkv * (T * 160 + (W + 2 * P) * 512) * 1.1) + (8 << 20)),
+                            dtype=torch.uint8, device="cuda")
+        c = kq.KvqCache(cfg, [1 << 60] * L, [2] * L, arena=arena)
+        for layer in range(L):
+            c.kvq_quantize_append(layer, Kd[:, :, :T - W].contiguous(), Vd[:, :, :T - W].contiguous(), 4)
+            c.kvq_quantize_append(layer, Kd[:, :, T - W:T].contiguous(), Vd[:, :, T - W:T].contiguous(), 16)
+        caches.append(c)
+        arenas.append(arena)
+    nbytes = sum(c.kvq_cache_describe(0)[1] for c in caches)
+    qs = [torch.from_numpy(kvq_synth.make_q(7, 0, 1, Hq, T)).cuda() for T in lengths]
+    outs = [torch.empty((1, Hq, 128), dtype=torch.float16, device="cuda") for _ in lengths]
+    ks = [Kd[:, :, T:T + 1].contiguous() for T in lengths]
+    vs = [Vd[:, :, T:T + 1].contiguous() for T in lengths]
+
+    def train(fn, reps=4):
+        times = []
+        for rep in range(reps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for layer in range(L):
+                fn(layer)
+            e1.record()
+            times.append((e0, e1))
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in times[1:]])) / L
+
+    def single(layer):
+        for c, q, o in zip(caches, qs, outs):
+            c.kvq_decode_attention(layer, q, o)
+
+    def batched(layer):
+        kq.kvq_decode_attention_batch(caches, layer, qs, outs)
+
+    def step_single(layer):
+        for c, k, v, q, o in zip(caches, ks, vs, qs, outs):
+            c.kvq_append_decode_attention(layer, k, v, q, o)
+
+    def step_batched(layer):
+        kq.kvq_append_decode_attention_batch(caches, layer, ks, vs, qs, outs)
+
+    res = {"sequences": len(lengths), "tokens_total": sum(lengths), "MB_per_block": round(nbytes / 1e6, 1)}
+    for name, fn in (("attention_16_launches", single), ("attention_1_launch", batched)):
+        ms = train(fn)
+        res[name] = {"us_per_block": round(ms * 1e3, 1), "GBps": round(nbytes / ms / 1e6, 1)}
+    # steps append tokens: 5 trains x 8 blocks add 5 tokens per block and sequence, far inside the 64 spare ones
+    for name, fn in (("step_16_launches", step_single), ("step_1_launch", step_batched)):
+        ms = train(fn)
+        res[name] = {"us_per_block": round(ms * 1e3, 1)}
+    for c in caches:
+        c.close()
+    return res
+
+
 def compare_shift_strategies(kq, torch, kvq_synth):
     """Sec. 4.3.1 without a model: mean squared reconstruction error of K and V after the 16 -> 8 -> 4 -> 2 chain under
     the three bit-width shrinking strategies, on a 14B-shaped slice of the synthetic recipe (8 KV heads, 2 sequences,
@@ -488,6 +554,7 @@ def main():
         result["reparam_effect"] = reparam_effect(kq, torch, kvq_synth)
         result["allocation"] = allocation_demo(kq, torch, kvq_synth)
         result["int16_tier"] = int16_tier(kq, torch, kvq_synth)
+        result["ragged_batch"] = ragged_batch(kq, torch, kvq_synth)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, KV, q_np)
     result["setup_seconds"] = {"generate_inputs": round(gen_s, 1)}

@@ -152,6 +152,31 @@ kvq_status_t kvq_append_decode_attention(kvq_cache_t* cache, int32_t layer, cons
                                          const float* cos_sin_dev, const void* q_dev, void* out_dev,
                                          int32_t out_is_fp32, float softmax_scale, void* hip_stream);
 
+/* Ragged batches: sequences of different lengths decode together when every sequence (or group of equally long
+ * sequences) has a cache of its own -- its own length, widths, budget and shrink history, as the method keeps them per
+ * sequence (Sec. 3.1) -- and one launch serves block `layer` of all of them.
+ *   caches[n_caches]: host array of distinct caches (1..64) that all use the same kind of 16-bit tier; they may differ
+ *   in batch, head counts, page size, length and state.  q_dev[i], out_dev[i], k_dev[i], v_dev[i], cos_sin_dev[i]: host
+ *   arrays of device pointers with the shapes the single-cache calls take for caches[i] (cos_sin_dev itself or any of
+ *   its entries may be NULL).
+ * kvq_decode_attention_batch: kvq_decode_attention of every cache in one launch.
+ * kvq_append_decode_attention_batch: kvq_append_decode_attention of every cache -- one new token each, then attention
+ *   -- in one attention launch (plus the small append and eviction launches of those caches whose token does not enter
+ *   the raw fp16 tier).  The bookkeeping of all appends is checked before the first one is carried out: on
+ *   KVQ_E_BUDGET / KVQ_E_STATE no cache has changed.  (An arena that runs out of pages, KVQ_E_OOM, is only found while
+ *   carrying them out; caches before the failing one then hold their new token.)
+ * The device's workgroups are shared among the caches in proportion to the time their tiles take.  Results per cache
+ * are those of the single-cache calls up to floating-point summation order.  The parameter blocks of the launch travel
+ * through the arena of caches[0]: calls that share that cache must be issued on one stream. */
+kvq_status_t kvq_decode_attention_batch(kvq_cache_t* const* caches, int32_t n_caches, int32_t layer,
+                                        const void* const* q_dev, void* const* out_dev, int32_t out_is_fp32,
+                                        float softmax_scale, void* hip_stream);
+kvq_status_t kvq_append_decode_attention_batch(kvq_cache_t* const* caches, int32_t n_caches, int32_t layer,
+                                               const void* const* k_dev, const void* const* v_dev,
+                                               const float* const* cos_sin_dev, const void* const* q_dev,
+                                               void* const* out_dev, int32_t out_is_fp32, float softmax_scale,
+                                               void* hip_stream);
+
 /* Bookkeeping read-out (host only): maximal runs of pages with equal width, oldest first.
  *   segs_host[cap] receives min(cap, *n) entries; n, bytes_used, n_tokens, current_bits may each be NULL.
  *   bytes_used = sum over tokens of batch * n_kv_heads * kvq_bytes_per_token_head(bits of that token). */

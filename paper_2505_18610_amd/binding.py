@@ -58,6 +58,11 @@ _SIGNATURES = {
     "kvq_decode_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]),
     "kvq_append_decode_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_int32, C.c_float, C.c_void_p]),
+    "kvq_decode_attention_batch": (C.c_int, [C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
+                                             C.POINTER(C.c_void_p), C.c_int32, C.c_float, C.c_void_p]),
+    "kvq_append_decode_attention_batch": (C.c_int, [C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
+                                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                                    C.POINTER(C.c_void_p), C.c_int32, C.c_float, C.c_void_p]),
     "kvq_cache_describe": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(_SegmentInfo), C.c_int32, C.POINTER(C.c_int32),
                                      C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "kvq_cache_export_segment": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
@@ -125,6 +130,39 @@ def kvq_calibrate_lambda(k_calib, alpha, lam_out, stream=None):
     st = load_library().kvq_calibrate_lambda(_ptr(k_calib), b, h, t, float(alpha), _ptr(lam_out), _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_calibrate_lambda")
+
+
+def _ptr_array(items):
+    """Host array of device pointers (None entries become NULL)."""
+    return (C.c_void_p * len(items))(*[_ptr(t) for t in items])
+
+
+def kvq_decode_attention_batch(caches, layer, qs, outs, softmax_scale=0.0, stream=None):
+    """Ragged batch: caches[i] (KvqCache) attends with qs[i] into outs[i]; all outs share one dtype."""
+    n = len(caches)
+    assert n == len(qs) == len(outs) and n > 0
+    out_is_fp32 = 1 if outs[0].dtype.itemsize == 4 else 0
+    assert all((o.dtype.itemsize == 4) == bool(out_is_fp32) for o in outs)
+    handles = (C.c_void_p * n)(*[c.handle for c in caches])
+    st = load_library().kvq_decode_attention_batch(handles, n, layer, _ptr_array(qs), _ptr_array(outs), out_is_fp32,
+                                                   float(softmax_scale), _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_decode_attention_batch")
+
+
+def kvq_append_decode_attention_batch(caches, layer, ks, vs, qs, outs, cos_sins=None, softmax_scale=0.0, stream=None):
+    """Ragged batch decode step: one new token (ks[i], vs[i]) into caches[i], then attention, in one attention launch."""
+    n = len(caches)
+    assert n == len(ks) == len(vs) == len(qs) == len(outs) and n > 0
+    out_is_fp32 = 1 if outs[0].dtype.itemsize == 4 else 0
+    assert all((o.dtype.itemsize == 4) == bool(out_is_fp32) for o in outs)
+    handles = (C.c_void_p * n)(*[c.handle for c in caches])
+    cs = _ptr_array(cos_sins) if cos_sins is not None else None
+    st = load_library().kvq_append_decode_attention_batch(handles, n, layer, _ptr_array(ks), _ptr_array(vs), cs,
+                                                          _ptr_array(qs), _ptr_array(outs), out_is_fp32,
+                                                          float(softmax_scale), _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_append_decode_attention_batch")
 
 
 def kvq_bytes_per_token_head(bits, head_dim=128, group=32, count_metadata=1, int16_tier=0) -> int:

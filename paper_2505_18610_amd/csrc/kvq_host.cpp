@@ -94,6 +94,7 @@ struct kvq_cache {
     uint64_t unit_bytes = 0;
     uint64_t table_off = 0, jobs_off = 0, part_o_off = 0, part_ml_off = 0, counters_off = 0, flags_off = 0, pages_off = 0;
     uint64_t reparam_off = 0;  // per block: lambda [n_kv_heads][128] fp32, then 1 / lambda
+    uint64_t batch_off = 0;    // parameter blocks of a ragged-batch attention launch led by this cache
     uint32_t* flags_dev() const { return reinterpret_cast<uint32_t*>(arena + flags_off); }
     Buddy buddy;
     std::vector<Layer> layers;
@@ -133,7 +134,7 @@ struct kvq_cache {
 namespace {
 
 struct Regions {
-    uint64_t table_off, jobs_off, part_o_off, part_ml_off, counters_off, flags_off, reparam_off, pages_off;
+    uint64_t table_off, jobs_off, part_o_off, part_ml_off, counters_off, flags_off, reparam_off, batch_off, pages_off;
 };
 uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
@@ -163,8 +164,7 @@ Regions layout_regions(const kvq_config_t* c) {
     r.counters_off = off;  off = align_up(off + units * sizeof(uint32_t), 256);
     r.flags_off = off;     off = align_up(off + 64, 256);
     r.reparam_off = off;   off = align_up(off + (uint64_t)c->n_layers * 2 * c->n_kv_heads * KVQ_D * sizeof(float), 256);
-    uint64_t unit_bytes = 32ull * c->page_tokens * units;
-    (void)unit_bytes;
+    r.batch_off = off;     off = align_up(off + (uint64_t)KVQ_MAX_BATCH_CACHES * sizeof(KvqAttnParams), 256);
     r.pages_off = align_up(off, 4096);
     return r;
 }
@@ -406,6 +406,7 @@ kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_bud
     c->table_off = r.table_off; c->jobs_off = r.jobs_off; c->part_o_off = r.part_o_off;
     c->part_ml_off = r.part_ml_off; c->counters_off = r.counters_off; c->flags_off = r.flags_off; c->pages_off = r.pages_off;
     c->reparam_off = r.reparam_off;
+    c->batch_off = r.batch_off;
     uint64_t super = c->unit_bytes << kMaxOrder;
     if (arena_bytes < c->pages_off + super) { delete c; return KVQ_E_OOM; }
     uint64_t n_super = (arena_bytes - c->pages_off) / super;
@@ -448,56 +449,70 @@ struct DeferredAppend {
     KvqPageDesc desc{};
 };
 
-// The append entry points.  defer != nullptr: a one-token append into the 16-bit tier is not launched but described
-// in *defer (bookkeeping, page allocation, table upload and window evictions happen as usual).
-kvq_status_t append_impl(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev, int32_t n_new,
-                         int32_t entry_bits, const float* cos_sin_dev, void* hip_stream, DeferredAppend* defer) {
-    if (!c || layer < 0 || layer >= c->cfg.n_layers || n_new < 0) return KVQ_E_INVALID;
-    if (entry_bits != 0 && !valid_bits(entry_bits)) return KVQ_E_INVALID;
-    if (n_new == 0) return KVQ_OK;
-    if (!c->dry && (!k_dev || !v_dev)) return KVQ_E_INVALID;
-    Layer& L = c->layers[(size_t)layer];
+// Bookkeeping of an append, worked out without touching the cache: entry width, page widths and fill counts
+// afterwards, the window pages the append evicts and the width they go to.
+struct AppendPlan {
+    int e = 16, T = 0, bcur = 16;
+    std::vector<int> bits, cnt, evicted;
+};
+
+kvq_status_t plan_append(const kvq_cache_t* c, int32_t layer, int32_t n_new, int32_t entry_bits, AppendPlan& pl) {
+    const Layer& L = c->layers[(size_t)layer];
     const kvq_config_t& cfg = c->cfg;
     const int P = cfg.page_tokens;
-    hipStream_t s = as_stream(hip_stream);
     if ((int64_t)L.T + n_new > cfg.max_tokens) return KVQ_E_STATE;
-
-    // entry width
     int e = entry_bits;
     if (e == 0) e = (cfg.policy == KVQ_POLICY_OLDEST_FIRST || cfg.window > 0) ? 16 : current_bits(c, L);
     if (L.T % P != 0 && L.pages.back().bits != e) return KVQ_E_STATE;
     const bool evict = entry_bits == 0 && cfg.policy == KVQ_POLICY_PAPER && cfg.window > 0;
-
-    // simulate the bookkeeping: page widths and fill counts after the append and the evictions it causes
-    std::vector<int> bits(L.pages.size()), cnt(L.pages.size());
-    for (size_t i = 0; i < L.pages.size(); ++i) { bits[i] = L.pages[i].bits; cnt[i] = L.pages[i].n; }
+    pl.e = e;
+    pl.bits.resize(L.pages.size());
+    pl.cnt.resize(L.pages.size());
+    for (size_t i = 0; i < L.pages.size(); ++i) { pl.bits[i] = L.pages[i].bits; pl.cnt[i] = L.pages[i].n; }
     int T = L.T, left = n_new;
     while (left) {
-        if (T % P == 0) { bits.push_back(e); cnt.push_back(0); }
-        int take = std::min(left, P - cnt.back());
-        cnt.back() += take; T += take; left -= take;
+        if (T % P == 0) { pl.bits.push_back(e); pl.cnt.push_back(0); }
+        int take = std::min(left, P - pl.cnt.back());
+        pl.cnt.back() += take; T += take; left -= take;
     }
-    std::vector<int> evicted;
-    int bcur = 16;
+    pl.T = T;
+    pl.evicted.clear();
+    pl.bcur = 16;
     if (evict) {
-        bcur = current_bits(c, bits);
-        if (bcur < 16) {
+        pl.bcur = current_bits(c, pl.bits);
+        if (pl.bcur < 16) {
             for (;;) {
-                int i = (int)bits.size(), first = cfg.n_sink / P;
-                while (i > first && bits[(size_t)i - 1] == 16) --i;  // start of the trailing 16-bit run
-                if (i < (int)bits.size() && T - i * P >= cfg.window + P) { bits[(size_t)i] = bcur; evicted.push_back(i); }
+                int i = (int)pl.bits.size(), first = cfg.n_sink / P;
+                while (i > first && pl.bits[(size_t)i - 1] == 16) --i;  // start of the trailing 16-bit run
+                if (i < (int)pl.bits.size() && T - i * P >= cfg.window + P) { pl.bits[(size_t)i] = pl.bcur; pl.evicted.push_back(i); }
                 else break;
             }
         }
     }
     uint64_t used = 0;
-    for (size_t i = 0; i < bits.size(); ++i) used += (uint64_t)cnt[i] * c->units * c->bpth(bits[i]);
+    for (size_t i = 0; i < pl.bits.size(); ++i) used += (uint64_t)pl.cnt[i] * c->units * c->bpth(pl.bits[i]);
     if (used > L.budget) return KVQ_E_BUDGET;
+    return KVQ_OK;
+}
 
+bool append_args_ok(const kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev, int32_t n_new,
+                    int32_t entry_bits) {
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || n_new < 0) return false;
+    if (entry_bits != 0 && !valid_bits(entry_bits)) return false;
+    if (n_new > 0 && !c->dry && (!k_dev || !v_dev)) return false;
+    return true;
+}
+
+// Carries a planned append out.  defer != nullptr: a one-token append into the raw fp16 tier is not launched but
+// described in *defer (page allocation, table upload and window evictions happen as usual).
+kvq_status_t commit_append(kvq_cache_t* c, int32_t layer, const AppendPlan& pl, const void* k_dev, const void* v_dev,
+                           int32_t n_new, const float* cos_sin_dev, hipStream_t s, DeferredAppend* defer) {
+    Layer& L = c->layers[(size_t)layer];
+    const int P = c->cfg.page_tokens, e = pl.e;
     // allocate the new pages
     const size_t old_pages = L.pages.size();
     std::vector<Page> fresh;
-    for (size_t i = old_pages; i < bits.size(); ++i) {
+    for (size_t i = old_pages; i < pl.bits.size(); ++i) {
         Page p;
         p.bits = e;
         bool ok = c->buddy.alloc(order_of_bits(e), &p.code_unit);
@@ -515,9 +530,9 @@ kvq_status_t append_impl(kvq_cache_t* c, int32_t layer, const void* k_dev, const
     }
     kvq_status_t st = ensure_device(c, s);
     if (st != KVQ_OK) return st;
-    const int t_old = L.T;
+    const int t_old = L.T, T = pl.T;
     for (Page& p : fresh) L.pages.push_back(p);
-    for (size_t i = 0; i < L.pages.size(); ++i) L.pages[i].n = cnt[i];
+    for (size_t i = 0; i < L.pages.size(); ++i) L.pages[i].n = pl.cnt[i];
     L.T = T;
     L.version++;
     st = upload_table(c, layer, (int)old_pages, (int)L.pages.size(), s);
@@ -541,13 +556,23 @@ kvq_status_t append_impl(kvq_cache_t* c, int32_t layer, const void* k_dev, const
                               cos_sin_dev, c->int16(), s) != hipSuccess)
             return KVQ_E_HIP;
     }
-    if (!evicted.empty()) {
+    if (!pl.evicted.empty()) {
         std::vector<Lowering> low;
-        for (int i : evicted) low.push_back(Lowering{i, 16, bcur});
+        for (int i : pl.evicted) low.push_back(Lowering{i, 16, pl.bcur});
         st = run_lowerings(c, layer, low, s);
         if (st != KVQ_OK) return st;
     }
     return KVQ_OK;
+}
+
+kvq_status_t append_impl(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev, int32_t n_new,
+                         int32_t entry_bits, const float* cos_sin_dev, void* hip_stream, DeferredAppend* defer) {
+    if (!append_args_ok(c, layer, k_dev, v_dev, n_new, entry_bits)) return KVQ_E_INVALID;
+    if (n_new == 0) return KVQ_OK;
+    AppendPlan pl;
+    kvq_status_t st = plan_append(c, layer, n_new, entry_bits, pl);
+    if (st != KVQ_OK) return st;
+    return commit_append(c, layer, pl, k_dev, v_dev, n_new, cos_sin_dev, as_stream(hip_stream), defer);
 }
 
 }  // namespace
@@ -621,35 +646,47 @@ kvq_status_t kvq_progressive_requant(kvq_cache_t* c, int32_t layer, int32_t segm
 
 namespace {
 
-kvq_status_t attention_impl(kvq_cache_t* c, int32_t layer, const void* q_dev, void* out_dev, int32_t out_is_fp32,
-                            float softmax_scale, void* hip_stream, const DeferredAppend* app, const void* k_new,
-                            const void* v_new, const float* cos_sin_dev) {
+// Relative time the attention kernel needs for the block's tiles, and how many of them are 2 bits wide.
+void tile_census(const kvq_cache_t* c, const Layer& L, int n_tiles, int* n2, int* n_all, uint64_t* cost) {
+    *n2 = *n_all = 0;
+    *cost = 0;
+    for (size_t i = 0; i < L.pages.size(); ++i) {
+        const int nt = std::min(c->tpp, n_tiles - (int)i * c->tpp);
+        if (nt <= 0) break;
+        *n_all += nt;
+        if (L.pages[i].bits == 2) *n2 += nt;
+        *cost += (uint64_t)nt * (uint64_t)c->tile_cost[cost_index(L.pages[i].bits)];
+    }
+}
+
+// Fills the parameter block of one attention launch over block `layer`.  wgs_share > 0: the number of workgroups this
+// cache may use (its share of a ragged batch); 0: the whole device.
+kvq_status_t fill_attn_params(kvq_cache_t* c, int32_t layer, const void* q_dev, void* out_dev, int32_t out_is_fp32,
+                              float softmax_scale, const DeferredAppend* app, const void* k_new, const void* v_new,
+                              const float* cos_sin_dev, int wgs_share, KvqAttnParams& p) {
     if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_dev || !out_dev) return KVQ_E_INVALID;
     if (c->dry) return KVQ_E_STATE;
     Layer& L = c->layers[(size_t)layer];
     if (L.T == 0) return KVQ_E_STATE;
-    hipStream_t s = as_stream(hip_stream);
     const int n_tiles = (L.T + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
     int n_splits = c->splits_override;
     if (n_splits <= 0) {
         // One workgroup per compute unit when a good part of the tiles is 2 bits wide (those are bound by vector
         // issue and want every unit).  A block of wider tiles is bound by HBM, and there three quarters of the
         // units stream measurably faster than all of them (4 to 7 % on 4-, 8- and 16-bit blocks).
-        int n2 = 0, n_all = 0;
-        for (size_t i = 0; i < L.pages.size(); ++i) {
-            const int nt = std::min(c->tpp, n_tiles - (int)i * c->tpp);
-            if (nt <= 0) break;
-            n_all += nt;
-            if (L.pages[i].bits == 2) n2 += nt;
+        int wgs = wgs_share;
+        if (wgs <= 0) {
+            int n2 = 0, n_all = 0;
+            uint64_t cost = 0;
+            tile_census(c, L, n_tiles, &n2, &n_all, &cost);
+            wgs = c->target_workgroups;
+            if (4 * n2 < n_all) wgs = std::max(c->units, wgs * 3 / 4);
         }
-        int wgs = c->target_workgroups;
-        if (4 * n2 < n_all) wgs = std::max(c->units, wgs * 3 / 4);
         n_splits = std::min(wgs / std::max(1, c->units), (n_tiles + 15) / 16);
     }
     n_splits = std::max(1, std::min(n_splits, std::min(KVQ_MAX_SPLITS, n_tiles)));
     plan_splits(c, L, n_tiles, n_splits);
 
-    KvqAttnParams p;
     p.arena = c->arena;
     p.table = c->table_dev(layer);
     p.q = q_dev;
@@ -675,6 +712,9 @@ kvq_status_t attention_impl(kvq_cache_t* c, int32_t layer, const void* q_dev, vo
     std::memcpy(p.split_begin, L.split_begin, sizeof(int32_t) * (size_t)(n_splits + 1));
     for (int i = n_splits + 1; i <= KVQ_MAX_SPLITS; ++i) p.split_begin[i] = n_tiles;
     p.app_t_old = -1;
+    p.app_desc = KvqPageDesc{0, 0, 0, 0};
+    p.app_k = p.app_v = nullptr;
+    p.app_rope = p.app_rinv = nullptr;
     if (app && app->active) {
         p.app_t_old = app->t_old;
         p.app_desc = app->desc;
@@ -683,7 +723,103 @@ kvq_status_t attention_impl(kvq_cache_t* c, int32_t layer, const void* q_dev, vo
         p.app_rope = cos_sin_dev;
         p.app_rinv = L.reparam ? c->lambda_dev(layer) + c->cfg.n_kv_heads * KVQ_D : nullptr;
     }
-    return kvq_launch_attention(p, c->units, s) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
+    return KVQ_OK;
+}
+
+kvq_status_t attention_impl(kvq_cache_t* c, int32_t layer, const void* q_dev, void* out_dev, int32_t out_is_fp32,
+                            float softmax_scale, void* hip_stream, const DeferredAppend* app, const void* k_new,
+                            const void* v_new, const float* cos_sin_dev) {
+    KvqAttnParams p;
+    kvq_status_t st = fill_attn_params(c, layer, q_dev, out_dev, out_is_fp32, softmax_scale, app, k_new, v_new,
+                                       cos_sin_dev, 0, p);
+    if (st != KVQ_OK) return st;
+    return kvq_launch_attention(p, c->units, as_stream(hip_stream)) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
+}
+
+// One attention launch over block `layer` of n caches, optionally with each cache's one-token append in front.
+kvq_status_t batch_impl(kvq_cache_t* const* caches, int32_t n, int32_t layer, const void* const* k_dev,
+                        const void* const* v_dev, const float* const* cos_sin_dev, const void* const* q_dev,
+                        void* const* out_dev, int32_t out_is_fp32, float softmax_scale, void* hip_stream, bool append) {
+    if (!caches || n < 1 || n > KVQ_MAX_BATCH_CACHES || !q_dev || !out_dev) return KVQ_E_INVALID;
+    if (append && (!k_dev || !v_dev)) return KVQ_E_INVALID;
+    for (int i = 0; i < n; ++i) {
+        kvq_cache_t* c = caches[i];
+        if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_dev[i] || !out_dev[i]) return KVQ_E_INVALID;
+        if (append && (!k_dev[i] || !v_dev[i])) return KVQ_E_INVALID;
+        if (c->dry) return KVQ_E_STATE;
+        if (c->int16() != caches[0]->int16()) return KVQ_E_INVALID;  // one kernel serves one kind of 16-bit tier
+        for (int k = 0; k < i; ++k)
+            if (caches[k] == c) return KVQ_E_INVALID;
+    }
+    hipStream_t s = as_stream(hip_stream);
+    std::vector<DeferredAppend> app((size_t)n);
+    if (append) {
+        // all or nothing as far as the bookkeeping can tell: plan every append before the first one is carried out
+        std::vector<AppendPlan> plans((size_t)n);
+        for (int i = 0; i < n; ++i) {
+            kvq_status_t st = plan_append(caches[i], layer, 1, 0, plans[(size_t)i]);
+            if (st != KVQ_OK) return st;
+        }
+        for (int i = 0; i < n; ++i) {
+            kvq_status_t st = commit_append(caches[i], layer, plans[(size_t)i], k_dev[i], v_dev[i], 1,
+                                            cos_sin_dev ? cos_sin_dev[i] : nullptr, s, &app[(size_t)i]);
+            if (st != KVQ_OK) return st;
+        }
+    }
+    // The device's workgroups are dealt to the caches so that the most loaded workgroup is as light as possible:
+    // every cache starts with one split per (sequence, KV head); the cache whose workgroups carry the most tile
+    // time gets one more split, as long as the workgroups last (and its splits keep 16 tiles or more).
+    std::vector<uint64_t> cost((size_t)n);  // tile time of one (sequence, KV head) of the cache
+    std::vector<int> splits((size_t)n, 1), max_splits((size_t)n);
+    int used = 0;
+    for (int i = 0; i < n; ++i) {
+        kvq_cache_t* c = caches[i];
+        const Layer& L = c->layers[(size_t)layer];
+        if (L.T == 0) return KVQ_E_STATE;
+        const int n_tiles = (L.T + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
+        int a = 0, b = 0;
+        tile_census(c, L, n_tiles, &a, &b, &cost[(size_t)i]);
+        max_splits[(size_t)i] = std::max(1, std::min(KVQ_MAX_SPLITS, (n_tiles + 15) / 16));
+        used += c->units;
+    }
+    // (every compute unit is used: with ranges of unequal length the heaviest workgroup decides the launch time,
+    //  which outweighs the few percent a block of equal ranges gains from leaving a quarter of the units idle)
+    const int wgs = caches[0]->target_workgroups;
+    for (;;) {
+        int pick = -1;
+        uint64_t worst = 0;
+        for (int i = 0; i < n; ++i) {
+            if (splits[(size_t)i] >= max_splits[(size_t)i] || used + caches[i]->units > wgs) continue;
+            const uint64_t per_wg = cost[(size_t)i] / (uint64_t)splits[(size_t)i];
+            if (per_wg > worst) { worst = per_wg; pick = i; }
+        }
+        if (pick < 0) break;
+        // stop once a heavier cache could still be split but no longer fits into the workgroups that are left:
+        // more splits elsewhere would not lighten the heaviest workgroup, only add merge work
+        bool blocked = false;
+        for (int i = 0; i < n; ++i)
+            if (i != pick && cost[(size_t)i] / (uint64_t)splits[(size_t)i] > worst &&
+                splits[(size_t)i] < max_splits[(size_t)i])
+                blocked = true;
+        if (blocked) break;
+        splits[(size_t)pick]++;
+        used += caches[pick]->units;
+    }
+    std::vector<KvqAttnParams> params((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        kvq_status_t st = fill_attn_params(caches[i], layer, q_dev[i], out_dev[i], out_is_fp32, softmax_scale,
+                                           &app[(size_t)i], append ? k_dev[i] : nullptr, append ? v_dev[i] : nullptr,
+                                           cos_sin_dev ? cos_sin_dev[i] : nullptr, splits[(size_t)i] * caches[i]->units,
+                                           params[(size_t)i]);
+        if (st != KVQ_OK) return st;
+    }
+    kvq_cache_t* lead = caches[0];
+    KvqAttnParams* params_dev = reinterpret_cast<KvqAttnParams*>(lead->arena + lead->batch_off);
+    kvq_status_t st = upload(lead, params_dev, params.data(), params.size() * sizeof(KvqAttnParams), s);
+    if (st != KVQ_OK) return st;
+    std::vector<int> units((size_t)n);
+    for (int i = 0; i < n; ++i) units[(size_t)i] = caches[i]->units;
+    return kvq_launch_attention_batch(params_dev, params.data(), units.data(), n, s) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
 }
 
 }  // namespace
@@ -705,6 +841,22 @@ kvq_status_t kvq_append_decode_attention(kvq_cache_t* c, int32_t layer, const vo
     kvq_status_t st = append_impl(c, layer, k_dev, v_dev, 1, 0, cos_sin_dev, hip_stream, &app);
     if (st != KVQ_OK) return st;
     return attention_impl(c, layer, q_dev, out_dev, out_is_fp32, softmax_scale, hip_stream, &app, k_dev, v_dev, cos_sin_dev);
+}
+
+kvq_status_t kvq_decode_attention_batch(kvq_cache_t* const* caches, int32_t n_caches, int32_t layer,
+                                        const void* const* q_dev, void* const* out_dev, int32_t out_is_fp32,
+                                        float softmax_scale, void* hip_stream) {
+    return batch_impl(caches, n_caches, layer, nullptr, nullptr, nullptr, q_dev, out_dev, out_is_fp32, softmax_scale,
+                      hip_stream, false);
+}
+
+kvq_status_t kvq_append_decode_attention_batch(kvq_cache_t* const* caches, int32_t n_caches, int32_t layer,
+                                               const void* const* k_dev, const void* const* v_dev,
+                                               const float* const* cos_sin_dev, const void* const* q_dev,
+                                               void* const* out_dev, int32_t out_is_fp32, float softmax_scale,
+                                               void* hip_stream) {
+    return batch_impl(caches, n_caches, layer, k_dev, v_dev, cos_sin_dev, q_dev, out_dev, out_is_fp32, softmax_scale,
+                      hip_stream, true);
 }
 
 kvq_status_t kvq_cache_describe(const kvq_cache_t* c, int32_t layer, kvq_segment_info_t* segs_host, int32_t cap,

@@ -74,7 +74,23 @@ hipError_t kvq_launch_error(bool l1, const uint8_t* arena, const KvqPageDesc* ta
 hipError_t kvq_launch_stream_read(const void* buf, size_t bytes, int n_workgroups, uint32_t* sink, hipStream_t s);
 hipError_t kvq_launch_fill_u32(uint32_t* dst, uint32_t value, size_t n, hipStream_t s);
 
+// A ragged batch: several caches (each with its own length, widths and tables) served by one attention launch.  The
+// parameter blocks sit in device memory; the map tells a workgroup which cache it works for.
+#define KVQ_MAX_BATCH_CACHES 64
+struct KvqBatchMap {
+    int32_t n;
+    int32_t wg_begin[KVQ_MAX_BATCH_CACHES + 1];  // first workgroup of every cache; [n] = grid size
+};
+
 // kvq_attention.hip
 hipError_t kvq_launch_attention(const KvqAttnParams& p, int units, hipStream_t s);
+hipError_t kvq_launch_merge(const KvqAttnParams& p, int units, hipStream_t s);
+// kvq_attention_batch.hip: the bare kernel launch kvq_launch_attention_batch wraps
+hipError_t kvq_launch_attention_batch_kernel(const KvqAttnParams* params_dev, const KvqBatchMap& map, bool int16,
+                                             hipStream_t s);
+// params_dev: the n parameter blocks in device memory (in stream order); params_host: the same blocks on the host;
+// units[i]: (sequence, KV head) units of cache i
+hipError_t kvq_launch_attention_batch(const KvqAttnParams* params_dev, const KvqAttnParams* params_host,
+                                      const int* units, int n, hipStream_t s);
 
 #endif

@@ -1,0 +1,128 @@
+"""GPU parity of the ragged-batch entry points: several caches of different lengths and states, one attention launch."""
+import numpy as np
+import pytest
+import torch
+
+import kvq_synth
+import paper_2505_18610_amd as kq
+from oracle import BudgetError, POLICY_PAPER, POLICY_OLDEST_FIRST, TIER16_INT16, bytes_per_token_head, decode_step_batch
+from gpu_util import dev, make_pair, append_both, assert_same_cache, attention_errors, MAX_ABS, REL_L2
+
+pytestmark = pytest.mark.gpu
+
+
+def _build(spec, Hq, Hkv, tier16=0):
+    """spec: (batch, page_tokens, seed, ((n_tokens, bits), ...), window)"""
+    B, P, seed, tiers, window = spec
+    T = sum(n for n, _ in tiers)
+    oc, gc = make_pair(1, B, Hq, Hkv, T + 300, P, window=window, policy=POLICY_OLDEST_FIRST, tier16=tier16)
+    K, V = kvq_synth.make_kv(seed, 0, B, Hkv, 0, T + 200)
+    t = 0
+    for n, b in tiers:
+        append_both(oc, gc, 0, K[:, :, t:t + n], V[:, :, t:t + n], b)
+        t += n
+    return oc, gc, K, V, T
+
+
+SPECS = [(1, 32, 401, ((1, 16),), 0),                                   # a sequence that has just started
+         (2, 64, 402, ((640, 2), (320, 4), (128, 8), (77, 16)), 0),     # long, all widths, ragged last tile
+         (1, 96, 403, ((288, 4), (50, 16)), 0),                          # pages of three tiles
+         (1, 32, 404, ((2048, 2), (31, 16)), 0),
+         (3, 32, 405, ((64, 8), (33, 16)), 0)]
+
+
+@pytest.mark.parametrize("det", [0, 1])
+def test_ragged_batch_attention_matches_oracle_and_single_calls(det):
+    Hq, Hkv = 10, 2
+    built = [_build(s, Hq, Hkv) for s in SPECS]
+    qs = [kvq_synth.make_q(s[2], 0, s[0], Hq, b[4] - 1) for s, b in zip(SPECS, built)]
+    for _, gc, *_ in built:
+        gc.kvq_cache_set_option(kq.KVQ_OPT_DETERMINISTIC, det)
+    outs = [torch.empty(q.shape, dtype=torch.float32, device="cuda") for q in qs]
+    kq.kvq_decode_attention_batch([b[1] for b in built], 0, [dev(q) for q in qs], outs)
+    torch.cuda.synchronize()
+    for (oc, gc, *_), q, o in zip(built, qs, outs):
+        mx, rl = attention_errors(o.cpu().numpy(), oc.attention(0, q))
+        assert mx <= MAX_ABS and rl <= REL_L2, (mx, rl)
+        single = torch.empty_like(o)
+        gc.kvq_decode_attention(0, dev(q), single)
+        torch.cuda.synchronize()
+        assert (single - o).abs().max().item() <= 1e-3
+    # a second launch right away (arrival counters were left at zero), other order, fp16 outputs
+    order = [3, 0, 4, 2, 1]
+    outs16 = [torch.empty(qs[i].shape, dtype=torch.float16, device="cuda") for i in order]
+    kq.kvq_decode_attention_batch([built[i][1] for i in order], 0, [dev(qs[i]) for i in order], outs16)
+    torch.cuda.synchronize()
+    for i, o in zip(order, outs16):
+        assert (o.float() - outs[i]).abs().max().item() <= 1e-3 + 1e-3 * outs[i].abs().max().item()
+    if det:   # bit-reproducible per cache, whatever the batch looks like
+        again = [torch.empty_like(o) for o in outs]
+        kq.kvq_decode_attention_batch([b[1] for b in built], 0, [dev(q) for q in qs], again)
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(again, outs))
+
+
+@pytest.mark.parametrize("tier16", [0, TIER16_INT16])
+def test_ragged_batch_decode_steps(tier16):
+    """A decode loop over five caches of different lengths with kvq_append_decode_attention_batch: cache contents stay
+    bit-identical to the oracle's, outputs within tolerance, through tile and page boundaries."""
+    Hq, Hkv = 8, 2
+    specs = [(1, 32, 411, ((20, 16),), 0), (2, 64, 412, ((256, 2), (128, 4), (60, 16)), 0),
+             (1, 32, 413, ((96, 8), (31, 16)), 0), (1, 64, 414, ((512, 4), (64, 16)), 64), (1, 32, 415, ((33, 16),), 0)]
+    built = [_build(s, Hq, Hkv, tier16) for s in specs]
+    ocs, gcs = [b[0] for b in built], [b[1] for b in built]
+    outs = [torch.empty((s[0], Hq, 128), dtype=torch.float32, device="cuda") for s in specs]
+    for step in range(70):
+        ks = [b[2][:, :, b[4] + step:b[4] + step + 1] for b in built]
+        vs = [b[3][:, :, b[4] + step:b[4] + step + 1] for b in built]
+        qs = [kvq_synth.make_q(s[2], 0, s[0], Hq, b[4] + step) for s, b in zip(specs, built)]
+        want = decode_step_batch(ocs, 0, ks, vs, qs)
+        kq.kvq_append_decode_attention_batch(gcs, 0, [dev(k) for k in ks], [dev(v) for v in vs], [dev(q) for q in qs], outs)
+        if step % 9 == 0 or step == 69:
+            torch.cuda.synchronize()
+            for o, w in zip(outs, want):
+                mx, rl = attention_errors(o.cpu().numpy(), w)
+                assert mx <= MAX_ABS and rl <= REL_L2, (step, mx, rl)
+    for oc, gc in zip(ocs, gcs):
+        assert_same_cache(oc, gc, 0)
+
+
+def test_ragged_batch_append_is_all_or_nothing_and_arguments_are_checked():
+    Hq, Hkv, P = 4, 2, 32
+    per16 = bytes_per_token_head(16, 128, 32, True)
+    oc0, gc0 = make_pair(1, 1, Hq, Hkv, 256, P, policy=POLICY_OLDEST_FIRST)
+    oc1, gc1 = make_pair(1, 1, Hq, Hkv, 256, P, budgets=[Hkv * 64 * per16], policy=POLICY_OLDEST_FIRST)
+    K, V = kvq_synth.make_kv(420, 0, 1, Hkv, 0, 100)
+    append_both(oc0, gc0, 0, K[:, :, :50], V[:, :, :50])
+    append_both(oc1, gc1, 0, K[:, :, :64], V[:, :, :64])                 # exactly full
+    k, v = dev(K[:, :, 64:65]), dev(V[:, :, 64:65])
+    q = dev(kvq_synth.make_q(420, 0, 1, Hq, 64))
+    outs = [torch.empty((1, Hq, 128), dtype=torch.float32, device="cuda") for _ in range(2)]
+    with pytest.raises(kq.KvqError) as e:
+        kq.kvq_append_decode_attention_batch([gc0, gc1], 0, [k, k], [v, v], [q, q], outs)
+    assert e.value.status == kq.KVQ_E_BUDGET
+    assert gc0.kvq_cache_describe(0)[2] == 50 and gc1.kvq_cache_describe(0)[2] == 64
+    assert_same_cache(oc0, gc0, 0)
+    with pytest.raises(kq.KvqError) as e:                                  # the same cache twice
+        kq.kvq_decode_attention_batch([gc0, gc0], 0, [q, q], outs)
+    assert e.value.status == kq.KVQ_E_INVALID
+    _, gi = make_pair(1, 1, Hq, Hkv, 256, P, tier16=TIER16_INT16)
+    gi.kvq_quantize_append(0, dev(K[:, :, :10]), dev(V[:, :, :10]))
+    with pytest.raises(kq.KvqError) as e:                                  # mixed kinds of 16-bit tier
+        kq.kvq_decode_attention_batch([gc0, gi], 0, [q, q], outs)
+    assert e.value.status == kq.KVQ_E_INVALID
+    _, ge = make_pair(1, 1, Hq, Hkv, 256, P)
+    with pytest.raises(kq.KvqError) as e:                                  # an empty cache
+        kq.kvq_decode_attention_batch([gc0, ge], 0, [q, q], outs)
+    assert e.value.status == kq.KVQ_E_STATE
+    # after making room the step goes through for both
+    assert gc1.kvq_progressive_requant(0, reserve_tokens=1) == oc1.requant(0, reserve_tokens=1)
+    want = decode_step_batch([oc0, oc1], 0, [K[:, :, 64:65]] * 2, [V[:, :, 64:65]] * 2,
+                             [kvq_synth.make_q(420, 0, 1, Hq, 64)] * 2)
+    kq.kvq_append_decode_attention_batch([gc0, gc1], 0, [k, k], [v, v], [q, q], outs)
+    torch.cuda.synchronize()
+    for o, w in zip(outs, want):
+        mx, rl = attention_errors(o.cpu().numpy(), w)
+        assert mx <= MAX_ABS and rl <= REL_L2
+    assert_same_cache(oc0, gc0, 0)
+    assert_same_cache(oc1, gc1, 0)
