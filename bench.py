@@ -132,7 +132,8 @@ def int16_tier(kq, torch, kvq_synth):
     in measure_requant; algorithmic bytes per element: 2 read + 1 written + 0.125 of scales re-written (group 32).
     bulk_append: Eq. 1-2 with 65,535 levels, 2 read + 2 written + 0.125 metadata per element.
     attention: trains of launches over 8 blocks of a 7B-shaped block (32,256 4-bit tokens + a 512-token 16-bit window,
-    64 units), window raw fp16 against window INT16; and the error of the two outputs against each other."""
+    64 units), window raw fp16 against window INT16, alternating, fastest train of each; and the error of the two
+    outputs against each other."""
     B, Hkv, T, P, L = 8, 8, 16384, 256, 6
     units = B * Hkv
     cfg = kq.KvqConfig(L, B, 40, Hkv, T, page_tokens=P)
@@ -178,7 +179,7 @@ def int16_tier(kq, torch, kvq_synth):
     Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
     q = torch.from_numpy(kvq_synth.make_q(7, 0, B, Hq, Tb + W - 1)).cuda()
     cfg = kq.KvqConfig(L, B, Hq, Hkv, Tb + W, page_tokens=P, policy=kq.KVQ_POLICY_OLDEST_FIRST)
-    res = {}
+    res, built = {}, {}
     for name, tier in (("fp16_window", kq.KVQ_TIER16_FP16), ("int16_window", kq.KVQ_TIER16_INT16)):
         arena = torch.empty(kq.kvq_arena_bytes(cfg, int(L * units * (Tb * 160 + W * 544) * 1.1) + (64 << 20)),
                             dtype=torch.uint8, device="cuda")
@@ -187,21 +188,25 @@ def int16_tier(kq, torch, kvq_synth):
         for layer in range(L):
             cache.kvq_quantize_append(layer, Kd[:, :, :Tb].contiguous(), Vd[:, :, :Tb].contiguous(), 4)
             cache.kvq_quantize_append(layer, Kd[:, :, Tb:].contiguous(), Vd[:, :, Tb:].contiguous(), 16)
-        o = torch.empty((B, Hq, 128), dtype=torch.float32, device="cuda")
-        trains = []
-        for rep in range(5):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for layer in range(L):
-                cache.kvq_decode_attention(layer, q, o)
-            e1.record()
-            trains.append((e0, e1))
-        torch.cuda.synchronize()
-        ms = float(np.mean([a.elapsed_time(b) for a, b in trains[1:]])) / L
+        built[name] = (cache, arena, torch.empty((B, Hq, 128), dtype=torch.float32, device="cuda"))
+    best = {name: 1e9 for name in built}
+    for rnd in range(3):                      # alternate the two variants; the fastest train of each counts
+        for name, (cache, _, o) in built.items():
+            trains = []
+            for rep in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for layer in range(L):
+                    cache.kvq_decode_attention(layer, q, o)
+                e1.record()
+                trains.append((e0, e1))
+            torch.cuda.synchronize()
+            best[name] = min(best[name], min(a.elapsed_time(b) for a, b in trains[1:]) / L)
+    for name, (cache, _, o) in built.items():
         nbytes = cache.kvq_cache_describe(0)[1]
-        res[name] = {"us_per_launch": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1), "out": o.clone()}
+        res[name] = {"us_per_launch": round(best[name] * 1e3, 2), "GBps": round(nbytes / best[name] / 1e6, 1), "out": o.clone()}
         cache.close()
-        del arena
+    del built
     a, b = res["fp16_window"].pop("out"), res["int16_window"].pop("out")
     res["rel_l2_between_outputs"] = float(f"{(torch.linalg.norm(a - b) / torch.linalg.norm(a)).item():.3e}")
     out["attention_7b_block"] = res
@@ -447,7 +452,8 @@ def main():
     w = kvq_synth.WORKLOADS[args.workload]
     B, Hkv, Hq, L = w.batch, w.n_kv_heads, w.n_q_heads, w.n_layers
     units = B * Hkv
-    steps_total = args.steps + args.warmup
+    n_trains = 5   # timing trains after the timed steps; with the fused step each of them appends one more token
+    steps_total = args.steps + args.warmup + (0 if args.separate_calls else n_trains)
 
     cache, arena, (k_tail, v_tail), gen_s, append_stats, KV = build_state(kq, torch, w, steps_total)
     if args.fused_merge is not None:
@@ -485,7 +491,7 @@ def main():
     torch.cuda.synchronize()
     events = []
     t0 = time.perf_counter()
-    for i in range(args.warmup, steps_total):
+    for i in range(args.warmup, args.warmup + args.steps):
         step(i, events)
     t_issue = time.perf_counter()
     torch.cuda.synchronize()
@@ -495,22 +501,40 @@ def main():
     T_mid = T_end - args.steps / 2.0
     kv_tokens_per_s = B * T_mid * L / (ms_per_step * 1e-3)
 
-    # roofline of the dominant kernel (fused de-quantize + decode attention), one launch = one block.
+    # roofline of the dominant kernel (fused de-quantize + decode attention, with the one-token append in front
+    # unless --separate-calls), one launch = one block.
     # An event pair around a single launch adds several microseconds of its own (the pair's packets sit between
-    # kernels), so the launch duration is taken from trains: one event pair around a sweep of the attention launch
-    # over all blocks, back to back on the same stream, in the state the timed steps left.  The per-launch figure
-    # of the pairs inside the timed steps is kept beside it.
+    # kernels), so the launch duration is taken from trains: one event pair around a sweep of the step's own launch
+    # over all blocks, back to back on the same stream, continuing the state the timed steps left (a train of the
+    # fused step appends one more token per block).  The per-launch figure of the pairs inside the timed steps is
+    # kept beside it.
     attn_ms_pairs = float(np.mean([a.elapsed_time(b) for a, b in events]))
     trains = []
-    for rep in range(5):
+    for rep in range(n_trains):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         for layer in range(L):
-            cache.kvq_decode_attention(layer, q, outs[layer], 0.0, stream)
+            if args.separate_calls:
+                cache.kvq_decode_attention(layer, q, outs[layer], 0.0, stream)
+            else:
+                i = args.warmup + args.steps + rep
+                cache.kvq_append_decode_attention(layer, new_k[i], new_v[i], q, outs[layer], None, 0.0, stream)
         e1.record(stream)
         trains.append((e0, e1))
     torch.cuda.synchronize()
     attn_ms = float(np.mean([a.elapsed_time(b) for a, b in trains[1:]])) / L
+    plain_ms = attn_ms
+    if not args.separate_calls:   # the attention-only kernel (kvq_decode_attention) beside the step's fused one
+        ptrains = []
+        for rep in range(n_trains):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for layer in range(L):
+                cache.kvq_decode_attention(layer, q, outs[layer], 0.0, stream)
+            e1.record(stream)
+            ptrains.append((e0, e1))
+        torch.cuda.synchronize()
+        plain_ms = float(np.mean([a.elapsed_time(b) for a, b in ptrains[1:]])) / L
     bytes_per_launch = 0
     for layer in range(L):
         segs, _, _, _ = cache.kvq_cache_describe(layer)
@@ -523,10 +547,14 @@ def main():
         traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                "kernel": "kvq_attention_kernel", "avg_launch_ms": round(attn_ms, 5),
-                "timing": f"HIP events around trains of {L} back-to-back launches (one per block), 4 trains",
+                "kernel": "kvq_attention_kernel" if args.separate_calls else "kvq_attention_append_kernel",
+                "avg_launch_ms": round(attn_ms, 5),
+                "timing": f"HIP events around trains of {L} back-to-back launches (one per block), {n_trains - 1} trains",
                 "avg_launch_ms_event_pair_in_steps": round(attn_ms_pairs, 5),
-                "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+                "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                "attention_only_kernel": {"kernel": "kvq_attention_kernel", "avg_launch_ms": round(plain_ms, 5),
+                                          "achieved": round(bytes_per_launch / (plain_ms * 1e-3) / 1e9, 1),
+                                          "frac": round(bytes_per_launch / (plain_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}}
 
     result = {
         "metric": "decode-attention KV tokens/s per GPU", "value": round(kv_tokens_per_s, 1), "unit": "KV tokens/s",

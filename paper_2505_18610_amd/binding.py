@@ -94,6 +94,9 @@ def load_library():
         if not os.path.exists(path):
             raise RuntimeError(f"{path} is missing: build it with `python -m paper_2505_18610_amd.build` "
                                "(or __graft_entry__.build()); there is no fallback path")
+        # PyTorch ships its own copy of the HIP runtime.  The library must use the same one (the arena, the tensors and
+        # the streams it is handed belong to it), which the dynamic linker arranges only if torch is loaded first.
+        import torch  # noqa: F401
         lib = C.CDLL(path)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(lib, name)

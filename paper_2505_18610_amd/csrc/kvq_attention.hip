@@ -9,8 +9,15 @@ namespace {
 // grid = (splits, units); 512 threads = 8 wavefronts, one workgroup per compute unit.
 __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const KvqAttnParams P) {
     __shared__ AttnShared sh;
-    if (__builtin_amdgcn_readfirstlane(P.flags[0] & 1u)) attention_body<true, false>(P, sh);
-    else attention_body<false, false>(P, sh);
+    if (__builtin_amdgcn_readfirstlane(P.flags[0] & 1u)) attention_body<true, false, false, false>(P, sh);
+    else attention_body<false, false, false, false>(P, sh);
+}
+
+// The same with a one-token append into the raw fp16 tier in front (kvq_append_decode_attention).
+__global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_append_kernel(const KvqAttnParams P) {
+    __shared__ AttnShared sh;
+    if (__builtin_amdgcn_readfirstlane(P.flags[0] & 1u)) attention_body<true, false, false, true>(P, sh);
+    else attention_body<false, false, false, true>(P, sh);
 }
 
 // The same for a cache whose 16-bit tier holds integer codes in byte planes (KVQ_TIER16_INT16).
@@ -41,6 +48,7 @@ hipError_t kvq_launch_merge(const KvqAttnParams& p, int units, hipStream_t s) {
 
 hipError_t kvq_launch_attention(const KvqAttnParams& p, int units, hipStream_t s) {
     if (p.int16_tier) hipLaunchKernelGGL(kvq_attention_i16_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
+    else if (p.app_t_old >= 0) hipLaunchKernelGGL(kvq_attention_append_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
     else hipLaunchKernelGGL(kvq_attention_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

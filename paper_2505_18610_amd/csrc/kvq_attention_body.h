@@ -841,7 +841,8 @@ static_assert(4 * 16 * KVQ_OPAD >= KVQ_MERGE_LDS_FLOATS, "the reduction slab dou
 // be fused into).  A cache has one kind only, so each kernel carries the code of one.
 // BATCH: the workgroup's (split, unit) come from the caller (ragged batch); else they are the workgroup's grid indices,
 // read where they are needed (handing them in as values costs the single-cache kernels scalar registers they lack).
-template <bool SAFE, bool I16, bool BATCH = false>
+// APPEND: the kernel can carry out a one-token append into the raw fp16 tier (P.app_t_old >= 0) before it attends.
+template <bool SAFE, bool I16, bool BATCH = false, bool APPEND = !I16>
 __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShared& sh, const int split_in = 0,
                                                const int unit_in = 0) {
     const int split = BATCH ? split_in : (int)blockIdx.x, unit = BATCH ? unit_in : (int)blockIdx.y;
@@ -893,13 +894,13 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
     // the token.  Its wavefront 0 does that after the staging barrier, waits until the stores have reached L2 and
     // takes the chunk that holds the tile as its first one (nobody else can claim it); the other seven wavefronts
     // start on the rest of the range meanwhile.
-    const int tile_new = (!I16 && P.app_t_old >= 0) ? P.app_t_old / KVQ_TILE_TOKENS : -1;
-    const bool appends = tile_new >= t_begin && tile_new < t_end;
+    const int tile_new = (APPEND && P.app_t_old >= 0) ? P.app_t_old / KVQ_TILE_TOKENS : -1;
+    const bool appends = APPEND && tile_new >= t_begin && tile_new < t_end;
     const bool one_window = p_last - p_first <= KVQ_DESC_CACHE;
     // the first chunk of every wavefront is fixed (see below); the counter starts behind them
     if (tid == 0) claim_ctr = (appends && one_window) ? KVQ_ATTN_WAVES - 1 : KVQ_ATTN_WAVES;
     __syncthreads();
-    if (!I16 && appends && wave == 0) {
+    if (APPEND && appends && wave == 0) {
         const int tip = tile_new - (tile_new / tpp) * tpp;
         const uint64_t tslot = (uint64_t)unit * tpp + tip;
         uint8_t* code = const_cast<uint8_t*>(P.arena) + (uint64_t)P.app_desc.code_off256 * 256u + tslot * 2 * (512u * 16);
