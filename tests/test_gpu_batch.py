@@ -126,3 +126,41 @@ def test_ragged_batch_append_is_all_or_nothing_and_arguments_are_checked():
         assert mx <= MAX_ABS and rl <= REL_L2
     assert_same_cache(oc0, gc0, 0)
     assert_same_cache(oc1, gc1, 0)
+
+
+def test_full_size_ragged_batch_sampled_sequences():
+    """The ragged batch the bench times (sixteen 7B-shaped sequences of 2,048 ... 32,768 tokens, 4-bit bulk and a
+    512-token raw window, one cache each) at full size, one block: the step in one launch, then sampled sequences
+    checked one by one against the oracle (outputs within tolerance, cache contents bit-exact)."""
+    from oracle import OracleCache, CacheConfig
+    Hq, Hkv, P, W = 28, 4, 256, 512
+    lengths = [2048 * (i + 1) for i in range(16)]
+    caches, arenas, data = [], [], []
+    for i, T in enumerate(lengths):
+        cfg = kq.KvqConfig(1, 1, Hq, Hkv, T + 64, page_tokens=P, policy=kq.KVQ_POLICY_OLDEST_FIRST)
+        arena = torch.empty(kq.kvq_arena_bytes(cfg, int(Hkv * (T * 160 + (W + 2 * P) * 512) * 1.1) + (8 << 20)),
+                            dtype=torch.uint8, device="cuda")
+        c = kq.KvqCache(cfg, [1 << 60], [2], arena=arena)
+        K, V = kvq_synth.make_kv(500 + i, 0, 1, Hkv, 0, T + 1)
+        c.kvq_quantize_append(0, dev(K[:, :, :T - W]), dev(V[:, :, :T - W]), 4)
+        c.kvq_quantize_append(0, dev(K[:, :, T - W:T]), dev(V[:, :, T - W:T]), 16)
+        caches.append(c); arenas.append(arena); data.append((K, V))
+    qs = [kvq_synth.make_q(500 + i, 0, 1, Hq, T) for i, T in enumerate(lengths)]
+    outs = [torch.empty((1, Hq, 128), dtype=torch.float32, device="cuda") for _ in lengths]
+    kq.kvq_append_decode_attention_batch(caches, 0, [dev(d[0][:, :, T:T + 1]) for d, T in zip(data, lengths)],
+                                         [dev(d[1][:, :, T:T + 1]) for d, T in zip(data, lengths)],
+                                         [dev(q) for q in qs], outs)
+    torch.cuda.synchronize()
+    assert all(bool(torch.isfinite(o).all()) for o in outs)
+    for i in (0, 6, 15):
+        T, (K, V) = lengths[i], data[i]
+        oc = OracleCache(CacheConfig(1, 1, Hq, Hkv, page_tokens=P, max_tokens=T + 64, policy=POLICY_OLDEST_FIRST), [1 << 60], [2])
+        oc.append(0, K[:, :, :T - W], V[:, :, :T - W], 4)
+        oc.append(0, K[:, :, T - W:T], V[:, :, T - W:T], 16)
+        want = decode_step_batch([oc], 0, [K[:, :, T:T + 1]], [V[:, :, T:T + 1]], [qs[i]])[0]
+        mx, rl = attention_errors(outs[i].cpu().numpy(), want)
+        assert mx <= MAX_ABS and rl <= REL_L2, (i, mx, rl)
+        if i == 0:
+            assert_same_cache(oc, caches[i], 0)
+    for c in caches:
+        c.close()
