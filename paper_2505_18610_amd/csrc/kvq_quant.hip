@@ -96,9 +96,8 @@ __device__ inline uint32_t pk_max_u(uint32_t a, uint32_t b) {
 #define KVQ_LDS_CODES (4 * KVQ_LDS_VGRP)           // room for either arrangement
 
 // Eq. 1-2 for the 32 fp16 values in w[16] (two per dword).  codes[e] receives the code of element e as a float.
-// Fast path: t = (x - Z) * (1/S) differs from the correctly rounded quotient by < 6.1e-5 for codes up to 255,
-// so rint(t) is the required code unless t lies within 1.3e-4 of a half-integer; if any lane of the wavefront
-// sees such a value the whole step is redone with the IEEE division the definition asks for.
+// Fast path: a reciprocal multiply, with the IEEE division the definition asks for only where the product lies too
+// close to a half-integer to decide the rounding (see the bound in the body).
 // gspan = G / 32: a quantization group of G = 64 or 128 channels spans 2 or 4 neighbouring owner lanes (the
 // owners of one token's four 32-channel runs are lanes 4k .. 4k+3), which then share min, max and so (S, Z).
 template <int B>
@@ -122,7 +121,17 @@ __device__ inline void quantize_owner(const uint32_t (&w)[16], float (&codes)[32
         }
         return;
     }
-    const float rcp = (Sf == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(Sf);
+    // Reciprocal: the hardware's (1 ulp) refined by one Newton step, relative error below 2^-24 (1 + 2^-22).  Then
+    // t = (x - Z) * rcp is within 2^-23 of the true quotient, relatively, and the correctly rounded fp32 quotient the
+    // definition asks for within 2^-24: the two differ by less than 1.8e-7 * (levels + 1), and rint(t) is the
+    // required code unless t lies that close to a half-integer (eps below adds a margin of 1.4).  Only then is the
+    // IEEE division carried out, and only for the elements concerned.
+    float rcp = 0.0f;
+    if (Sf != 0.0f) {
+        const float r0 = __builtin_amdgcn_rcpf(Sf);
+        rcp = fmaf(r0, fmaf(-Sf, r0, 1.0f), r0);
+    }
+    constexpr float near_half = 0.5f - 2.5e-7f * (float)(levels + 1);
     float worst = 0.0f;
 #pragma unroll
     for (int e = 0; e < 32; ++e) {
@@ -132,12 +141,13 @@ __device__ inline void quantize_owner(const uint32_t (&w)[16], float (&codes)[32
         worst = fmaxf(worst, fabsf(t - r));
         codes[e] = fminf(r, (float)levels);
     }
-    if (__any(worst > 0.5f - 1.3e-4f)) {
+    if (__any(worst > near_half)) {
         asm volatile("" ::: "memory");  // keep this a branch
 #pragma unroll
         for (int e = 0; e < 32; ++e) {
             const float x = h2f((uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffff)));
-            codes[e] = (float)code_of(x, mn, Sf, levels);
+            const float t = (x - mn) * rcp;
+            if (fabsf(t - rintf(t)) > near_half) codes[e] = (float)code_of(x, mn, Sf, levels);
         }
     }
 }
@@ -440,22 +450,23 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
     {
         uint32_t in[32];
         load_chunks_stream<16>(src, lane, in);
+        // LDS rows are tokens (256 bytes); the bytes of row r are rotated by 32 * (r / 8), so that the four lane
+        // quarters, which write rows 8 apart, land in different banks
         if (!which) {
 #pragma unroll
             for (int p = 0; p < 8; ++p) {  // piece (sub, grp): 8 consecutive channels of one token
                 const int sub = p >> 2, g = p & 3;
                 const int t = 8 * (n >> 2) + 4 * sub + (n & 3);
-                *reinterpret_cast<u32x4*>(raw_lds + t * 256 + (32 * g + 8 * j) * 2) =
+                *reinterpret_cast<u32x4*>(raw_lds + t * 256 + (((32 * g + 8 * j) * 2 + 32 * (t >> 3)) & 255)) =
                     u32x4{in[4 * p], in[4 * p + 1], in[4 * p + 2], in[4 * p + 3]};
             }
         } else {
-            uint16_t* r16 = reinterpret_cast<uint16_t*>(raw_lds);
 #pragma unroll
             for (int d = 0; d < 32; ++d) {  // dword d = slots 2d, 2d+1 = tokens 8j + (2d%8), +1 of channel 16*(d/4)+n
                 const int nt = d >> 2, i = (2 * d) & 7;
-                const int ch = 16 * nt + n;
-                r16[(8 * j + i) * 128 + ch] = (uint16_t)(in[d] & 0xffff);
-                r16[(8 * j + i + 1) * 128 + ch] = (uint16_t)(in[d] >> 16);
+                const int col = ((16 * nt + n) * 2 + 32 * j) & 255;  // rows 8j + i and 8j + i + 1 share the rotation
+                *reinterpret_cast<uint16_t*>(raw_lds + (8 * j + i) * 256 + col) = (uint16_t)(in[d] & 0xffff);
+                *reinterpret_cast<uint16_t*>(raw_lds + (8 * j + i + 1) * 256 + col) = (uint16_t)(in[d] >> 16);
             }
         }
     }
@@ -465,11 +476,14 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
     for (int pass = 0; pass < 2; ++pass) {
         const int tl = 16 * pass + (lane >> 2);
         uint32_t w[16];
-        const u32x4* rp = reinterpret_cast<const u32x4*>(raw_lds + tl * 256 + grp * 64);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            u32x4 v = rp[c];
-            w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+        for (int h = 0; h < 2; ++h) {  // the two 32-byte halves of the group's 64 bytes (the rotation may wrap between them)
+            const u32x4* rp = reinterpret_cast<const u32x4*>(raw_lds + tl * 256 + ((grp * 64 + 32 * h + 32 * (tl >> 3)) & 255));
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                u32x4 v = rp[c];
+                w[8 * h + 4 * c] = v.x; w[8 * h + 4 * c + 1] = v.y; w[8 * h + 4 * c + 2] = v.z; w[8 * h + 4 * c + 3] = v.w;
+            }
         }
         float codes[32];
         uint16_t S, Z;

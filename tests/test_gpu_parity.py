@@ -88,6 +88,26 @@ def test_quantizer_ties_and_near_ties():
             assert_same_cache(oc2, gc2, 0)
 
 
+@pytest.mark.parametrize("bits", [8, 4, 2])
+def test_quantizer_bulk_random_data_bit_exact(bits):
+    """Four million elements per tensor with arbitrary scales: the reciprocal-multiply shortcut of the quantizer meets
+    quotients within a few fp32 ulps of a half-integer some tens of times here (8 bits), and every code must still be
+    the one the correctly rounded division gives.  Through the append kernel and, for 8 bits, the fp16-page kernel."""
+    B, H, T, P = 2, 2, 8192, 256
+    rng = np.random.default_rng(900 + bits)
+    gain = np.exp(rng.uniform(-4, 4, (B, H, T, 4, 1)))
+    K = (rng.standard_normal((B, H, T, 4, 32)) * gain).reshape(B, H, T, 128).astype(np.float16)
+    V = (rng.uniform(-1, 1, (B, H, T, 4, 32)) * gain[::-1]).reshape(B, H, T, 128).astype(np.float16)
+    oc, gc = make_pair(1, B, 2 * H, H, T, P)
+    append_both(oc, gc, 0, K, V, bits)
+    assert_same_cache(oc, gc, 0)
+    if bits == 8:
+        oc2, gc2 = make_pair(1, B, 2 * H, H, T, P)
+        append_both(oc2, gc2, 0, K, V, 16)
+        assert gc2.kvq_progressive_requant(0, segment=0) == oc2.requant(0, segment=0)
+        assert_same_cache(oc2, gc2, 0)
+
+
 def test_requant_chain_bit_exact():
     B, H, T, P = 2, 2, 512, 128
     K, V = kvq_synth.make_kv(103, 0, B, H, 0, T)
