@@ -166,8 +166,8 @@ kvq_status_t kvq_append_decode_attention(kvq_cache_t* cache, int32_t layer, cons
  *   KVQ_E_BUDGET / KVQ_E_STATE no cache has changed.  (An arena that runs out of pages, KVQ_E_OOM, is only found while
  *   carrying them out; caches before the failing one then hold their new token.)
  * The device's workgroups are shared among the caches in proportion to the time their tiles take.  Results per cache
- * are those of the single-cache calls up to floating-point summation order.  The parameter blocks of the launch travel
- * through the arena of caches[0]: calls that share that cache must be issued on one stream. */
+ * are those of the single-cache calls up to floating-point summation order.  The parameter blocks of the launch are
+ * read from the pinned staging memory of caches[0]: calls that involve that cache must be issued on one stream. */
 kvq_status_t kvq_decode_attention_batch(kvq_cache_t* const* caches, int32_t n_caches, int32_t layer,
                                         const void* const* q_dev, void* const* out_dev, int32_t out_is_fp32,
                                         float softmax_scale, void* hip_stream);

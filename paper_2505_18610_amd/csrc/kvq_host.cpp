@@ -94,11 +94,11 @@ struct kvq_cache {
     uint64_t unit_bytes = 0;
     uint64_t table_off = 0, jobs_off = 0, part_o_off = 0, part_ml_off = 0, counters_off = 0, flags_off = 0, pages_off = 0;
     uint64_t reparam_off = 0;  // per block: lambda [n_kv_heads][128] fp32, then 1 / lambda
-    uint64_t batch_off = 0;    // parameter blocks of a ragged-batch attention launch led by this cache
     uint32_t* flags_dev() const { return reinterpret_cast<uint32_t*>(arena + flags_off); }
     Buddy buddy;
     std::vector<Layer> layers;
     uint8_t* ring = nullptr;
+    uint8_t* ring_dev = nullptr;  // the same pinned memory as the device addresses it
     uint64_t ring_pos = 0;
     bool device_ready = false;
     int splits_override = 0;
@@ -134,7 +134,7 @@ struct kvq_cache {
 namespace {
 
 struct Regions {
-    uint64_t table_off, jobs_off, part_o_off, part_ml_off, counters_off, flags_off, reparam_off, batch_off, pages_off;
+    uint64_t table_off, jobs_off, part_o_off, part_ml_off, counters_off, flags_off, reparam_off, pages_off;
 };
 uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
@@ -164,7 +164,6 @@ Regions layout_regions(const kvq_config_t* c) {
     r.counters_off = off;  off = align_up(off + units * sizeof(uint32_t), 256);
     r.flags_off = off;     off = align_up(off + 64, 256);
     r.reparam_off = off;   off = align_up(off + (uint64_t)c->n_layers * 2 * c->n_kv_heads * KVQ_D * sizeof(float), 256);
-    r.batch_off = off;     off = align_up(off + (uint64_t)KVQ_MAX_BATCH_CACHES * sizeof(KvqAttnParams), 256);
     r.pages_off = align_up(off, 4096);
     return r;
 }
@@ -184,6 +183,20 @@ kvq_status_t upload(kvq_cache* c, void* dst_dev, const void* src, uint64_t bytes
     if (hipMemcpyAsync(dst_dev, c->ring + c->ring_pos, bytes, hipMemcpyHostToDevice, s) != hipSuccess)
         return KVQ_E_HIP;
     c->ring_pos = align_up(c->ring_pos + bytes, 64);
+    return KVQ_OK;
+}
+
+// Place `bytes` of host data in the pinned staging ring and return where (a host address the device can read as
+// well); the space is not reused before the work enqueued on s so far has completed.
+kvq_status_t stage(kvq_cache* c, const void* src, uint64_t bytes, hipStream_t s, const void** where) {
+    if (bytes == 0 || bytes > kRingBytes) return KVQ_E_INVALID;
+    if (c->ring_pos + bytes > kRingBytes) {
+        if (hipStreamSynchronize(s) != hipSuccess) return KVQ_E_HIP;
+        c->ring_pos = 0;
+    }
+    std::memcpy(c->ring + c->ring_pos, src, bytes);
+    *where = c->ring_dev + c->ring_pos;
+    c->ring_pos = align_up(c->ring_pos + bytes, 256);
     return KVQ_OK;
 }
 
@@ -406,7 +419,6 @@ kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_bud
     c->table_off = r.table_off; c->jobs_off = r.jobs_off; c->part_o_off = r.part_o_off;
     c->part_ml_off = r.part_ml_off; c->counters_off = r.counters_off; c->flags_off = r.flags_off; c->pages_off = r.pages_off;
     c->reparam_off = r.reparam_off;
-    c->batch_off = r.batch_off;
     uint64_t super = c->unit_bytes << kMaxOrder;
     if (arena_bytes < c->pages_off + super) { delete c; return KVQ_E_OOM; }
     uint64_t n_super = (arena_bytes - c->pages_off) / super;
@@ -419,6 +431,11 @@ kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_bud
     }
     if (!c->dry) {
         if (hipHostMalloc(reinterpret_cast<void**>(&c->ring), kRingBytes, hipHostMallocDefault) != hipSuccess) {
+            delete c;
+            return KVQ_E_HIP;
+        }
+        if (hipHostGetDevicePointer(reinterpret_cast<void**>(&c->ring_dev), c->ring, 0) != hipSuccess) {
+            (void)hipHostFree(c->ring);
             delete c;
             return KVQ_E_HIP;
         }
@@ -813,9 +830,13 @@ kvq_status_t batch_impl(kvq_cache_t* const* caches, int32_t n, int32_t layer, co
                                            params[(size_t)i]);
         if (st != KVQ_OK) return st;
     }
+    // The kernel reads the parameter blocks straight from the pinned staging ring of the first cache (host memory the
+    // device can address): a copy into the arena would be a separate transfer between two kernels on the stream, which
+    // costs more than the workgroups' first reads travelling over the host link.
     kvq_cache_t* lead = caches[0];
-    KvqAttnParams* params_dev = reinterpret_cast<KvqAttnParams*>(lead->arena + lead->batch_off);
-    kvq_status_t st = upload(lead, params_dev, params.data(), params.size() * sizeof(KvqAttnParams), s);
+    const KvqAttnParams* params_dev = nullptr;
+    kvq_status_t st = stage(lead, params.data(), params.size() * sizeof(KvqAttnParams), s,
+                            reinterpret_cast<const void**>(&params_dev));
     if (st != KVQ_OK) return st;
     std::vector<int> units((size_t)n);
     for (int i = 0; i < n; ++i) units[(size_t)i] = caches[i]->units;
