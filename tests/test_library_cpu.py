@@ -255,3 +255,33 @@ def test_tier16_option_only_on_empty_caches():
     free0 = c.kvq_cache_arena_free_bytes()
     assert c.kvq_progressive_requant(1, segment=0) == 2 and c.kvq_cache_describe(1)[0] == [(0, 40, 8)]
     assert c.kvq_cache_arena_free_bytes() - free0 == 2 * 32 * 32 * 8      # each page gave back half of its code block
+
+
+def test_batch_entry_points_reject_what_they_cannot_run():
+    """Argument checks of the ragged-batch calls that need no GPU: accounting-only caches cannot attend, and a batch
+    holds at most 64 caches."""
+    cfg = kq.KvqConfig(1, 1, 2, 1, 256, page_tokens=32)
+    caches = [kq.KvqCache(cfg, [1 << 30], [2], arena=None, arena_bytes=1 << 24) for _ in range(65)]
+    for c in caches:
+        c.kvq_quantize_append(0, None, None, n_new=5)
+    fake = [1 << 20] * 65          # never dereferenced: the calls fail before any launch
+    with pytest.raises(kq.KvqError) as e:
+        kq.kvq_decode_attention_batch(caches[:2], 0, fake[:2], _FakeOuts(2))
+    assert e.value.status == kq.KVQ_E_STATE
+    with pytest.raises(kq.KvqError) as e:
+        kq.kvq_decode_attention_batch(caches, 0, fake, _FakeOuts(65))
+    assert e.value.status == kq.KVQ_E_INVALID
+    with pytest.raises(kq.KvqError) as e:
+        kq.kvq_append_decode_attention_batch(caches[:2], 3, fake[:2], fake[:2], fake[:2], _FakeOuts(2))
+    assert e.value.status == kq.KVQ_E_INVALID                       # no such block
+    assert all(c.kvq_cache_describe(0)[2] == 5 for c in caches[:2])  # nothing was appended
+
+
+class _FakeOut(int):
+    class _D:
+        itemsize = 4
+    dtype = _D()
+
+
+def _FakeOuts(n):
+    return [_FakeOut(1 << 21) for _ in range(n)]
