@@ -55,11 +55,17 @@ def test_ragged_batch_attention_matches_oracle_and_single_calls(det):
     torch.cuda.synchronize()
     for i, o in zip(order, outs16):
         assert (o.float() - outs[i]).abs().max().item() <= 1e-3 + 1e-3 * outs[i].abs().max().item()
-    if det:   # bit-reproducible per cache, whatever the batch looks like
+    if det:   # bit-reproducible per cache, whatever the batch looks like, and with the merge as separate kernels
         again = [torch.empty_like(o) for o in outs]
         kq.kvq_decode_attention_batch([b[1] for b in built], 0, [dev(q) for q in qs], again)
         torch.cuda.synchronize()
         assert all(torch.equal(a, b) for a, b in zip(again, outs))
+        for _, gc, *_ in built:
+            gc.kvq_cache_set_option(kq.KVQ_OPT_FUSED_MERGE, 0)
+        unfused = [torch.empty_like(o) for o in outs]
+        kq.kvq_decode_attention_batch([b[1] for b in built], 0, [dev(q) for q in qs], unfused)
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(unfused, outs))
 
 
 @pytest.mark.parametrize("tier16", [0, TIER16_INT16])
