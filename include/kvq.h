@@ -17,7 +17,8 @@
  *     are updated at enqueue time, the device tables in stream order).
  *   - Errors are reported as kvq_status_t; argument, state and budget errors are detected on the host before
  *     anything is enqueued and leave the cache unchanged.  Nothing throws or aborts across this boundary.
- *   - All sequences of a batch have the same length and share one page table per block.
+ *   - All sequences of one cache have the same length and share one page table per block; sequences of different
+ *     lengths live in caches of their own and are served together by the *_batch entry points.
  *   - head_dim is 128, group is 32, 64 or 128 channels (128 is the paper's setting, Sec. 4.1.2),
  *     1 <= n_q_heads / n_kv_heads <= 16.
  */
