@@ -598,6 +598,9 @@ __device__ inline void issue_stage(Stage<B, TPI>& sg, const RunCtx& c, const Cla
 template <int B, int TPI, int N, bool SAFE>
 __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds, RunCtx& c, uint8_t* meta_lds,
                                   int lane) {
+    // Values a path derives from the lane index (LDS addresses, operand selectors) would otherwise be hoisted out of the
+    // caller's loop over runs, for all widths at once, and held in registers the kernel does not have.
+    asm volatile("" : "+v"(lane));
     set_accumulator_exponent(st, v_exponent<B>(SAFE));
     if constexpr (B >= 8) {
         // wide tiles (8 and 16 KiB, the latter raw fp16 or integer byte planes): one register stage, tile by tile, K and V staggered (V loads fly during
