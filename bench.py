@@ -522,7 +522,8 @@ def main():
         e1.record(stream)
         trains.append((e0, e1))
     torch.cuda.synchronize()
-    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in trains[1:]])) / L
+    train_ms = [a.elapsed_time(b) / L for a, b in trains[1:]]
+    attn_ms = float(np.mean(train_ms))
     plain_ms = attn_ms
     if not args.separate_calls:   # the attention-only kernel (kvq_decode_attention) beside the step's fused one
         ptrains = []
@@ -549,6 +550,7 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "kernel": "kvq_attention_kernel" if args.separate_calls else "kvq_attention_append_kernel",
                 "avg_launch_ms": round(attn_ms, 5),
+                "min_launch_ms": round(float(np.min(train_ms)), 5), "median_launch_ms": round(float(np.median(train_ms)), 5),
                 "timing": f"HIP events around trains of {L} back-to-back launches (one per block), {n_trains - 1} trains",
                 "avg_launch_ms_event_pair_in_steps": round(attn_ms_pairs, 5),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch),
