@@ -588,6 +588,9 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, KV, q_np)
     result["setup_seconds"] = {"generate_inputs": round(gen_s, 1)}
+    prop = torch.cuda.get_device_properties(0)
+    result["device"] = {"name": prop.name, "compute_units": prop.multi_processor_count,
+                        "hbm_GiB": round(prop.total_memory / 2 ** 30, 1)}
     print(json.dumps(result))
 
 
