@@ -282,6 +282,12 @@ kvq_status_t kvq_allocate_bits(int32_t n_blocks, int32_t n_choices, const double
 kvq_status_t kvq_stream_read_probe(kvq_cache_t* cache, const void* buf_dev, uint64_t bytes, int32_t n_workgroups,
                                    void* hip_stream);
 
+/* Empties block `layer` (-1: every block) so that the cache can take a new sequence: its pages go back to the arena
+ * (reused only by work enqueued later, so on the cache's stream nothing in flight is disturbed), its token count to
+ * zero; budget, Fbit, options and the block's reparameterization factors stay (kvq_cache_set_reparam may be called
+ * again, the block being empty).  Host bookkeeping only; nothing is enqueued. */
+kvq_status_t kvq_cache_reset(kvq_cache_t* cache, int32_t layer);
+
 /* Free bytes left in the arena's page area (host bookkeeping). */
 uint64_t kvq_cache_arena_free_bytes(const kvq_cache_t* cache);
 

@@ -69,6 +69,7 @@ _SIGNATURES = {
                                            C.c_void_p, C.c_void_p]),
     "kvq_cache_set_option": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "kvq_cache_arena_free_bytes": (C.c_uint64, [C.c_void_p]),
+    "kvq_cache_reset": (C.c_int, [C.c_void_p, C.c_int32]),
     "kvq_cache_set_reparam": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
     "kvq_calibrate_lambda": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]),
     "kvq_cache_sensitivity": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -308,6 +309,9 @@ class KvqCache:
     def kvq_stream_read_probe(self, buf, n_workgroups, stream=None):
         self._check(self.lib.kvq_stream_read_probe(self.handle, _ptr(buf), buf.numel() * buf.element_size(), n_workgroups,
                                                    _stream(stream)), "kvq_stream_read_probe")
+
+    def kvq_cache_reset(self, layer=-1):
+        self._check(self.lib.kvq_cache_reset(self.handle, layer), "kvq_cache_reset")
 
     def kvq_cache_arena_free_bytes(self) -> int:
         return int(self.lib.kvq_cache_arena_free_bytes(self.handle))

@@ -1108,6 +1108,23 @@ kvq_status_t kvq_stream_read_probe(kvq_cache_t* c, const void* buf_dev, uint64_t
     return kvq_launch_stream_read(buf_dev, bytes, n_workgroups, sink, as_stream(hip_stream)) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
 }
 
+kvq_status_t kvq_cache_reset(kvq_cache_t* c, int32_t layer) {
+    if (!c || layer < -1 || layer >= c->cfg.n_layers) return KVQ_E_INVALID;
+    const int first = layer < 0 ? 0 : layer, last = layer < 0 ? c->cfg.n_layers : layer + 1;
+    for (int l = first; l < last; ++l) {
+        Layer& L = c->layers[(size_t)l];
+        for (const Page& p : L.pages) {
+            c->buddy.release(p.code_unit, order_of_bits(p.bits));
+            if (c->has_meta(p.bits)) c->buddy.release(p.meta_unit, 0);
+        }
+        L.pages.clear();
+        L.T = 0;
+        L.version++;
+        L.plan_tiles = -1;
+    }
+    return KVQ_OK;
+}
+
 uint64_t kvq_cache_arena_free_bytes(const kvq_cache_t* c) { return c ? c->buddy.free_units() * c->unit_bytes : 0; }
 
 const char* kvq_status_string(kvq_status_t s) {

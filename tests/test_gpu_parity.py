@@ -639,3 +639,23 @@ def test_full_size_14b_layer_sampled_units():
     layers = [w.layer_bits.index(b) for b in (2, 8) if b in w.layer_bits]
     for layer in layers:
         _sampled_full_size(w, 1, ((0, 2),), layer=layer)
+
+
+def test_cache_reset_and_reuse():
+    """A block that held one sequence is emptied and takes another: contents and attention are those of a fresh cache."""
+    B, H, T, P = 1, 2, 300, 64
+    oc, gc = make_pair(2, B, 2 * H, H, 512, P)
+    K, V = kvq_synth.make_kv(950, 0, B, H, 0, T)
+    append_both(oc, gc, 1, K, V, 4)
+    gc.kvq_progressive_requant(1, segment=0)
+    free_before = gc.kvq_cache_arena_free_bytes()
+    gc.kvq_cache_reset(1)
+    assert gc.kvq_cache_arena_free_bytes() > free_before and gc.kvq_cache_describe(1)[2] == 0
+    oc2, _ = make_pair(2, B, 2 * H, H, 512, P)
+    K2, V2 = kvq_synth.make_kv(951, 0, B, H, 0, 200)
+    for n, bits in ((64, 2), (64, 8), (72, 16)):
+        t = oc2.layers[1].T
+        oc2.append(1, K2[:, :, t:t + n], V2[:, :, t:t + n], bits)
+        gc.kvq_quantize_append(1, dev(K2[:, :, t:t + n]), dev(V2[:, :, t:t + n]), bits)
+    assert_same_cache(oc2, gc, 1)
+    check_attention(oc2, gc, 1, kvq_synth.make_q(951, 0, B, 2 * H, 199))

@@ -285,3 +285,23 @@ class _FakeOut(int):
 
 def _FakeOuts(n):
     return [_FakeOut(1 << 21) for _ in range(n)]
+
+
+def test_cache_reset_returns_every_page():
+    cfg = kq.KvqConfig(2, 2, 4, 2, 1024, page_tokens=32, window=32)
+    c = kq.KvqCache(cfg, [1 << 30] * 2, [2, 4], arena=None, arena_bytes=1 << 26)
+    free0 = c.kvq_cache_arena_free_bytes()
+    for layer in range(2):
+        c.kvq_quantize_append(layer, None, None, n_new=300)
+        c.kvq_progressive_requant(layer)
+        c.kvq_quantize_append(layer, None, None, n_new=70, entry_bits=0)
+    assert c.kvq_cache_arena_free_bytes() < free0
+    c.kvq_cache_reset(1)
+    assert c.kvq_cache_describe(1) == ([], 0, 0, 16) and c.kvq_cache_describe(0)[2] == 370
+    c.kvq_cache_reset()
+    assert c.kvq_cache_arena_free_bytes() == free0 and c.kvq_cache_describe(0) == ([], 0, 0, 16)
+    c.kvq_quantize_append(0, None, None, n_new=40)           # usable again
+    assert c.kvq_cache_describe(0)[0] == [(0, 40, 16)]
+    with pytest.raises(kq.KvqError) as e:
+        c.kvq_cache_reset(5)
+    assert e.value.status == kq.KVQ_E_INVALID
