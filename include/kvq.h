@@ -90,7 +90,8 @@ kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_bud
                               const uint8_t* block_fbit_host, void* arena_dev, uint64_t arena_bytes,
                               kvq_cache_t** out);
 
-/* Frees the host tables.  Work already enqueued keeps running; the arena is the caller's. */
+/* Frees the host tables and the pinned staging memory (freeing it makes the HIP runtime wait for the device, so work
+ * already enqueued that still reads it completes first); the arena is the caller's. */
 void kvq_cache_destroy(kvq_cache_t* cache);
 
 /* Quantize-on-append (Sec. 2.2 Eq. 1-2; Sec. 3.1).
