@@ -659,3 +659,47 @@ def test_cache_reset_and_reuse():
         gc.kvq_quantize_append(1, dev(K2[:, :, t:t + n]), dev(V2[:, :, t:t + n]), bits)
     assert_same_cache(oc2, gc, 1)
     check_attention(oc2, gc, 1, kvq_synth.make_q(951, 0, B, 2 * H, 199))
+
+
+def test_attention_launches_replay_from_a_hip_graph():
+    """kvq_decode_attention enqueues kernels only (arguments by value, no copies, no clears), so a sweep over blocks can
+    be captured into a HIP graph: replays, interleaved with eager launches and synchronisations, reproduce the eager
+    outputs bit for bit in deterministic mode, also after q has been overwritten in place."""
+    L, B, H, g, T, P = 3, 2, 2, 4, 700, 64
+    oc, gc = make_pair(L, B, H * g, H, 1024, P)
+    gc.kvq_cache_set_option(kq.KVQ_OPT_DETERMINISTIC, 1)
+    for layer in range(L):
+        K, V = kvq_synth.make_kv(960 + layer, layer, B, H, 0, T)
+        t = 0
+        for n, bits in ((256, 2), (192, 4), (128, 8), (124, 16)):
+            append_both(oc, gc, layer, K[:, :, t:t + n], V[:, :, t:t + n], bits)
+            t += n
+    q = dev(kvq_synth.make_q(960, 0, B, H * g, T - 1))
+    outs = [torch.empty((B, H * g, 128), dtype=torch.float32, device="cuda") for _ in range(L)]
+    eager = []
+    for layer in range(L):
+        gc.kvq_decode_attention(layer, q, outs[layer])
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for layer in range(L):
+                gc.kvq_decode_attention(layer, q, outs[layer], stream=torch.cuda.current_stream())
+    for rep in range(4):
+        for o in outs:
+            o.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(outs, eager)), rep
+        gc.kvq_decode_attention(rep % L, q, outs[rep % L])           # eager work between the replays
+        torch.cuda.synchronize()
+    q2 = dev(kvq_synth.make_q(961, 0, B, H * g, T - 1))
+    q.copy_(q2)                                                       # same buffer, new queries
+    graph.replay()
+    torch.cuda.synchronize()
+    for layer in range(L):
+        mx, rl = attention_errors(outs[layer].cpu().numpy(), oc.attention(layer, q2.cpu().numpy()))
+        assert mx <= MAX_ABS and rl <= REL_L2, (layer, mx, rl)
