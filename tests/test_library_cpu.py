@@ -305,3 +305,54 @@ def test_cache_reset_returns_every_page():
     with pytest.raises(kq.KvqError) as e:
         c.kvq_cache_reset(5)
     assert e.value.status == kq.KVQ_E_INVALID
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """include/kvq.h compiles as C99 and as C++17, and a C program linked against libkvq.so runs the entry points that
+    need no GPU: the byte accounting, the allocation solver (Sec. 3.2, Eq. 6) and an accounting-only cache."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_kvq.c"
+    src.write_text(r'''
+#include "kvq.h"
+#include <stdio.h>
+int main(void) {
+    if (kvq_bytes_per_token_head(2, 128, 32, 1, 0) != 96) return 1;
+    double s[4] = {4.0, 1.0, 3.0, 0.5};
+    uint64_t mem[4] = {10, 20, 10, 20};
+    int32_t choice[2];
+    double total;
+    uint64_t used;
+    if (kvq_allocate_bits(2, 2, s, mem, 30, choice, &total, &used) != KVQ_OK) return 2;
+    if (choice[0] != 1 || choice[1] != 0 || total != 4.0 || used != 30) return 3;
+    kvq_config_t cfg = {1, 1, 8, 2, 128, 32, 1024, 0, 0, 128, KVQ_POLICY_PAPER, 1};
+    uint64_t budget = 1u << 20;
+    uint8_t fbit = 2;
+    kvq_cache_t* c = 0;
+    if (kvq_cache_create(&cfg, &budget, &fbit, 0, 1u << 26, &c) != KVQ_OK) return 4;
+    if (kvq_quantize_append(c, 0, 0, 0, 100, 0, 0) != KVQ_OK) return 5;
+    int32_t n = 0, tokens = 0, bits = 0;
+    uint64_t bytes = 0;
+    kvq_segment_info_t seg[2];
+    if (kvq_cache_describe(c, 0, seg, 2, &n, &bytes, &tokens, &bits) != KVQ_OK) return 6;
+    if (n != 1 || tokens != 100 || bits != 16 || bytes != 100u * 2u * 512u) return 7;
+    if (kvq_decode_attention(c, 0, 0, 0, 1, 0.0f, 0) == KVQ_OK) return 8;   /* no arena: must refuse */
+    kvq_cache_destroy(c);
+    puts(kvq_status_string(KVQ_OK));
+    return 0;
+}
+''')
+    inc = os.path.join(ROOT, "include")
+    libdir = os.path.dirname(kq.library_path())
+    for cmd in (["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, "-x", "c", os.path.join(inc, "kvq.h")],
+                ["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, "-x", "c++", os.path.join(inc, "kvq.h")]):
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+    exe = tmp_path / "use_kvq"
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lkvq",
+                        "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
