@@ -132,8 +132,8 @@ def int16_tier(kq, torch, kvq_synth):
     in measure_requant; algorithmic bytes per element: 2 read + 1 written + 0.125 of scales re-written (group 32).
     bulk_append: Eq. 1-2 with 65,535 levels, 2 read + 2 written + 0.125 metadata per element.
     attention: trains of launches over 8 blocks of a 7B-shaped block (32,256 4-bit tokens + a 512-token 16-bit window,
-    64 units), window raw fp16 against window INT16, alternating, fastest train of each; and the error of the two
-    outputs against each other."""
+    64 units), window raw fp16 against window INT16, alternating, fastest train of each; the error of the two outputs
+    against each other (taken before any token is added); and the whole decode step of a block, new token included."""
     B, Hkv, T, P, L = 8, 8, 16384, 256, 6
     units = B * Hkv
     cfg = kq.KvqConfig(L, B, 40, Hkv, T, page_tokens=P)
@@ -178,7 +178,7 @@ def int16_tier(kq, torch, kvq_synth):
     K, V = kvq_synth.make_kv(7, 0, B, Hkv, 0, Tb + W)
     Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
     q = torch.from_numpy(kvq_synth.make_q(7, 0, B, Hq, Tb + W - 1)).cuda()
-    cfg = kq.KvqConfig(L, B, Hq, Hkv, Tb + W, page_tokens=P, policy=kq.KVQ_POLICY_OLDEST_FIRST)
+    cfg = kq.KvqConfig(L, B, Hq, Hkv, Tb + W + 64, page_tokens=P, policy=kq.KVQ_POLICY_OLDEST_FIRST)
     res, built = {}, {}
     for name, tier in (("fp16_window", kq.KVQ_TIER16_FP16), ("int16_window", kq.KVQ_TIER16_INT16)):
         arena = torch.empty(kq.kvq_arena_bytes(cfg, int(L * units * (Tb * 160 + W * 544) * 1.1) + (64 << 20)),
@@ -205,6 +205,23 @@ def int16_tier(kq, torch, kvq_synth):
     for name, (cache, _, o) in built.items():
         nbytes = cache.kvq_cache_describe(0)[1]
         res[name] = {"us_per_launch": round(best[name] * 1e3, 2), "GBps": round(nbytes / best[name] / 1e6, 1), "out": o.clone()}
+    # the whole decode step of a block (one new token + attention, kvq_append_decode_attention: one launch in both tiers)
+    k1, v1 = Kd[:, :, :1].contiguous(), Vd[:, :, :1].contiguous()
+    step = {name: 1e9 for name in built}
+    for rnd in range(3):
+        for name, (cache, _, o) in built.items():
+            trains = []
+            for rep in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for layer in range(L):
+                    cache.kvq_append_decode_attention(layer, k1, v1, q, o)
+                e1.record()
+                trains.append((e0, e1))
+            torch.cuda.synchronize()
+            step[name] = min(step[name], min(a.elapsed_time(b) for a, b in trains[1:]) / L)
+    for name, (cache, _, o) in built.items():
+        res[name]["step_us_per_block"] = round(step[name] * 1e3, 2)
         cache.close()
     del built
     a, b = res["fp16_window"].pop("out"), res["int16_window"].pop("out")

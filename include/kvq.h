@@ -143,11 +143,11 @@ kvq_status_t kvq_decode_attention(kvq_cache_t* cache, int32_t layer, const void*
 
 /* One decode step of a block in one launch: kvq_quantize_append_rope of one token (n_new = 1, entry_bits = 0; k_dev,
  * v_dev: fp16 [batch, n_kv_heads, 1, 128]; cos_sin_dev: fp32 [1][128] or NULL for keys that already carry RoPE)
- * followed by kvq_decode_attention over the block including that token.  When the token enters the raw fp16 tier
+ * followed by kvq_decode_attention over the block including that token.  When the token enters the 16-bit tier
  * (a window is configured, the policy is OLDEST_FIRST, or the block is still at 16 bits) it is written by the attention
  * kernel itself - by the workgroup that owns the last tile, which reads it back only after its stores have
- * completed - so the small append launch and its gap disappear; otherwise the two kernels are launched one after the
- * other.  Bookkeeping, budget check, page allocation and window evictions are those of kvq_quantize_append; the
+ * completed; with KVQ_TIER16_INT16 that workgroup quantizes it (Eq. 1-2, 2^16 - 1 levels) - so the small append launch
+ * and its gap disappear; otherwise the two kernels are launched one after the other.  Bookkeeping, budget check, page allocation and window evictions are those of kvq_quantize_append; the
  * cache contents afterwards are bit-identical to the two separate calls, the outputs equal up to summation order.
  * Errors of the append part leave the cache unchanged and nothing is computed. */
 kvq_status_t kvq_append_decode_attention(kvq_cache_t* cache, int32_t layer, const void* k_dev, const void* v_dev,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvq.so")
-SOURCES = ["kvq_host.cpp", "kvq_quant.hip", "kvq_attention.hip", "kvq_attention_batch.hip"]
+SOURCES = ["kvq_host.cpp", "kvq_quant.hip", "kvq_attention.hip", "kvq_attention_batch.hip", "kvq_attention_i16_append.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-fhip-fp32-correctly-rounded-divide-sqrt", "-ffp-contract=on",

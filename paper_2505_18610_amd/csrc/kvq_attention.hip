@@ -47,7 +47,8 @@ hipError_t kvq_launch_merge(const KvqAttnParams& p, int units, hipStream_t s) {
 }
 
 hipError_t kvq_launch_attention(const KvqAttnParams& p, int units, hipStream_t s) {
-    if (p.int16_tier) hipLaunchKernelGGL(kvq_attention_i16_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
+    if (p.int16_tier && p.app_t_old >= 0) { hipError_t e0 = kvq_launch_attention_i16_append(p, units, s); if (e0 != hipSuccess) return e0; }
+    else if (p.int16_tier) hipLaunchKernelGGL(kvq_attention_i16_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
     else if (p.app_t_old >= 0) hipLaunchKernelGGL(kvq_attention_append_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
     else hipLaunchKernelGGL(kvq_attention_kernel, dim3(p.n_splits, units), dim3(KVQ_ATTN_THREADS), 0, s, p);
     hipError_t e = hipGetLastError();

@@ -20,6 +20,9 @@
 
 #include "kvq_internal.h"
 #include "kvq_append16.h"
+#ifdef KVQ_WITH_I16_APPEND
+#include "kvq_quant_dev.h"
+#endif
 
 namespace {
 
@@ -909,10 +912,24 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
         uint8_t* code = const_cast<uint8_t*>(P.arena) + (uint64_t)P.app_desc.code_off256 * 256u + tslot * 2 * (512u * 16);
         const uint16_t* in_k = static_cast<const uint16_t*>(P.app_k) + (size_t)unit * KVQ_D;
         const uint16_t* in_v = static_cast<const uint16_t*>(P.app_v) + (size_t)unit * KVQ_D;
-        kvq_dev::append16_tile(code, in_k, 0, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1, lane, P.app_rope,
-                               P.app_rinv ? P.app_rinv + hk * KVQ_D : nullptr);
-        kvq_dev::append16_tile(code + 512u * 16, in_v, 1, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1, lane,
-                               nullptr, nullptr);
+#ifdef KVQ_WITH_I16_APPEND
+        if constexpr (I16) {  // integer tier: the token is quantized (Eq. 1-2, 2^16 - 1 levels); the reduction slab is free
+            uint8_t* meta = const_cast<uint8_t*>(P.arena) + (uint64_t)P.app_desc.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
+            uint8_t* lds0 = reinterpret_cast<uint8_t*>(&red_o[0][0]);
+            uint8_t* lds1 = lds0 + KVQ_LDS_CODES;
+            kvq_q::append_i16_string(lds0, lds1, code, meta, in_k, 0, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1,
+                                     P.app_gspan, P.app_rope, P.app_rinv ? P.app_rinv + hk * KVQ_D : nullptr, lane);
+            kvq_q::wave_sync_lds();
+            kvq_q::append_i16_string(lds0, lds1, code + 512u * 16, meta, in_v, 1, tile_new * KVQ_TILE_TOKENS, P.app_t_old,
+                                     P.app_t_old + 1, P.app_gspan, nullptr, nullptr, lane);
+        } else
+#endif
+        {
+            kvq_dev::append16_tile(code, in_k, 0, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1, lane, P.app_rope,
+                                   P.app_rinv ? P.app_rinv + hk * KVQ_D : nullptr);
+            kvq_dev::append16_tile(code + 512u * 16, in_v, 1, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1, lane,
+                                   nullptr, nullptr);
+        }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     KVQ_STAMP(1);

@@ -461,6 +461,7 @@ namespace {
 
 // What a deferred single-token append into the 16-bit tier leaves for the attention launch to do.
 struct DeferredAppend {
+    bool int16_too = false;  // in: the attention launch that follows can also append into the integer 16-bit tier
     bool active = false;
     int t_old = 0;
     KvqPageDesc desc{};
@@ -520,7 +521,7 @@ bool append_args_ok(const kvq_cache_t* c, int32_t layer, const void* k_dev, cons
     return true;
 }
 
-// Carries a planned append out.  defer != nullptr: a one-token append into the raw fp16 tier is not launched but
+// Carries a planned append out.  defer != nullptr: a one-token append into the 16-bit tier is not launched but
 // described in *defer (page allocation, table upload and window evictions happen as usual).
 kvq_status_t commit_append(kvq_cache_t* c, int32_t layer, const AppendPlan& pl, const void* k_dev, const void* v_dev,
                            int32_t n_new, const float* cos_sin_dev, hipStream_t s, DeferredAppend* defer) {
@@ -554,7 +555,7 @@ kvq_status_t commit_append(kvq_cache_t* c, int32_t layer, const AppendPlan& pl, 
     L.version++;
     st = upload_table(c, layer, (int)old_pages, (int)L.pages.size(), s);
     if (st != KVQ_OK) return st;
-    if (!c->dry && defer && n_new == 1 && e == 16 && !c->int16()) {
+    if (!c->dry && defer && n_new == 1 && e == 16 && (!c->int16() || defer->int16_too)) {
         defer->active = true;
         defer->t_old = t_old;
         defer->desc = c->desc(L.pages[(size_t)(t_old / P)]);
@@ -740,6 +741,7 @@ kvq_status_t fill_attn_params(kvq_cache_t* c, int32_t layer, const void* q_dev, 
         p.app_rope = cos_sin_dev;
         p.app_rinv = L.reparam ? c->lambda_dev(layer) + c->cfg.n_kv_heads * KVQ_D : nullptr;
     }
+    p.app_gspan = c->cfg.group / 32;
     return KVQ_OK;
 }
 
@@ -859,6 +861,7 @@ kvq_status_t kvq_append_decode_attention(kvq_cache_t* c, int32_t layer, const vo
     if (!q_dev || !out_dev) return KVQ_E_INVALID;  // nothing may be appended when the attention cannot follow
     if (c && c->dry) return KVQ_E_STATE;
     DeferredAppend app;
+    app.int16_too = true;
     kvq_status_t st = append_impl(c, layer, k_dev, v_dev, 1, 0, cos_sin_dev, hip_stream, &app);
     if (st != KVQ_OK) return st;
     return attention_impl(c, layer, q_dev, out_dev, out_is_fp32, softmax_scale, hip_stream, &app, k_dev, v_dev, cos_sin_dev);

@@ -52,6 +52,7 @@ struct KvqAttnParams {
     const void* app_v;
     const float* app_rope;     // [1][128] cos | sin of the new position, or null
     const float* app_rinv;     // [n_kv_heads][128] reciprocal reparameterization factors, or null
+    int32_t app_gspan;         // quantization group / 32 (integer 16-bit tier: the new token is quantized, Eq. 1-2)
 };
 
 // kvq_quant.hip
@@ -85,6 +86,7 @@ struct KvqBatchMap {
 // kvq_attention.hip
 hipError_t kvq_launch_attention(const KvqAttnParams& p, int units, hipStream_t s);
 hipError_t kvq_launch_merge(const KvqAttnParams& p, int units, hipStream_t s);
+hipError_t kvq_launch_attention_i16_append(const KvqAttnParams& p, int units, hipStream_t s);  // kernel only, no merge
 // kvq_attention_batch.hip: the bare kernel launch kvq_launch_attention_batch wraps
 hipError_t kvq_launch_attention_batch_kernel(const KvqAttnParams* params_dev, const KvqBatchMap& map, bool int16,
                                              hipStream_t s);

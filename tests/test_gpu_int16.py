@@ -153,3 +153,56 @@ def test_int16_with_rope_and_reparameterization():
         t += n
     assert_same_cache(oc, gc, 0)
     check_attention(oc, gc, 0, kvq_synth.make_q(340, 0, B, 2 * H, T - 1))
+
+
+@pytest.mark.parametrize("P,W,splits,det,extras,group", [(64, 64, 0, 0, False, 32), (96, 96, 1, 0, False, 32),
+                                                         (32, 32, 3, 1, False, 64), (64, 128, 0, 0, True, 128)])
+def test_int16_fused_append_and_attention_step(P, W, splits, det, extras, group):
+    """kvq_append_decode_attention on a cache with the integer 16-bit tier: the attention launch itself quantizes the new
+    token into the tile's byte planes (Eq. 1-2 with 2^16 - 1 levels).  Against the two separate calls and the oracle over
+    a decode loop that crosses tile and page boundaries and evicts window pages down the shift chain: identical cache
+    contents, outputs within the tolerance.  Variants as for the raw fp16 tier, plus groups of 64 and 128 channels."""
+    from oracle import rope_rotate_keys, calibrate_lambda
+    B, H, g, T0, steps = 2, 2, 3, P + W + 29, 2 * P + 9
+    budget = B * H * (T0 + steps + 2 * P) * 544
+    K, V = kvq_synth.make_kv(190, 0, B, H, 0, T0 + steps, rope_base=None if extras else 1.0e6)
+    cos, sin = kvq_synth.rope_tables(np.arange(T0 + steps), 1.0e6)
+    Kin = rope_rotate_keys(K, cos, sin) if extras else K
+    cs = dev(np.concatenate([cos, sin], 1))
+    lam = calibrate_lambda(Kin[:, :, :64], 0.5) if extras else None
+    caches = []
+    for _ in range(2):
+        oc, gc = make_pair(1, B, H * g, H, T0 + steps + P, P, budgets=[budget], fbits=[2], window=W, group=group,
+                           tier16=TIER16_INT16)
+        if extras:
+            oc.set_reparam(0, lam)
+            gc.kvq_cache_set_reparam(0, dev(lam))
+        gc.kvq_cache_set_option(kq.KVQ_OPT_SPLITS, splits)
+        gc.kvq_cache_set_option(kq.KVQ_OPT_DETERMINISTIC, det)
+        oc.append(0, Kin[:, :, :T0], V[:, :, :T0])
+        gc.kvq_quantize_append(0, dev(Kin[:, :, :T0]), dev(V[:, :, :T0]))
+        assert gc.kvq_progressive_requant(0) == oc.requant(0)
+        caches.append((oc, gc))
+    (oc, plain), (_, fused) = caches
+    out_p = torch.empty((B, H * g, 128), dtype=torch.float32, device="cuda")
+    out_f = torch.empty_like(out_p)
+    for i in range(steps):
+        t = T0 + i
+        q = kvq_synth.make_q(190, 0, B, H * g, t)
+        k1, v1 = dev(Kin[:, :, t:t + 1]), dev(V[:, :, t:t + 1])
+        oc.append(0, Kin[:, :, t:t + 1], V[:, :, t:t + 1])
+        plain.kvq_quantize_append(0, k1, v1)
+        plain.kvq_decode_attention(0, dev(q), out_p)
+        if extras:
+            fused.kvq_append_decode_attention(0, dev(K[:, :, t:t + 1]), v1, dev(q), out_f, cos_sin=cs[t:t + 1].contiguous())
+        else:
+            fused.kvq_append_decode_attention(0, k1, v1, dev(q), out_f)
+        torch.cuda.synchronize()
+        a, b = out_p.cpu().numpy(), out_f.cpu().numpy()
+        assert np.abs(a - b).max() <= 1e-3, (i, np.abs(a - b).max())
+        if i % 23 == 0 or i == steps - 1 or (t + 1) % P in (0, 1):
+            mx, rl = attention_errors(b, oc.attention(0, q))
+            assert mx <= MAX_ABS and rl <= REL_L2, (i, mx, rl)
+            assert_same_cache(oc, fused, 0)
+    assert_same_cache(oc, plain, 0)
+    assert any(bits == 8 for _, _, bits in fused.kvq_cache_describe(0)[0])
