@@ -915,13 +915,12 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
 #ifdef KVQ_WITH_I16_APPEND
         if constexpr (I16) {  // integer tier: the token is quantized (Eq. 1-2, 2^16 - 1 levels); the reduction slab is free
             uint8_t* meta = const_cast<uint8_t*>(P.arena) + (uint64_t)P.app_desc.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
-            uint8_t* lds0 = reinterpret_cast<uint8_t*>(&red_o[0][0]);
-            uint8_t* lds1 = lds0 + KVQ_LDS_CODES;
-            kvq_q::append_i16_string(lds0, lds1, code, meta, in_k, 0, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1,
-                                     P.app_gspan, P.app_rope, P.app_rinv ? P.app_rinv + hk * KVQ_D : nullptr, lane);
+            auto& lds = *reinterpret_cast<uint8_t (*)[2][KVQ_LDS_CODES]>(&red_o[0][0]);
+            kvq_q::append_i16_string(lds, code, meta, in_k, 0, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1,
+                                     P.app_gspan, P.app_rope, P.app_rinv, hk, lane);
             kvq_q::wave_sync_lds();
-            kvq_q::append_i16_string(lds0, lds1, code + 512u * 16, meta, in_v, 1, tile_new * KVQ_TILE_TOKENS, P.app_t_old,
-                                     P.app_t_old + 1, P.app_gspan, nullptr, nullptr, lane);
+            kvq_q::append_i16_string(lds, code + 512u * 16, meta, in_v, 1, tile_new * KVQ_TILE_TOKENS, P.app_t_old,
+                                     P.app_t_old + 1, P.app_gspan, nullptr, nullptr, 0, lane);
         } else
 #endif
         {

@@ -105,7 +105,10 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
     store_chunks<B>(code, lane, str);
 }
 
-// Append into the integer 16-bit tier (append_i16_string): grid as above.
+// Append into the integer 16-bit tier: Eq. 1-2 with 2^16 - 1 levels by the same owner lanes; the high and the low
+// bytes of the codes then travel through LDS and into the tile's two byte planes like two 8-bit tiles.
+// (The same steps as kvq_q::append_i16_string, which the attention kernel uses for its fused one-token append, written
+// out here: as a call of that function this kernel measured 15 % slower on bulk appends, forced inlining or not.)
 __global__ __launch_bounds__(64) void kvq_append_i16_kernel(uint8_t* __restrict__ arena,
                                                             const KvqPageDesc* __restrict__ table,
                                                             const uint16_t* __restrict__ k_in,
@@ -114,7 +117,7 @@ __global__ __launch_bounds__(64) void kvq_append_i16_kernel(uint8_t* __restrict_
                                                             int gspan, const float* __restrict__ rinv,
                                                             int n_kv_heads, const float* __restrict__ rope) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[2][KVQ_LDS_CODES];
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
     const int tile = tile0 + (blockIdx.x >> 1);
     const int unit = blockIdx.y;
@@ -123,11 +126,76 @@ __global__ __launch_bounds__(64) void kvq_append_i16_kernel(uint8_t* __restrict_
     const uint64_t tslot = (uint64_t)unit * tpp + tip;
     uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * 16);
     uint8_t* meta = arena + (uint64_t)pd.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
+    const int t_new = t_old + n_new, tok0 = tile * KVQ_TILE_TOKENS;
     const uint16_t* in = (which ? v_in : k_in) + (uint64_t)unit * n_new * KVQ_D;
-    append_i16_string(lds[0], lds[1], code, meta, in, which, tile * KVQ_TILE_TOKENS, t_old, t_old + n_new, gspan, rope,
-                      rinv ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr, lane);
+    const int grp = lane & 3;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tl = 16 * pass + (lane >> 2);
+        const int tok = tok0 + tl;
+        const bool isnew = tok >= t_old && tok < t_new;
+        uint32_t w[16];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (isnew) {
+                const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
+                if (which) v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
+                else v = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr,
+                                   rinv ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
+            }
+            w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+        }
+        float codes[32], lo[32];
+        uint16_t S, Z;
+        quantize_owner<16>(w, codes, &S, &Z, gspan);
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {  // exact: integers below 2^16
+            const float hi = floorf(codes[e] * 0.00390625f);
+            lo[e] = codes[e] - 256.0f * hi;
+            codes[e] = hi;
+        }
+        scatter_codes(lds[0], which, tl, grp, codes);
+        scatter_codes(lds[1], which, tl, grp, lo);
+        if (tok >= t_old) store_meta_owner(meta, which, tl, grp, S, Z);
+    }
+    wave_sync_lds();
+    uint32_t keep = 0;  // stored tokens keep their bits
+    if (!which) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+            if (tok0 + 8 * (n >> 2) + 4 * sub + (n & 3) < t_old) keep |= 1u << sub;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (tok0 + 8 * j + i < t_old) keep |= 1u << i;
+    }
+#pragma unroll
+    for (int plane = 0; plane < 2; ++plane) {
+        uint32_t str[16];
+        gather_string<8>(lds[plane], which, lane, str);
+        uint8_t* dst = code + plane * (512u * 8);
+        if (tok0 < t_old && keep) {
+            uint32_t old[16];
+            load_chunks<8>(dst, lane, old);
+#pragma unroll
+            for (int d = 0; d < 16; ++d) {
+                uint32_t m = which ? v_token_mask<8>(keep, d) : (((keep >> (d / 8)) & 1u) ? 0xffffffffu : 0u);
+                str[d] = (old[d] & m) | (str[d] & ~m);
+            }
+        }
+        store_chunks<8>(dst, lane, str);
+    }
 }
 
+// ------------------------------------------------------------------------------------- fp16 page -> b bits
+// grid.x = 2 * n_jobs * tiles_per_page, grid.y = unit, 64 threads.  Direct quantization (Eq. 1-2) of a page
+// that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by
+// owner lanes exactly like an append.
+// ------------------------------------------------------------------------------------- fp16 page -> b bits
+// grid.x = 2 * n_jobs * tiles_per_page, grid.y = unit, 64 threads.  Direct quantization (Eq. 1-2) of a page
+// that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by
+// owner lanes exactly like an append.
 // ------------------------------------------------------------------------------------- fp16 page -> b bits
 // grid.x = 2 * n_jobs * tiles_per_page, grid.y = unit, 64 threads.  Direct quantization (Eq. 1-2) of a page
 // that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by

@@ -255,11 +255,13 @@ __device__ inline KvqPageDesc append_desc(const KvqPageDesc* table, const KvqApp
 // LDS into the tile's two byte planes like two 8-bit tiles, tokens stored earlier keep their bits.  One wavefront.
 //   code: the string (its high-byte plane; the low-byte plane follows), meta: the tile's metadata,
 //   in: fp16 rows [t_new - t_old][128] of this (sequence, KV head), tok0: first token of the tile,
-//   rope: [t_new - t_old][128] cos | sin rows or null, rinv: this KV head's reciprocal reparameterization factors or null,
-//   lds0, lds1: KVQ_LDS_CODES bytes each, used by this wavefront alone.
-__device__ inline void append_i16_string(uint8_t* lds0, uint8_t* lds1, uint8_t* code, uint8_t* meta, const uint16_t* in,
-                                         int which, int tok0, int t_old, int t_new, int gspan, const float* rope,
-                                         const float* rinv, int lane) {
+//   rope: [t_new - t_old][128] cos | sin rows or null, rinv: [n_kv_heads][128] reciprocal reparameterization factors or
+//   null, head: this unit's KV head,
+//   lds: scratch of this wavefront alone.
+__device__ __forceinline__ void append_i16_string(uint8_t (&lds)[2][KVQ_LDS_CODES], uint8_t* __restrict__ code,
+                                         uint8_t* __restrict__ meta, const uint16_t* __restrict__ in, int which, int tok0,
+                                         int t_old, int t_new, int gspan, const float* __restrict__ rope,
+                                         const float* __restrict__ rinv, int head, int lane) {
     const int j = lane >> 4, n = lane & 15;
     const int grp = lane & 3;
 #pragma unroll
@@ -274,28 +276,22 @@ __device__ inline void append_i16_string(uint8_t* lds0, uint8_t* lds1, uint8_t* 
             if (isnew) {
                 const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
                 if (which) v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
-                else v = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr, rinv);
+                else v = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr,
+                                   rinv ? rinv + head * KVQ_D : nullptr);
             }
             w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
         }
         float codes[32], lo[32];
-        uint16_t S = 0, Z = 0;
-        // (a pass none of whose 16 tokens is new -- one of the two when a single token is appended -- has nothing to
-        //  quantize: all-zero rows give S = Z = 0 and codes 0)
-        if (tok0 + 16 * pass < t_new && tok0 + 16 * pass + 16 > t_old) {
-            quantize_owner<16>(w, codes, &S, &Z, gspan);
+        uint16_t S, Z;
+        quantize_owner<16>(w, codes, &S, &Z, gspan);
 #pragma unroll
-            for (int e = 0; e < 32; ++e) {  // exact: integers below 2^16
-                const float hi = floorf(codes[e] * 0.00390625f);
-                lo[e] = codes[e] - 256.0f * hi;
-                codes[e] = hi;
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 32; ++e) codes[e] = lo[e] = 0.0f;
+        for (int e = 0; e < 32; ++e) {  // exact: integers below 2^16
+            const float hi = floorf(codes[e] * 0.00390625f);
+            lo[e] = codes[e] - 256.0f * hi;
+            codes[e] = hi;
         }
-        scatter_codes(lds0, which, tl, grp, codes);
-        scatter_codes(lds1, which, tl, grp, lo);
+        scatter_codes(lds[0], which, tl, grp, codes);
+        scatter_codes(lds[1], which, tl, grp, lo);
         if (tok >= t_old) store_meta_owner(meta, which, tl, grp, S, Z);
     }
     wave_sync_lds();
@@ -312,7 +308,7 @@ __device__ inline void append_i16_string(uint8_t* lds0, uint8_t* lds1, uint8_t* 
 #pragma unroll
     for (int plane = 0; plane < 2; ++plane) {
         uint32_t str[16];
-        gather_string<8>(plane ? lds1 : lds0, which, lane, str);
+        gather_string<8>(lds[plane], which, lane, str);
         uint8_t* dst = code + plane * (512u * 8);
         if (tok0 < t_old && keep) {
             uint32_t old[16];
