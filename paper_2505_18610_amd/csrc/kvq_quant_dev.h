@@ -252,7 +252,9 @@ __device__ inline KvqPageDesc append_desc(const KvqPageDesc* table, const KvqApp
 
 // Appends the tokens [t_old, t_new) that fall into one tile of the integer 16-bit tier to its K (which = 0) or V (1)
 // string: Eq. 1-2 with 2^16 - 1 levels by the owner lanes; the high and the low bytes of the codes then travel through
-// LDS into the tile's two byte planes like two 8-bit tiles, tokens stored earlier keep their bits.  One wavefront.
+// LDS into the tile's two byte planes like two 8-bit tiles.  A tile that already holds tokens gets the bytes of the new
+// tokens only (the append that started the tile has zeroed the slots and the metadata of the tokens to come); a new
+// tile is written whole.  One wavefront.
 //   code: the string (its high-byte plane; the low-byte plane follows), meta: the tile's metadata,
 //   in: fp16 rows [t_new - t_old][128] of this (sequence, KV head), tok0: first token of the tile,
 //   rope: [t_new - t_old][128] cos | sin rows or null, rinv: [n_kv_heads][128] reciprocal reparameterization factors or
@@ -295,31 +297,36 @@ __device__ __forceinline__ void append_i16_string(uint8_t (&lds)[2][KVQ_LDS_CODE
         if (tok >= t_old) store_meta_owner(meta, which, tl, grp, S, Z);
     }
     wave_sync_lds();
-    uint32_t keep = 0;  // stored tokens keep their bits
-    if (!which) {
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-            if (tok0 + 8 * (n >> 2) + 4 * sub + (n & 3) < t_old) keep |= 1u << sub;
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if (tok0 + 8 * j + i < t_old) keep |= 1u << i;
-    }
+    const bool has_old = tok0 < t_old;  // then only the bytes of the new tokens are stored: nothing is read back
 #pragma unroll
     for (int plane = 0; plane < 2; ++plane) {
         uint32_t str[16];
         gather_string<8>(lds[plane], which, lane, str);
         uint8_t* dst = code + plane * (512u * 8);
-        if (tok0 < t_old && keep) {
-            uint32_t old[16];
-            load_chunks<8>(dst, lane, old);
+        if (!has_old) {
+            store_chunks<8>(dst, lane, str);
+        } else if (!which) {  // K: dwords 8 sub .. 8 sub + 7 of a lane are one token
 #pragma unroll
-            for (int d = 0; d < 16; ++d) {
-                uint32_t m = which ? v_token_mask<8>(keep, d) : (((keep >> (d / 8)) & 1u) ? 0xffffffffu : 0u);
-                str[d] = (old[d] & m) | (str[d] & ~m);
+            for (int sub = 0; sub < 2; ++sub) {
+                const int tok = tok0 + 8 * (n >> 2) + 4 * sub + (n & 3);
+                if (tok >= t_old && tok < t_new) {
+#pragma unroll
+                    for (int c = 2 * sub; c < 2 * sub + 2; ++c)
+                        *reinterpret_cast<u32x4*>(dst + (c * 64 + lane) * 16) =
+                            u32x4{str[4 * c], str[4 * c + 1], str[4 * c + 2], str[4 * c + 3]};
+                }
+            }
+        } else {              // V: slot 4 d + e of a lane is token 8 j + ((4 d + e) & 7)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int tok = tok0 + 8 * j + i;
+                if (tok >= t_old && tok < t_new) {
+#pragma unroll
+                    for (int d = (i >> 2); d < 16; d += 2)
+                        dst[((d >> 2) * 64 + lane) * 16 + (d & 3) * 4 + (i & 3)] = (uint8_t)(str[d] >> (8 * (i & 3)));
+                }
             }
         }
-        store_chunks<8>(dst, lane, str);
     }
 }
 
