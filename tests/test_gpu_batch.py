@@ -170,3 +170,39 @@ def test_full_size_ragged_batch_sampled_sequences():
             assert_same_cache(oc, caches[i], 0)
     for c in caches:
         c.close()
+
+
+def test_maximum_batch_of_64_caches():
+    """The largest batch the entry points take: 64 caches (1 or 2 sequences each, 2 KV heads) of 1 ... ~700 tokens in
+    every mix of widths, three decode steps in one launch each; every cache stays bit-identical to its oracle and every
+    output within the tolerance.  A 65th cache is refused before anything changes."""
+    Hq, Hkv, n = 6, 2, 64
+    rng = np.random.default_rng(64)
+    built = []
+    for i in range(n):
+        B, P = int(rng.choice([1, 2])), int(rng.choice([32, 64]))
+        tiers = []
+        for bits in (2, 4, 8):
+            if rng.random() < 0.5:
+                tiers.append((P * int(rng.integers(1, 5)), bits))
+        tiers.append((int(rng.integers(1, 2 * P)), 16))
+        built.append(_build((B, P, 600 + i, tuple(tiers), 0), Hq, Hkv) + (B,))
+    ocs, gcs = [b[0] for b in built], [b[1] for b in built]
+    outs = [torch.empty((b[5], Hq, 128), dtype=torch.float32, device="cuda") for b in built]
+    for step in range(3):
+        ks = [b[2][:, :, b[4] + step:b[4] + step + 1] for b in built]
+        vs = [b[3][:, :, b[4] + step:b[4] + step + 1] for b in built]
+        qs = [kvq_synth.make_q(600 + i, 0, b[5], Hq, b[4] + step) for i, b in enumerate(built)]
+        want = decode_step_batch(ocs, 0, ks, vs, qs)
+        kq.kvq_append_decode_attention_batch(gcs, 0, [dev(k) for k in ks], [dev(v) for v in vs], [dev(q) for q in qs], outs)
+        torch.cuda.synchronize()
+        for i in range(n):
+            mx, rl = attention_errors(outs[i].cpu().numpy(), want[i])
+            assert mx <= MAX_ABS and rl <= REL_L2, (step, i, mx, rl)
+    for oc, gc in zip(ocs, gcs):
+        assert_same_cache(oc, gc, 0)
+    extra = _build((1, 32, 699, ((5, 16),), 0), Hq, Hkv)
+    q65 = [dev(kvq_synth.make_q(1, 0, o.shape[0], Hq, 0)) for o in outs] + [dev(kvq_synth.make_q(1, 0, 1, Hq, 0))]
+    with pytest.raises(kq.KvqError) as e:
+        kq.kvq_decode_attention_batch(gcs + [extra[1]], 0, q65, outs + [torch.empty((1, Hq, 128), dtype=torch.float32, device="cuda")])
+    assert e.value.status == kq.KVQ_E_INVALID
