@@ -41,7 +41,8 @@ typedef enum {
     KVQ_E_OOM = 3,     /* the arena has no free block of the needed size                                  */
     KVQ_E_STATE = 4,   /* the call does not fit the cache state (width change inside a page, max_tokens   */
                        /* exceeded, no such segment, compute call on an accounting-only cache)            */
-    KVQ_E_HIP = 5      /* a HIP runtime call or kernel launch failed                                      */
+    KVQ_E_HIP = 5,     /* a HIP runtime call or kernel launch failed                                      */
+    KVQ_E_LIMIT = 6    /* kvq_decode_attention_static: the launch needs more than the library's static scratch */
 } kvq_status_t;
 
 enum { KVQ_POLICY_PAPER = 0, KVQ_POLICY_OLDEST_FIRST = 1 };
@@ -140,6 +141,19 @@ kvq_status_t kvq_progressive_requant(kvq_cache_t* cache, int32_t layer, int32_t 
  *   else fp16; softmax_scale 0 means 1/sqrt(head_dim).  KVQ_E_STATE if the block is empty. */
 kvq_status_t kvq_decode_attention(kvq_cache_t* cache, int32_t layer, const void* q_dev, void* out_dev,
                                   int32_t out_is_fp32, float softmax_scale, void* hip_stream);
+
+/* kvq_decode_attention for callers that cannot allocate device memory or hand over a workspace at call time -- code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result (to
+ * floating-point summation order), same kernels; the split partials and arrival counters of the launch live in a
+ * static array of the library's device image (4,276,224 bytes per GPU, held until the process ends) instead of the
+ * arena.  The call allocates nothing and frees nothing on host-visible HIP interfaces: it looks the array's device
+ * address up once per device (first call on that device), clears the counters with a small fill kernel and launches.
+ * Limits: batch * n_kv_heads * splits <= 512 workgroups and batch * n_kv_heads <= 4096, else KVQ_E_LIMIT and nothing is
+ * enqueued (the automatic split count never exceeds one workgroup per compute unit; KVQ_OPT_SPLITS can).
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different streams, or
+ * different caches on different streams) race; issue them on one stream. */
+kvq_status_t kvq_decode_attention_static(kvq_cache_t* cache, int32_t layer, const void* q_dev, void* out_dev,
+                                         int32_t out_is_fp32, float softmax_scale, void* hip_stream);
 
 /* One decode step of a block in one launch: kvq_quantize_append_rope of one token (n_new = 1, entry_bits = 0; k_dev,
  * v_dev: fp16 [batch, n_kv_heads, 1, 128]; cos_sin_dev: fp32 [1][128] or NULL for keys that already carry RoPE)

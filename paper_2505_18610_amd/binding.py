@@ -6,7 +6,7 @@ import os
 
 import numpy as np
 
-KVQ_OK, KVQ_E_INVALID, KVQ_E_BUDGET, KVQ_E_OOM, KVQ_E_STATE, KVQ_E_HIP = range(6)
+KVQ_OK, KVQ_E_INVALID, KVQ_E_BUDGET, KVQ_E_OOM, KVQ_E_STATE, KVQ_E_HIP, KVQ_E_LIMIT = range(7)
 KVQ_POLICY_PAPER, KVQ_POLICY_OLDEST_FIRST = 0, 1
 KVQ_WHICH_K, KVQ_WHICH_V = 0, 1
 KVQ_OPT_SPLITS, KVQ_OPT_FUSED_MERGE, KVQ_OPT_DETERMINISTIC = 0, 1, 2
@@ -56,6 +56,8 @@ _SIGNATURES = {
                                            C.c_void_p, C.c_void_p]),
     "kvq_progressive_requant": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_int32)]),
     "kvq_decode_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]),
+    "kvq_decode_attention_static": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float,
+                                              C.c_void_p]),
     "kvq_append_decode_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_int32, C.c_float, C.c_void_p]),
     "kvq_decode_attention_batch": (C.c_int, [C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.POINTER(C.c_void_p),
@@ -246,6 +248,12 @@ class KvqCache:
         out_is_fp32 = 1 if out.dtype.itemsize == 4 else 0
         self._check(self.lib.kvq_decode_attention(self.handle, layer, _ptr(q), _ptr(out), out_is_fp32,
                                                   float(softmax_scale), _stream(stream)), "kvq_decode_attention")
+
+    def kvq_decode_attention_static(self, layer, q, out, softmax_scale=0.0, stream=None):
+        out_is_fp32 = 1 if out.dtype.itemsize == 4 else 0
+        self._check(self.lib.kvq_decode_attention_static(self.handle, layer, _ptr(q), _ptr(out), out_is_fp32,
+                                                         float(softmax_scale), _stream(stream)),
+                    "kvq_decode_attention_static")
 
     def kvq_append_decode_attention(self, layer, k, v, q, out, cos_sin=None, softmax_scale=0.0, stream=None):
         out_is_fp32 = 1 if out.dtype.itemsize == 4 else 0

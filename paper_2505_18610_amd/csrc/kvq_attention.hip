@@ -4,7 +4,19 @@
 // they do not change the inlining and register allocation of these.
 #include "kvq_attention_body.h"
 
+#include <mutex>
+
 namespace {
+
+// Scratch of kvq_decode_attention_static: split partials, (max, sum) pairs and arrival counters in the device image
+// of this library instead of the caller's arena, for callers that cannot allocate.  Every GPU the library runs on
+// holds its own copy until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[KVQ_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device, looked up once
 
 // grid = (splits, units); 512 threads = 8 wavefronts, one workgroup per compute unit.
 __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_attention_kernel(const KvqAttnParams P) {
@@ -40,6 +52,23 @@ extern "C" int kvq_debug_read(unsigned long long* host) {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kvq_dbg), sizeof(unsigned long long) * 1024 * 8);
 }
 #endif
+
+hipError_t kvq_static_scratch(unsigned char** ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 hipError_t kvq_launch_merge(const KvqAttnParams& p, int units, hipStream_t s) {
     hipLaunchKernelGGL(kvq_merge_kernel, dim3(units), dim3(KVQ_ATTN_THREADS), 0, s, p);

@@ -855,6 +855,28 @@ kvq_status_t kvq_decode_attention(kvq_cache_t* c, int32_t layer, const void* q_d
                           nullptr);
 }
 
+kvq_status_t kvq_decode_attention_static(kvq_cache_t* c, int32_t layer, const void* q_dev, void* out_dev,
+                                         int32_t out_is_fp32, float softmax_scale, void* hip_stream) {
+    KvqAttnParams p;
+    kvq_status_t st = fill_attn_params(c, layer, q_dev, out_dev, out_is_fp32, softmax_scale, nullptr, nullptr, nullptr,
+                                       nullptr, 0, p);
+    if (st != KVQ_OK) return st;
+    if (c->units > KVQ_STATIC_MAX_UNITS || (int64_t)c->units * p.n_splits > KVQ_STATIC_MAX_WGS) return KVQ_E_LIMIT;
+    unsigned char* scr = nullptr;
+    if (kvq_static_scratch(&scr) != hipSuccess) return KVQ_E_HIP;
+    hipStream_t s = as_stream(hip_stream);
+    p.part_o = reinterpret_cast<float*>(scr);
+    p.part_ml = reinterpret_cast<float*>(scr + KVQ_STATIC_PART_O_BYTES);
+    p.counters = reinterpret_cast<uint32_t*>(scr + KVQ_STATIC_PART_O_BYTES + KVQ_STATIC_PART_ML_BYTES);
+    // The array keeps what the last call left.  Partials are written before they are read; the arrival counters must
+    // start at zero (a kernel leaves them there, but a launch that failed half-way would not): a fill kernel, which a
+    // caller may also capture into a graph.
+    if (p.n_splits > 1 && p.fused_merge &&
+        kvq_launch_fill_u32(p.counters, 0u, (size_t)c->units, s) != hipSuccess)
+        return KVQ_E_HIP;
+    return kvq_launch_attention(p, c->units, s) == hipSuccess ? KVQ_OK : KVQ_E_HIP;
+}
+
 kvq_status_t kvq_append_decode_attention(kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev,
                                          const float* cos_sin_dev, const void* q_dev, void* out_dev,
                                          int32_t out_is_fp32, float softmax_scale, void* hip_stream) {
@@ -1138,6 +1160,7 @@ const char* kvq_status_string(kvq_status_t s) {
         case KVQ_E_OOM: return "arena out of memory";
         case KVQ_E_STATE: return "call does not fit the cache state";
         case KVQ_E_HIP: return "HIP runtime error";
+        case KVQ_E_LIMIT: return "launch exceeds the static scratch of kvq_decode_attention_static";
     }
     return "unknown status";
 }

@@ -83,6 +83,17 @@ struct KvqBatchMap {
     int32_t wg_begin[KVQ_MAX_BATCH_CACHES + 1];  // first workgroup of every cache; [n] = grid size
 };
 
+// Static scratch of kvq_decode_attention_static (kvq_attention.hip): room for the partials of KVQ_STATIC_MAX_WGS
+// workgroups (units * splits of one launch) and the arrival counters of KVQ_STATIC_MAX_UNITS units.
+#define KVQ_STATIC_MAX_WGS 512
+#define KVQ_STATIC_MAX_UNITS 4096
+#define KVQ_STATIC_PART_O_BYTES ((size_t)KVQ_STATIC_MAX_WGS * 16 * KVQ_D * sizeof(float))
+#define KVQ_STATIC_PART_ML_BYTES ((size_t)KVQ_STATIC_MAX_WGS * 32 * sizeof(float))
+#define KVQ_STATIC_COUNTER_BYTES ((size_t)KVQ_STATIC_MAX_UNITS * sizeof(uint32_t))
+#define KVQ_STATIC_SCRATCH_BYTES (KVQ_STATIC_PART_O_BYTES + KVQ_STATIC_PART_ML_BYTES + KVQ_STATIC_COUNTER_BYTES)
+// Device address of the scratch array on the current device (looked up once per device, no allocation).
+hipError_t kvq_static_scratch(unsigned char** ptr);
+
 // kvq_attention.hip
 hipError_t kvq_launch_attention(const KvqAttnParams& p, int units, hipStream_t s);
 hipError_t kvq_launch_merge(const KvqAttnParams& p, int units, hipStream_t s);
