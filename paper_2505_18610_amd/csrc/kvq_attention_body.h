@@ -240,6 +240,15 @@ struct Stage {
 #define KVQ_ATTN_THREADS 512
 #define KVQ_ATTN_WAVES 8
 #define KVQ_PAD_TOK0 0x3fffff00
+#ifndef KVQ_RING_SINGLE
+#define KVQ_RING_SINGLE 2  // register stages of the single-tile pipelines of the narrow widths
+#endif
+#ifndef KVQ_SKIP_PAD
+#define KVQ_SKIP_PAD 0
+#endif
+#ifndef KVQ_TAIL_SINGLES
+#define KVQ_TAIL_SINGLES 16  // tiles at the end of a workgroup's range that are claimed one at a time
+#endif
 #ifndef KVQ_RING_2BIT
 #define KVQ_RING_2BIT 2   // register stages of the 2-bit pipeline (one less is in flight)
 #endif
@@ -482,27 +491,35 @@ __device__ inline void compute_stage(WaveState& st, const QOps& Q, const Stage<B
     }
     float s[TPI][2][4];
 #pragma unroll
-    for (int k = 0; k < TPI; ++k)
-        scores_tile<B>(Q, sg.kw[k], meta_lds + k * KVQ_META_TILE_BYTES, scale_log2, lane, s[k]);
+    for (int k = 0; k < TPI; ++k) {
+        // a slot that only pads the stage (wavefront-uniform) costs no arithmetic: its scores are masked anyway
+        if (k == 0 || !KVQ_SKIP_PAD || sg.tok0[k] != KVQ_PAD_TOK0) {
+            scores_tile<B>(Q, sg.kw[k], meta_lds + k * KVQ_META_TILE_BYTES, scale_log2, lane, s[k]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[k][e >> 2][e & 3] = -INFINITY;
+        }
+    }
     uint32_t pop[TPI][4];
     softmax_stage<B, TPI>(st, s, sg.tok0, n_tokens, lane, pop);
 #pragma unroll
     for (int k = 0; k < TPI; ++k)
-        accumulate_tile<B, SAFE>(st, sg.vw[k], meta_lds + k * KVQ_META_TILE_BYTES, meta_lds + KVQ_WAVE_LDS_CONST, pop[k], lane);
+        if (k == 0 || !KVQ_SKIP_PAD || sg.tok0[k] != KVQ_PAD_TOK0)
+            accumulate_tile<B, SAFE>(st, sg.vw[k], meta_lds + k * KVQ_META_TILE_BYTES, meta_lds + KVQ_WAVE_LDS_CONST, pop[k], lane);
     if constexpr (B < 16) wave_lds_sync();
 }
 
 // A claimed chunk, resolved to addresses; every member is wavefront-uniform (scalar registers).
 struct Claim {
     int tile;             // first tile
-    int nt;               // tiles (1 .. tpc), adjacent in one page
+    int nt;               // tiles (1 or 2), adjacent in one page
     uint32_t bits;        // width of the page; 0: nothing left in this window
     const uint8_t* code;  // K string of the first tile; its V string follows, then the next tile's pair
     const uint8_t* meta;  // metadata of the first tile; the next tile's follows
 };
 
 // What a wavefront needs to find and claim work inside its workgroup's tile range.  The range is cut into
-// chunks of tpc consecutive tiles (2, or 1 when pages hold an odd number of tiles); the 8 wavefronts of the
+// chunks of two consecutive tiles (one when pages hold an odd number of tiles, and at the end of the range); the 8 wavefronts of the
 // workgroup claim chunks from a counter in LDS, so wavefronts that get more issue slots simply do more chunks.
 //   next      - resolved claim, the chunk whose loads are issued next
 //   claim_v   - result of the claim after it (LDS atomic in flight while a stage is computed)
@@ -517,7 +534,7 @@ struct RunCtx {
     int unit;
     int n_tokens;
     int lo, hi;              // tile range of the current descriptor window
-    int tpc;                 // tiles per chunk
+    int n_pairs;             // chunks 0 .. n_pairs - 1 hold two tiles, the chunks after them one
     int n_chunks;
     int next_static;         // >= 0: deterministic mode, this wavefront takes chunks next_static, + static_stride, ...
     int static_stride;
@@ -547,14 +564,15 @@ __device__ inline int page_of_tile(const RunCtx& c, int tile) {
 __device__ inline void start_desc(RunCtx& c, int chunk) {
     chunk = __builtin_amdgcn_readfirstlane(chunk);
     c.desc_chunk = chunk;
-    const int tile = c.lo + max(0, min(chunk, c.n_chunks - 1)) * c.tpc;  // past the end: any valid slot, ignored later
+    const int cc = max(0, min(chunk, c.n_chunks - 1));  // past the end: any valid slot, ignored later
+    const int tile = c.lo + cc + min(cc, c.n_pairs);
     c.desc_v = c.desc_lds[page_of_tile(c, tile) - c.page0];
 }
 __device__ inline Claim finish_desc(const RunCtx& c) {
     Claim r;
     const int chunk = c.desc_chunk;
-    r.tile = c.lo + chunk * c.tpc;
-    r.nt = min(c.tpc, c.hi - r.tile);
+    r.tile = c.lo + chunk + min(chunk, c.n_pairs);
+    r.nt = min(chunk < c.n_pairs ? 2 : 1, c.hi - r.tile);
     const uint32_t code_off = __builtin_amdgcn_readfirstlane(c.desc_v.x);
     const uint32_t meta_off = __builtin_amdgcn_readfirstlane(c.desc_v.y);
     const uint32_t bits = __builtin_amdgcn_readfirstlane(c.desc_v.z);
@@ -664,7 +682,7 @@ __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds,
         //  graph paths from a step straight back to itself, and the wait counts are derived from that graph)
 #pragma unroll
         for (int i = 1; i + 1 < N; ++i) {  // fill the ring
-            if (c.next.bits != B) goto drain;
+            if (c.next.bits != B || c.next.nt != TPI) goto drain;
             issue_stage<B, TPI>(sg[i], c, c.next);
             n_live = i + 1;
             advance_begin(c);
@@ -673,7 +691,7 @@ __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds,
         for (;;) {
 #pragma unroll
             for (int k = 0; k < N; ++k) {
-                if (c.next.bits != B) { head = k; goto drain; }
+                if (c.next.bits != B || c.next.nt != TPI) { head = k; goto drain; }
                 issue_stage<B, TPI>(sg[(k + N - 1) % N], c, c.next);
                 advance_begin(c);
                 compute_stage<B, TPI, SAFE>(st, Q, sg[k], meta_lds, c.n_tokens, c.scale_log2, lane);
@@ -717,6 +735,31 @@ __device__ inline float2v load_pair(const float* p, bool agent) {  // 8 bytes at
     return *reinterpret_cast<const float2v*>(p);
 }
 
+#define KVQ_DESC_CACHE 256  // page descriptors staged in LDS per chunk of the split's range
+#define KVQ_OPAD 132  // padded row of the LDS reduction slab (floats)
+
+
+// LDS of one workgroup.
+struct AttnShared {
+    __attribute__((aligned(16))) _Float16 q[16 * KVQ_D];
+    float red_o[KVQ_ATTN_WAVES][16 * KVQ_OPAD];  // partial outputs of the eight wavefronts
+    float red_m[KVQ_ATTN_WAVES][16];
+    float red_l[KVQ_ATTN_WAVES][16];
+    int is_last;
+    unsigned claim_ctr;
+    u32x4 desc[KVQ_DESC_CACHE];
+    __attribute__((aligned(16))) uint8_t meta[KVQ_ATTN_WAVES * KVQ_WAVE_LDS_BYTES];
+};
+
+
+#ifdef KVQ_DEBUG_TIMING
+static __device__ unsigned long long kvq_dbg[1024 * 16];
+#define KVQ_STAMP(k) do { if ((threadIdx.x & 511) == 0) kvq_dbg[(blockIdx.y * gridDim.x + blockIdx.x) % 1024 * 16 + (k)] = wall_clock64(); } while (0)
+#define KVQ_STAMP_ID() do { if ((threadIdx.x & 511) == 0) kvq_dbg[(blockIdx.y * gridDim.x + blockIdx.x) % 1024 * 16 + 7] = ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32) | (unsigned)__builtin_amdgcn_s_getreg(4 | (31 << 11)); } while (0)
+#else
+#define KVQ_STAMP(k) do { } while (0)
+#define KVQ_STAMP_ID() do { } while (0)
+#endif
 #define KVQ_MERGE_LDS_FLOATS (KVQ_MAX_SPLITS * 16 * 3 + 16 + (KVQ_ATTN_THREADS / 32) * 32 * 4)
 
 // Merge of the split partials of one unit by a workgroup of KVQ_ATTN_THREADS threads.  Threads work in 16 slots
@@ -818,29 +861,124 @@ __device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, f
     }
 }
 
-#define KVQ_DESC_CACHE 256  // page descriptors staged in LDS per chunk of the split's range
-#ifdef KVQ_DEBUG_TIMING
-static __device__ unsigned long long kvq_dbg[1024 * 8];
-#define KVQ_STAMP(k) do { if (lane == 0 && wave == 0) kvq_dbg[(blockIdx.y * gridDim.x + blockIdx.x) % 1024 * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define KVQ_STAMP(k) do { } while (0)
-#endif
-#define KVQ_OPAD 132  // padded row of the LDS reduction slab (floats)
+static_assert(KVQ_ATTN_WAVES * 16 * KVQ_OPAD >= KVQ_MERGE_LDS_FLOATS, "the wavefront slab doubles as scratch of the split merge");
 
+// End of a workgroup's range: merge of its eight wavefront partials through LDS, then either the output (one split),
+// the partial for the separate merge kernel, or the fused merge of the unit's split partials.
+__device__ __forceinline__ void finish_workgroup(const KvqAttnParams& P, AttnShared& sh, WaveState& st, int split, int unit) {
+    // the thread index is taken afresh, opaque to the compiler: nothing derived from it stays in a register across
+    // the streaming loop for the sake of this epilogue
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = lane >> 4, n = lane & 15;
+    const int g = P.gqa, ns = P.n_splits;
+    const int b = unit / P.n_kv_heads, hk = unit - b * P.n_kv_heads;
+    float (*const red_o)[16 * KVQ_OPAD] = sh.red_o;
 
-// LDS of one workgroup.
-struct AttnShared {
-    __attribute__((aligned(16))) _Float16 q[16 * KVQ_D];
-    float red_o[4][16 * KVQ_OPAD];  // wavefront reduction slab, later the scratch of the split merge
-    float red_m[KVQ_ATTN_WAVES][16];
-    float red_l[KVQ_ATTN_WAVES][16];
-    int is_last;
-    unsigned claim_ctr;
-    u32x4 desc[KVQ_DESC_CACHE];
-    __attribute__((aligned(16))) uint8_t meta[KVQ_ATTN_WAVES * KVQ_WAVE_LDS_BYTES];
-};
+    set_accumulator_exponent(st, 0);
+    // ---- wavefront epilogue: add the zero-point term, fetch the denominator, leave the partial in LDS
+    const float l_w = __shfl(st.zl[0], 16 + n);
+    {
+        const float z0 = __shfl(st.zl[0], n), z1 = __shfl(st.zl[1], n), z2 = __shfl(st.zl[2], n), z3 = __shfl(st.zl[3], n);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            st.o[0][i] += z0; st.o[1][i] += z0;
+            st.o[2][i] += z1; st.o[3][i] += z1;
+            st.o[4][i] += z2; st.o[5][i] += z2;
+            st.o[6][i] += z3; st.o[7][i] += z3;
+        }
+    }
+    if (j == 0) { sh.red_m[wave][n] = st.m; sh.red_l[wave][n] = l_w; }
+    if (n < g) {
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt)
+            *reinterpret_cast<float4v*>(&red_o[wave][n * KVQ_OPAD + 16 * nt + 4 * j]) = st.o[nt];
+    }
+    __syncthreads();  // the eight wavefronts of the workgroup have joined
+    KVQ_STAMP(6);
 
-static_assert(4 * 16 * KVQ_OPAD >= KVQ_MERGE_LDS_FLOATS, "the reduction slab doubles as merge scratch");
+    const bool direct = (ns == 1);
+    const bool fused = !direct && P.fused_merge;
+
+    // ---- merge the eight wavefront partials: thread t takes the pairs of elements t, t + 512 of the
+    // [head][64 channel pairs] block; common maximum, weights and a fixed-order sum, one pass over LDS
+    const int n_pairs = g * (KVQ_D / 2);
+    float2v acc[2], ml[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int pr = tid + r * KVQ_ATTN_THREADS;
+        acc[r] = float2v{0.f, 0.f};
+        ml[r] = float2v{-INFINITY, 0.f};
+        if (pr < n_pairs) {
+            const int head = pr >> 6, d = 2 * (pr & 63);
+            float M = -INFINITY;
+            for (int w = 0; w < KVQ_ATTN_WAVES; ++w) M = fmaxf(M, sh.red_m[w][head]);
+            float2v a = {0.f, 0.f};
+            float L = 0.f;
+            for (int w = 0; w < KVQ_ATTN_WAVES; ++w) {
+                const float mw = sh.red_m[w][head];
+                const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+                const float2v o2 = *reinterpret_cast<const float2v*>(&red_o[w][head * KVQ_OPAD + d]);
+                a[0] = fmaf(o2[0], f, a[0]);
+                a[1] = fmaf(o2[1], f, a[1]);
+                L = fmaf(sh.red_l[w][head], f, L);
+            }
+            acc[r] = a;
+            ml[r] = float2v{M, L};
+        }
+    }
+    KVQ_STAMP(3);
+    float* po = P.part_o + ((size_t)unit * ns + split) * 16 * KVQ_D;
+    float* pml = P.part_ml + ((size_t)unit * ns + split) * 32;
+    if (!fused) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int pr = tid + r * KVQ_ATTN_THREADS;
+            if (pr >= n_pairs) continue;
+            const int head = pr >> 6, d = 2 * (pr & 63);
+            if (direct) {
+                const float inv = 1.0f / ml[r][1];
+                const float r0 = acc[r][0] * inv, r1 = acc[r][1] * inv;
+                const size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + d;
+                if (P.out_fp32) *reinterpret_cast<float2v*>(static_cast<float*>(P.out) + oi) = float2v{r0, r1};
+                else *reinterpret_cast<half2v*>(static_cast<_Float16*>(P.out) + oi) = half2v{(_Float16)r0, (_Float16)r1};
+            } else {  // the merge kernel that follows reads these
+                *reinterpret_cast<float2v*>(po + 2 * pr) = acc[r];
+                if (d == 0) *reinterpret_cast<float2v*>(pml + 2 * head) = ml[r];
+            }
+        }
+        return;
+    }
+
+    // ---- fused merge of the split partials: every workgroup publishes its partial with device-scope stores, waits
+    // until they have been performed, and one thread bumps the unit's arrival counter (device-scope atomic); the
+    // workgroup that draws the last ticket reads all partials back with device-scope loads and writes the output.
+    // The counter is left at zero for the next launch.
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int pr = tid + r * KVQ_ATTN_THREADS;
+        if (pr >= n_pairs) continue;
+        __hip_atomic_store(reinterpret_cast<unsigned long long*>(po + 2 * pr), __builtin_bit_cast(unsigned long long, acc[r]),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((pr & 63) == 0)
+            __hip_atomic_store(reinterpret_cast<unsigned long long*>(pml + 2 * (pr >> 6)),
+                               __builtin_bit_cast(unsigned long long, ml[r]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int& is_last = sh.is_last;
+    if (tid == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(&P.counters[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (old == (uint32_t)ns - 1u) ? 1 : 0;
+    }
+    __syncthreads();
+    KVQ_STAMP(4);
+    if (!is_last) return;
+    merge_splits<true>(P, unit, tid, &sh.red_o[0][0]);
+    if (tid == 0) __hip_atomic_store(&P.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    KVQ_STAMP(5);
+}
 
 // The whole kernel for one of the two V paths (SAFE: overflow-proof, see accumulate_tile) and one of the two kinds
 // of 16-bit tier (I16: integer codes in byte planes; else raw fp16, which is also the kind a one-token append can
@@ -853,20 +991,16 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
                                                const int unit_in = 0) {
     const int split = BATCH ? split_in : (int)blockIdx.x, unit = BATCH ? unit_in : (int)blockIdx.y;
     _Float16* const q_lds = sh.q;
-    float (*const red_o)[16 * KVQ_OPAD] = sh.red_o;
-    float (*const red_m)[16] = sh.red_m;
-    float (*const red_l)[16] = sh.red_l;
-    int& is_last = sh.is_last;
     unsigned& claim_ctr = sh.claim_ctr;
     u32x4* const desc_lds = sh.desc;
     uint8_t* const meta_lds = sh.meta;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int j = lane >> 4, n = lane & 15;
     const int g = P.gqa;
     const int b = unit / P.n_kv_heads, hk = unit - b * P.n_kv_heads;
 
     KVQ_STAMP(0);
+    KVQ_STAMP_ID();
     const int tpp = P.tiles_per_page;
     const int t_begin = P.split_begin[split], t_end = P.split_begin[split + 1];
     const int p_first = t_begin / tpp, p_last = (t_end + tpp - 1) / tpp;  // pages touched: [p_first, p_last)
@@ -915,7 +1049,7 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
 #ifdef KVQ_WITH_I16_APPEND
         if constexpr (I16) {  // integer tier: the token is quantized (Eq. 1-2, 2^16 - 1 levels); the reduction slab is free
             uint8_t* meta = const_cast<uint8_t*>(P.arena) + (uint64_t)P.app_desc.meta_off256 * 256u + tslot * KVQ_META_TILE_BYTES;
-            auto& lds = *reinterpret_cast<uint8_t (*)[2][KVQ_LDS_CODES]>(&red_o[0][0]);
+            auto& lds = *reinterpret_cast<uint8_t (*)[2][KVQ_LDS_CODES]>(&sh.red_o[0][0]);
             kvq_q::append_i16_string(lds, code, meta, in_k, 0, tile_new * KVQ_TILE_TOKENS, P.app_t_old, P.app_t_old + 1,
                                      P.app_gspan, P.app_rope, P.app_rinv, hk, lane);
             kvq_q::wave_sync_lds();
@@ -949,7 +1083,6 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
     ctx.arena = P.arena; ctx.desc_lds = desc_lds; ctx.claim_ctr = &claim_ctr; ctx.tpp = tpp; ctx.unit = unit;
     ctx.tpp_magic = P.tpp_magic;
     ctx.n_tokens = P.n_tokens; ctx.scale_log2 = P.scale_log2;
-    ctx.tpc = (tpp & 1) ? 1 : 2;
     ctx.lane_off = (uint32_t)lane * 16u;
     uint8_t* my_meta = meta_lds + wave * KVQ_WAVE_LDS_BYTES;
     if (lane < 8) reinterpret_cast<uint32_t*>(my_meta + KVQ_WAVE_LDS_CONST)[lane] = lane < 4 ? 0x3c003c00u : 0u;
@@ -965,8 +1098,13 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
         ctx.page0 = pc;
         ctx.lo = max(t_begin, pc * tpp);
         ctx.hi = min(t_end, (pc + pn) * tpp);
-        const int n_all = (ctx.hi - ctx.lo + ctx.tpc - 1) / ctx.tpc;
-        if (n_all <= 0) continue;
+        // Chunks of two tiles (one when pages hold an odd number of tiles), except at the end of the range: its last
+        // KVQ_TAIL_SINGLES tiles are claimed one by one, so that the wavefronts run out of work at nearly the same time.
+        const int n_t = ctx.hi - ctx.lo;
+        if (n_t <= 0) continue;
+        const int singles = (tpp & 1) ? n_t : (pc + KVQ_DESC_CACHE >= p_last ? min(KVQ_TAIL_SINGLES, n_t) : 0);
+        ctx.n_pairs = (n_t - singles) >> 1;
+        const int n_all = n_t - ctx.n_pairs;
         // The first chunk of every wavefront is fixed, from then on chunks are claimed one at a time.  Normally it
         // is the wavefront's own index.  With a fused append the last chunk is kept out of the claimable range:
         // wavefront 0 starts with it, wavefronts 1..7 with chunks 0..6.
@@ -1000,101 +1138,20 @@ __device__ __forceinline__ void attention_body(const KvqAttnParams& P, AttnShare
                     else run_chunks<16, 1, 2, false>(st, Q, q_lds, ctx, my_meta, lane);
                     break;
                 case 8: run_chunks<8, 1, 2, SAFE>(st, Q, q_lds, ctx, my_meta, lane); break;
-                case 4: run_chunks<4, 2, KVQ_RING_4BIT, SAFE>(st, Q, q_lds, ctx, my_meta, lane); break;
-                default: run_chunks<2, 2, KVQ_RING_2BIT, SAFE>(st, Q, q_lds, ctx, my_meta, lane); break;
+                case 4:
+                    if (ctx.next.nt == 2) run_chunks<4, 2, KVQ_RING_4BIT, SAFE>(st, Q, q_lds, ctx, my_meta, lane);
+                    else run_chunks<4, 1, KVQ_RING_SINGLE, SAFE>(st, Q, q_lds, ctx, my_meta, lane);
+                    break;
+                default:
+                    if (ctx.next.nt == 2) run_chunks<2, 2, KVQ_RING_2BIT, SAFE>(st, Q, q_lds, ctx, my_meta, lane);
+                    else run_chunks<2, 1, KVQ_RING_SINGLE, SAFE>(st, Q, q_lds, ctx, my_meta, lane);
+                    break;
             }
         }
     }
 
     KVQ_STAMP(2);
-    set_accumulator_exponent(st, 0);
-    // ---- wavefront epilogue: add the zero-point term, fetch the denominator
-    float l_w = __shfl(st.zl[0], 16 + n);
-    {
-        float z0 = __shfl(st.zl[0], n), z1 = __shfl(st.zl[1], n), z2 = __shfl(st.zl[2], n), z3 = __shfl(st.zl[3], n);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            st.o[0][i] += z0; st.o[1][i] += z0;
-            st.o[2][i] += z1; st.o[3][i] += z1;
-            st.o[4][i] += z2; st.o[5][i] += z2;
-            st.o[6][i] += z3; st.o[7][i] += z3;
-        }
-    }
-    // ---- merge the eight wavefronts through LDS: common maximum, then a fixed-order two-level sum
-    if (j == 0) red_m[wave][n] = st.m;
-    __syncthreads();
-    float M = red_m[0][n];
-#pragma unroll
-    for (int w = 1; w < KVQ_ATTN_WAVES; ++w) M = fmaxf(M, red_m[w][n]);
-    const float f = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - M);
-    if (j == 0) red_l[wave][n] = l_w * f;
-#pragma unroll
-    for (int nt = 0; nt < 8; ++nt) st.o[nt] *= f;
-    if (wave >= 4) {
-#pragma unroll
-        for (int nt = 0; nt < 8; ++nt)
-            *reinterpret_cast<float4v*>(&red_o[wave - 4][n * KVQ_OPAD + 16 * nt + 4 * j]) = st.o[nt];
-    }
-    __syncthreads();
-    if (wave < 4) {
-#pragma unroll
-        for (int nt = 0; nt < 8; ++nt) {
-            float4v* slot = reinterpret_cast<float4v*>(&red_o[wave][n * KVQ_OPAD + 16 * nt + 4 * j]);
-            *slot = st.o[nt] + *slot;
-        }
-    }
-    __syncthreads();
-
-    KVQ_STAMP(3);
-    const bool direct = (P.n_splits == 1);
-    float* po = P.part_o + ((size_t)unit * P.n_splits + split) * 16 * KVQ_D;
-    float* pml = P.part_ml + ((size_t)unit * P.n_splits + split) * 32;
-    for (int e = tid; e < g * KVQ_D; e += KVQ_ATTN_THREADS) {
-        int head = e >> 7, d = e & 127;
-        int li = head * KVQ_OPAD + d;
-        float acc = (red_o[0][li] + red_o[1][li]) + (red_o[2][li] + red_o[3][li]);
-        if (direct) {
-            float L = 0.f;
-#pragma unroll
-            for (int w = 0; w < KVQ_ATTN_WAVES; ++w) L += red_l[w][head];
-            float r = acc / L;
-            size_t oi = ((size_t)b * P.n_q_heads + hk * g + head) * KVQ_D + d;
-            if (P.out_fp32) static_cast<float*>(P.out)[oi] = r;
-            else static_cast<_Float16*>(P.out)[oi] = (_Float16)r;
-        } else if (P.fused_merge) {
-            store_agent(po + e, acc);
-        } else {
-            po[e] = acc;
-        }
-    }
-    if (direct) return;
-    if (tid < 16) {
-        float Mh = red_m[0][tid], Lh = 0.f;
-#pragma unroll
-        for (int w = 1; w < KVQ_ATTN_WAVES; ++w) Mh = fmaxf(Mh, red_m[w][tid]);
-#pragma unroll
-        for (int w = 0; w < KVQ_ATTN_WAVES; ++w) Lh += red_l[w][tid];
-        if (P.fused_merge) { store_agent(pml + 2 * tid, Mh); store_agent(pml + 2 * tid + 1, Lh); }
-        else { pml[2 * tid] = Mh; pml[2 * tid + 1] = Lh; }
-    }
-    if (!P.fused_merge) return;
-
-    // ---- fused merge: the last workgroup of the unit to arrive combines all split partials.  Every thread
-    // waits until its device-scope stores have been performed, the workgroup meets, one thread bumps the
-    // unit's arrival counter (device-scope atomic); the workgroup that sees the last ticket reads the partials
-    // with device-scope loads.  The counter is left at zero for the next launch.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t old = __hip_atomic_fetch_add(&P.counters[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (old == (uint32_t)P.n_splits - 1u);
-    }
-    __syncthreads();
-    KVQ_STAMP(4);
-    if (!is_last) return;
-    merge_splits<true>(P, unit, tid, &red_o[0][0]);
-    if (tid == 0) __hip_atomic_store(&P.counters[unit], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    KVQ_STAMP(5);
+    finish_workgroup(P, sh, st, split, unit);
 }
 
 }  // namespace

@@ -41,7 +41,7 @@
 #define KVQ_MAX_SPLITS 128
 #define KVQ_MAX_GQA 16
 
-#if defined(__HIPCC__) || defined(__CUDACC__)
+#if defined(__HIPCC__)
 #define KVQ_HD __host__ __device__ inline
 #else
 #define KVQ_HD inline
