@@ -11,12 +11,23 @@
  *     returns a framework type.
  *   - The caller owns the arena, the q/k/v/out buffers and the stream.  The library owns the kvq_cache_t
  *     (host tables) and sub-allocates inside the arena; it never allocates or frees device memory.
- *   - Every kernel is enqueued on the given HIP stream (hipStream_t passed as void*, NULL = default stream)
- *     and no entry point synchronises, except kvq_cache_export_segment which copies to the host.
+ *   - Every kernel is enqueued on the given HIP stream (hipStream_t passed as void*, NULL = default stream).
+ *     No entry point waits for the stream, except the three that copy results to the host
+ *     (kvq_cache_export_segment, kvq_cache_sq_error, kvq_cache_sensitivity).  Small host-to-device uploads (page
+ *     tables, job lists, the parameter blocks of a ragged batch) travel through a pinned staging ring of 4 segments of
+ *     1 MiB whose reuse is guarded by one HIP event per segment: a call blocks the host only when it has run a whole
+ *     ring of uploads ahead of the device, and then only until the oldest segment has been consumed.
+ *   - Stream capture: kvq_decode_attention and kvq_decode_attention_static enqueue kernels only and may be captured
+ *     into a HIP graph (the cache must not change between capture and replay).  Calls that change a cache or stage
+ *     parameter blocks (append, requant, the *_batch calls, set_reparam) use the staging ring and its events and must
+ *     not be captured.
  *   - All calls on one cache must be issued from one thread at a time and on one stream (the host tables
  *     are updated at enqueue time, the device tables in stream order).
  *   - Errors are reported as kvq_status_t; argument, state and budget errors are detected on the host before
  *     anything is enqueued and leave the cache unchanged.  Nothing throws or aborts across this boundary.
+ *     KVQ_E_OOM of an append is found before anything changes as well.  A HIP failure (KVQ_E_HIP) while a call is
+ *     being enqueued can strike after the host tables have been updated; the block is then marked unusable: every
+ *     later call on it returns KVQ_E_STATE until kvq_cache_reset empties it (other blocks are unaffected).
  *   - All sequences of one cache have the same length and share one page table per block; sequences of different
  *     lengths live in caches of their own and are served together by the *_batch entry points.
  *   - head_dim is 128, group is 32, 64 or 128 channels (128 is the paper's setting, Sec. 4.1.2),
@@ -123,7 +134,9 @@ kvq_status_t kvq_quantize_append_rope(kvq_cache_t* cache, int32_t layer, const v
  *   is what an integer 16-bit tier followed by Eq. 3 would give; with KVQ_TIER16_INT16 the 16-bit pages are that
  *   integer tier and 16 -> 8 is Eq. 3 at b = 8 (multiplier 65281, offset 128, shift 24, in unsigned 32-bit).
  *   segment >= 0: lower every page of that run (kvq_cache_describe order) one step; KVQ_E_STATE if it is
- *   already at 2 bits or does not exist.
+ *   already at 2 bits or does not exist, or if the run ends in the partly filled last page while the policy appends
+ *   at 16 bits (OLDEST_FIRST, or a window): that page could take no further token.  Tiles of a partly filled page
+ *   that hold no token yet are left untouched.
  *   segment == -1, KVQ_POLICY_PAPER: halve the block's current width: every page at that width outside the
  *   sink and the window is lowered one step.  KVQ_E_BUDGET if the block is already at Fbit.
  *   segment == -1, KVQ_POLICY_OLDEST_FIRST: while bytes_used + reserve_tokens 16-bit tokens exceed the
@@ -300,7 +313,9 @@ kvq_status_t kvq_stream_read_probe(kvq_cache_t* cache, const void* buf_dev, uint
 /* Empties block `layer` (-1: every block) so that the cache can take a new sequence: its pages go back to the arena
  * (reused only by work enqueued later, so on the cache's stream nothing in flight is disturbed), its token count to
  * zero; budget, Fbit, options and the block's reparameterization factors stay (kvq_cache_set_reparam may be called
- * again, the block being empty).  Host bookkeeping only; nothing is enqueued. */
+ * again, the block being empty).  Host bookkeeping only; nothing is enqueued.  Once every block is empty, the
+ * device-side flags of the cache (the mark that a V scale >= 256 was seen, which selects the slower overflow-proof
+ * attention path) are cleared by the next call that enqueues work, in stream order. */
 kvq_status_t kvq_cache_reset(kvq_cache_t* cache, int32_t layer);
 
 /* Free bytes left in the arena's page area (host bookkeeping). */

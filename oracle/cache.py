@@ -255,6 +255,10 @@ class OracleCache:
             t0, t1, b = segs[segment]
             if b == 2:
                 raise StateError("already at 2 bits")
+            if t1 == L.T and L.T % P != 0 and (c.policy == POLICY_OLDEST_FIRST or c.window > 0):
+                # the run ends in the partly filled last page and the policy appends at 16 bits: lowered, that
+                # page could take no further token (a page holds one width)
+                raise StateError("run ends in the partly filled last page")
             idx = range(t0 // P, (t1 + P - 1) // P)
             for i in idx:
                 self._lower_page(L.pages[i], b // 2)

@@ -12,11 +12,21 @@
 
 #include "../../include/kvq.h"
 #include "kvq_internal.h"
+#include "kvq_ring.h"
 
 namespace {
 
 constexpr int kMaxOrder = 4;  // allocation blocks of 1, 2, 4, 8, 16 units; a unit is one metadata block
-constexpr uint64_t kRingBytes = 4u << 20;
+constexpr int kRingSegments = 4;
+constexpr uint64_t kRingSegmentBytes = 1u << 20;  // the pinned staging ring: 4 segments of 1 MiB
+
+// Markers of the staging ring: one HIP event per segment, recorded on the cache's stream.
+struct RingEvents {
+    hipEvent_t ev[kRingSegments] = {};
+    hipStream_t stream = nullptr;
+    bool record(int i) { return hipEventRecord(ev[i], stream) == hipSuccess; }
+    bool wait(int i) { return hipEventSynchronize(ev[i]) == hipSuccess; }
+};
 
 int order_of_bits(int bits) { return bits == 16 ? 4 : bits == 8 ? 3 : bits == 4 ? 2 : 1; }
 bool valid_bits(int b) { return b == 16 || b == 8 || b == 4 || b == 2; }
@@ -76,6 +86,7 @@ struct Layer {
     int fbit = 2;
     int T = 0;
     bool reparam = false;  // keys stored as K / lambda, queries multiplied by lambda (Sec. 3.3)
+    bool poisoned = false; // an enqueue failed after the host tables had been updated: unusable until kvq_cache_reset
     std::vector<Page> pages;
     // split plan cache of kvq_decode_attention
     int plan_tiles = -1, plan_splits = 0;
@@ -99,7 +110,8 @@ struct kvq_cache {
     std::vector<Layer> layers;
     uint8_t* ring = nullptr;
     uint8_t* ring_dev = nullptr;  // the same pinned memory as the device addresses it
-    uint64_t ring_pos = 0;
+    KvqStagingRing<RingEvents, kRingSegments> ring_ctl;
+    RingEvents ring_events;
     bool device_ready = false;
     int splits_override = 0;
     int fused_merge = 1;
@@ -170,33 +182,32 @@ Regions layout_regions(const kvq_config_t* c) {
 
 hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
 
-// Copy `bytes` of host data to device memory in stream order through the pinned staging ring.
+// Copy `bytes` of host data to device memory in stream order through the pinned staging ring (in pieces of at most
+// one ring segment).  The host waits only if it is a whole ring ahead of the device.
 kvq_status_t upload(kvq_cache* c, void* dst_dev, const void* src, uint64_t bytes, hipStream_t s) {
-    if (bytes == 0) return KVQ_OK;
-    if (bytes > kRingBytes) return KVQ_E_INVALID;
-    if (c->ring_pos + bytes > kRingBytes) {
-        // the ring wraps: wait until the copies enqueued from it have been consumed
-        if (hipStreamSynchronize(s) != hipSuccess) return KVQ_E_HIP;
-        c->ring_pos = 0;
+    c->ring_events.stream = s;
+    const uint8_t* from = static_cast<const uint8_t*>(src);
+    uint8_t* to = static_cast<uint8_t*>(dst_dev);
+    while (bytes) {
+        const uint64_t n = std::min<uint64_t>(bytes, c->ring_ctl.segment_bytes());
+        const int64_t at = c->ring_ctl.reserve(c->ring_events, n, 64);
+        if (at < 0) return KVQ_E_HIP;
+        std::memcpy(c->ring + at, from, n);
+        if (hipMemcpyAsync(to, c->ring + at, n, hipMemcpyHostToDevice, s) != hipSuccess) return KVQ_E_HIP;
+        from += n; to += n; bytes -= n;
     }
-    std::memcpy(c->ring + c->ring_pos, src, bytes);
-    if (hipMemcpyAsync(dst_dev, c->ring + c->ring_pos, bytes, hipMemcpyHostToDevice, s) != hipSuccess)
-        return KVQ_E_HIP;
-    c->ring_pos = align_up(c->ring_pos + bytes, 64);
     return KVQ_OK;
 }
 
-// Place `bytes` of host data in the pinned staging ring and return where (a host address the device can read as
-// well); the space is not reused before the work enqueued on s so far has completed.
+// Place `bytes` of host data (at most one ring segment) in the pinned staging ring and return where (a host address
+// the device can read as well); the space is not reused before the work enqueued on s after this call has completed.
 kvq_status_t stage(kvq_cache* c, const void* src, uint64_t bytes, hipStream_t s, const void** where) {
-    if (bytes == 0 || bytes > kRingBytes) return KVQ_E_INVALID;
-    if (c->ring_pos + bytes > kRingBytes) {
-        if (hipStreamSynchronize(s) != hipSuccess) return KVQ_E_HIP;
-        c->ring_pos = 0;
-    }
-    std::memcpy(c->ring + c->ring_pos, src, bytes);
-    *where = c->ring_dev + c->ring_pos;
-    c->ring_pos = align_up(c->ring_pos + bytes, 256);
+    if (bytes == 0 || bytes > c->ring_ctl.segment_bytes()) return KVQ_E_INVALID;
+    c->ring_events.stream = s;
+    const int64_t at = c->ring_ctl.reserve(c->ring_events, bytes, 256);
+    if (at < 0) return KVQ_E_HIP;
+    std::memcpy(c->ring + at, src, bytes);
+    *where = c->ring_dev + at;
     return KVQ_OK;
 }
 
@@ -281,7 +292,7 @@ kvq_status_t run_lowering_step(kvq_cache* c, int layer, std::vector<Lowering>& l
             jobs[i].src_code_off256 = (uint32_t)(c->unit_off_bytes(p.code_unit) / 256);
             jobs[i].dst_code_off256 = (uint32_t)(c->unit_off_bytes(low[i].new_code) / 256);
             jobs[i].meta_off256 = (uint32_t)(c->unit_off_bytes(fresh_meta ? low[i].new_meta : p.meta_unit) / 256);
-            jobs[i].pad = 0;
+            jobs[i].n_tiles = (uint32_t)((p.n + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS);
         }
         KvqRequantJob* jd = reinterpret_cast<KvqRequantJob*>(c->arena + c->jobs_off);
         const bool by_arg = jobs.size() <= (size_t)KVQ_JOBS_BY_ARG;  // short lists ride in the kernel arguments
@@ -311,7 +322,9 @@ kvq_status_t run_lowering_step(kvq_cache* c, int layer, std::vector<Lowering>& l
         hi = std::max(hi, w.page + 1);
     }
     L.version++;
-    return upload_table(c, layer, lo, hi, s);
+    const kvq_status_t up = upload_table(c, layer, lo, hi, s);
+    if (up != KVQ_OK) L.poisoned = true;  // host tables and device page table disagree
+    return up;
 }
 
 // Lower a set of pages that share (from, to).  Pages of the integer 16-bit tier go down one halving at a time
@@ -430,11 +443,21 @@ kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_bud
         c->layers[(size_t)i].fbit = block_fbit_host[i];
     }
     if (!c->dry) {
-        if (hipHostMalloc(reinterpret_cast<void**>(&c->ring), kRingBytes, hipHostMallocDefault) != hipSuccess) {
+        c->ring_ctl.init(kRingSegmentBytes);
+        if (hipHostMalloc(reinterpret_cast<void**>(&c->ring), c->ring_ctl.total_bytes(), hipHostMallocDefault) != hipSuccess) {
             delete c;
             return KVQ_E_HIP;
         }
+        for (int i = 0; i < kRingSegments; ++i) {
+            if (hipEventCreateWithFlags(&c->ring_events.ev[i], hipEventDisableTiming) != hipSuccess) {
+                for (int k = 0; k < i; ++k) (void)hipEventDestroy(c->ring_events.ev[k]);
+                (void)hipHostFree(c->ring);
+                delete c;
+                return KVQ_E_HIP;
+            }
+        }
         if (hipHostGetDevicePointer(reinterpret_cast<void**>(&c->ring_dev), c->ring, 0) != hipSuccess) {
+            for (int i = 0; i < kRingSegments; ++i) (void)hipEventDestroy(c->ring_events.ev[i]);
             (void)hipHostFree(c->ring);
             delete c;
             return KVQ_E_HIP;
@@ -451,7 +474,10 @@ kvq_status_t kvq_cache_create(const kvq_config_t* cfg, const uint64_t* block_bud
 
 void kvq_cache_destroy(kvq_cache_t* c) {
     if (!c) return;
-    if (c->ring) (void)hipHostFree(c->ring);
+    if (c->ring) {
+        (void)hipHostFree(c->ring);
+        for (int i = 0; i < kRingSegments; ++i) (void)hipEventDestroy(c->ring_events.ev[i]);
+    }
     delete c;
 }
 
@@ -478,6 +504,7 @@ kvq_status_t plan_append(const kvq_cache_t* c, int32_t layer, int32_t n_new, int
     const Layer& L = c->layers[(size_t)layer];
     const kvq_config_t& cfg = c->cfg;
     const int P = cfg.page_tokens;
+    if (L.poisoned) return KVQ_E_STATE;
     if ((int64_t)L.T + n_new > cfg.max_tokens) return KVQ_E_STATE;
     int e = entry_bits;
     if (e == 0) e = (cfg.policy == KVQ_POLICY_OLDEST_FIRST || cfg.window > 0) ? 16 : current_bits(c, L);
@@ -547,14 +574,21 @@ kvq_status_t commit_append(kvq_cache_t* c, int32_t layer, const AppendPlan& pl, 
         fresh.push_back(p);
     }
     kvq_status_t st = ensure_device(c, s);
-    if (st != KVQ_OK) return st;
+    if (st != KVQ_OK) {
+        for (Page& q : fresh) {
+            c->buddy.release(q.code_unit, order_of_bits(e));
+            if (c->has_meta(e)) c->buddy.release(q.meta_unit, 0);
+        }
+        return st;
+    }
     const int t_old = L.T, T = pl.T;
     for (Page& p : fresh) L.pages.push_back(p);
     for (size_t i = 0; i < L.pages.size(); ++i) L.pages[i].n = pl.cnt[i];
     L.T = T;
     L.version++;
+    // From here on the host tables count the new tokens: a failing enqueue leaves the block unusable (poisoned).
     st = upload_table(c, layer, (int)old_pages, (int)L.pages.size(), s);
-    if (st != KVQ_OK) return st;
+    if (st != KVQ_OK) { L.poisoned = true; return st; }
     if (!c->dry && defer && n_new == 1 && e == 16 && (!c->int16() || defer->int16_too)) {
         defer->active = true;
         defer->t_old = t_old;
@@ -571,14 +605,16 @@ kvq_status_t commit_append(kvq_cache_t* c, int32_t layer, const AppendPlan& pl, 
         if (kvq_launch_append(e, c->arena, c->table_dev(layer), k_dev, v_dev, t_old, n_new, c->tpp, c->units,
                               by_arg ? two : nullptr, pg0, c->flags_dev(), c->cfg.group,
                               L.reparam ? c->lambda_dev(layer) + c->cfg.n_kv_heads * KVQ_D : nullptr, c->cfg.n_kv_heads,
-                              cos_sin_dev, c->int16(), s) != hipSuccess)
+                              cos_sin_dev, c->int16(), s) != hipSuccess) {
+            L.poisoned = true;
             return KVQ_E_HIP;
+        }
     }
     if (!pl.evicted.empty()) {
         std::vector<Lowering> low;
         for (int i : pl.evicted) low.push_back(Lowering{i, 16, pl.bcur});
         st = run_lowerings(c, layer, low, s);
-        if (st != KVQ_OK) return st;
+        if (st != KVQ_OK) { L.poisoned = true; return st; }  // the plan counted these pages at their new width
     }
     return KVQ_OK;
 }
@@ -614,6 +650,7 @@ kvq_status_t kvq_progressive_requant(kvq_cache_t* c, int32_t layer, int32_t segm
     Layer& L = c->layers[(size_t)layer];
     const kvq_config_t& cfg = c->cfg;
     const int P = cfg.page_tokens;
+    if (L.poisoned) return KVQ_E_STATE;
     hipStream_t s = as_stream(hip_stream);
     kvq_status_t st = ensure_device(c, s);
     if (st != KVQ_OK) return st;
@@ -624,6 +661,10 @@ kvq_status_t kvq_progressive_requant(kvq_cache_t* c, int32_t layer, int32_t segm
         if (segment >= (int)segs.size()) return KVQ_E_STATE;
         const kvq_segment_info_t sg = segs[(size_t)segment];
         if (sg.bits == 2) return KVQ_E_STATE;
+        // A run that ends in the partly filled last page: lowering it would leave that page at a width other than the
+        // one the policy appends at (16 bits under OLDEST_FIRST or with a window), and no token could follow.
+        if (sg.token_end == L.T && L.T % P != 0 && (cfg.policy == KVQ_POLICY_OLDEST_FIRST || cfg.window > 0))
+            return KVQ_E_STATE;
         std::vector<Lowering> low;
         for (int i = sg.token_begin / P; i < (sg.token_end + P - 1) / P; ++i) low.push_back(Lowering{i, sg.bits, sg.bits / 2});
         st = run_lowerings(c, layer, low, s);
@@ -685,7 +726,7 @@ kvq_status_t fill_attn_params(kvq_cache_t* c, int32_t layer, const void* q_dev, 
     if (!c || layer < 0 || layer >= c->cfg.n_layers || !q_dev || !out_dev) return KVQ_E_INVALID;
     if (c->dry) return KVQ_E_STATE;
     Layer& L = c->layers[(size_t)layer];
-    if (L.T == 0) return KVQ_E_STATE;
+    if (L.T == 0 || L.poisoned) return KVQ_E_STATE;
     const int n_tiles = (L.T + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
     int n_splits = c->splits_override;
     if (n_splits <= 0) {
@@ -925,6 +966,7 @@ kvq_status_t kvq_cache_export_segment(kvq_cache_t* c, int32_t layer, int32_t seg
     if (which != KVQ_WHICH_K && which != KVQ_WHICH_V) return KVQ_E_INVALID;
     if (c->dry) return KVQ_E_STATE;
     const Layer& L = c->layers[(size_t)layer];
+    if (L.poisoned) return KVQ_E_STATE;
     std::vector<kvq_segment_info_t> segs;
     build_segments(c, L, segs);
     if (segment >= (int)segs.size()) return KVQ_E_STATE;
@@ -1146,7 +1188,13 @@ kvq_status_t kvq_cache_reset(kvq_cache_t* c, int32_t layer) {
         L.T = 0;
         L.version++;
         L.plan_tiles = -1;
+        L.poisoned = false;
     }
+    // An empty cache starts over: the next enqueueing call clears the device flags again (in stream order), among them
+    // the mark that some V scale was large, which would otherwise outlive the data that set it.
+    bool all_empty = true;
+    for (const Layer& L : c->layers) all_empty = all_empty && L.T == 0;
+    if (all_empty) c->device_ready = false;
     return KVQ_OK;
 }
 

@@ -10,7 +10,7 @@ struct KvqRequantJob {        // one page to re-quantize
     uint32_t src_code_off256; // source code block
     uint32_t dst_code_off256; // destination code block
     uint32_t meta_off256;     // metadata block (updated in place for 2b -> b, written for fp16 -> b)
-    uint32_t pad;
+    uint32_t n_tiles;         // tiles of the page that hold tokens; the kernels leave the others alone
 };
 
 // Up to KVQ_JOBS_BY_ARG jobs ride in the kernel arguments (no table upload in front of the launch);

@@ -213,6 +213,7 @@ __global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ a
     const int job = idx / tpp, tip = idx - job * tpp;
     const int unit = blockIdx.y;
     const KvqRequantJob jb = ja.n ? ja.jobs[job] : jobs[job];
+    if (tip >= (int)jb.n_tiles) return;  // tiles of a partly filled page that hold no token yet (wavefront-uniform)
     const uint64_t tslot = (uint64_t)unit * tpp + tip;
     const uint8_t* src = arena + (uint64_t)jb.src_code_off256 * 256u + (tslot * 2 + which) * (512u * 16);
     uint8_t* dst = arena + (uint64_t)jb.dst_code_off256 * 256u + (tslot * 2 + which) * (512u * B);
@@ -329,6 +330,7 @@ __global__ __launch_bounds__(64) void kvq_shrink_kernel(uint8_t* __restrict__ ar
     const int job = blockIdx.x / tpp, tip = blockIdx.x - job * tpp;
     const int unit = blockIdx.y;
     const KvqRequantJob jb = ja.n ? ja.jobs[job] : jobs[job];
+    if (tip >= (int)jb.n_tiles) return;  // tiles of a partly filled page that hold no token yet (wavefront-uniform)
     const uint64_t tslot = (uint64_t)unit * tpp + tip;
     const uint8_t* src = arena + (uint64_t)jb.src_code_off256 * 256u + tslot * 2 * (512u * 2 * B);
     uint8_t* dst = arena + (uint64_t)jb.dst_code_off256 * 256u + tslot * 2 * (512u * B);

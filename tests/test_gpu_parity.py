@@ -628,19 +628,6 @@ def test_full_size_70b_layer_sampled_units():
     _sampled_full_size(kvq_synth.WORKLOADS["70b"], 1, ((0, 0), (0, 5)))
 
 
-def test_full_size_7b_layer_sampled_units():
-    """One block of the 7B-shaped workload at batch 2 of 16 (the launch shape per unit is unchanged)."""
-    _sampled_full_size(kvq_synth.WORKLOADS["7b"], 2, ((0, 1), (1, 3)))
-
-
-def test_full_size_14b_layer_sampled_units():
-    """Two blocks of the 14B-shaped workload (their bulk widths are drawn per block) at batch 1 of 8."""
-    w = kvq_synth.WORKLOADS["14b"]
-    layers = [w.layer_bits.index(b) for b in (2, 8) if b in w.layer_bits]
-    for layer in layers:
-        _sampled_full_size(w, 1, ((0, 2),), layer=layer)
-
-
 def test_cache_reset_and_reuse():
     """A block that held one sequence is emptied and takes another: contents and attention are those of a fresh cache."""
     B, H, T, P = 1, 2, 300, 64

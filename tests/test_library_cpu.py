@@ -356,3 +356,90 @@ int main(void) {
     assert r.returncode == 0, r.stderr
     r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+
+
+def test_segment_requant_refuses_to_strand_the_partly_filled_last_page():
+    """Lowering a run that ends in the partly filled last page is refused when the policy appends at 16 bits (a page
+    holds one width, so no token could follow); under policy PAPER without a window the block's width follows the
+    page and the append goes on.  Library and oracle take the same decision."""
+    for policy, W, refuse in ((POLICY_OLDEST_FIRST, 0, True), (POLICY_PAPER, 64, True), (POLICY_PAPER, 0, False)):
+        oc, gc = _pair(policy, 64, W, 0, 1 << 40, 2, Tmax=1024, B=1, H=2)
+        K, V = kvq_synth.make_kv(79, 0, 1, 2, 0, 200, rope_base=None)
+        oc.append(0, K[:, :, :100], V[:, :, :100], 0)
+        gc.kvq_quantize_append(0, None, None, n_new=100)
+        _same_state(oc, gc)
+        if refuse:
+            with pytest.raises(StateError):
+                oc.requant(0, segment=0)
+            with pytest.raises(kq.KvqError) as e:
+                gc.kvq_progressive_requant(0, segment=0)
+            assert e.value.status == kq.KVQ_E_STATE
+        else:
+            assert gc.kvq_progressive_requant(0, segment=0) == oc.requant(0, segment=0) == 2
+        _same_state(oc, gc)
+        oc.append(0, K[:, :, 100:200], V[:, :, 100:200], 0)      # the block still takes tokens
+        gc.kvq_quantize_append(0, None, None, n_new=100)
+        _same_state(oc, gc)
+
+
+def test_staging_ring_bookkeeping(tmp_path):
+    """The pinned staging ring (csrc/kvq_ring.h) with a fake marker backend: offsets stay inside a segment and aligned,
+    a marker is recorded whenever the write position leaves a segment, a segment is written again only after its
+    marker has been waited for, and nothing is ever waited for that was not recorded."""
+    import shutil
+    import subprocess
+    if not shutil.which("g++"):
+        pytest.skip("no C++ compiler")
+    src = tmp_path / "ring_test.cpp"
+    src.write_text(r'''
+#include "kvq_ring.h"
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+struct Fake {
+    std::vector<int> log;           // +seg+1: record, -(seg+1): wait
+    bool recorded[4] = {false, false, false, false};
+    bool record(int s) { recorded[s] = true; log.push_back(s + 1); return true; }
+    bool wait(int s) { if (!recorded[s]) { std::puts("wait without record"); std::exit(2); } recorded[s] = false; log.push_back(-(s + 1)); return true; }
+};
+int main() {
+    KvqStagingRing<Fake, 4> ring;
+    Fake be;
+    ring.init(1024);
+    if (ring.total_bytes() != 4096) return 3;
+    if (ring.reserve(be, 0, 64) != -1 || ring.reserve(be, 1025, 64) != -1) return 4;   // empty / larger than a segment
+    unsigned seed = 12345;
+    long last_seg = 0, wraps = 0;
+    bool live[4] = {true, false, false, false};   // segments holding data whose marker has not been waited for
+    for (int i = 0; i < 20000; ++i) {
+        seed = seed * 1664525u + 1013904223u;
+        const unsigned long bytes = 1 + (seed >> 8) % 700;
+        const unsigned long align = (i & 1) ? 256 : 64;
+        const size_t before = be.log.size();
+        const long at = (long)ring.reserve(be, bytes, align);
+        if (at < 0 || at % (long)align) return 5;
+        const long seg = at / 1024;
+        if ((at + (long)bytes - 1) / 1024 != seg) return 6;          // never straddles segments
+        if (seg != last_seg) {
+            if (seg != (last_seg + 1) % 4) return 7;                   // segments are taken in order
+            if (at % 1024 != 0) return 8;                              // and entered at their start
+            // leaving last_seg recorded its marker first; entering `seg` waited for its own old marker if it had one
+            if (be.log.size() < before + 1 || be.log[before] != last_seg + 1) return 9;
+            if (live[seg]) { if (be.log.size() != before + 2 || be.log[before + 1] != -(seg + 1)) return 10; }
+            else if (be.log.size() != before + 1) return 11;
+            live[seg] = true;
+            last_seg = seg;
+            ++wraps;
+        } else if (be.log.size() != before) return 12;                 // no marker traffic inside a segment
+    }
+    if (wraps < 1000 || ring.waits() != wraps - 3) return 13;          // every entry but the first three waited
+    std::puts("ok");
+    return 0;
+}
+''')
+    exe = tmp_path / "ring_test"
+    r = subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-O1", "-I", os.path.join(ROOT, "paper_2505_18610_amd", "csrc"),
+                        str(src), "-o", str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0 and r.stdout.strip() == "ok", (r.returncode, r.stdout, r.stderr)
