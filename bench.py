@@ -413,13 +413,112 @@ def measure_read_ceiling(kq, torch, cache):
     return round(best, 1)
 
 
-def cpu_baseline(w, KV, q_np, seconds_hint=12.0):
-    """The oracle's attention (de-quantize + fp64 attention) on one sequence of one block of the same workload."""
+def library_source_sha16():
+    """Hash of the library's sources (kernels, host code, public header): ties stored counter results to the code."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(ROOT, "paper_2505_18610_amd", "csrc", "*.h")) +
+                   glob.glob(os.path.join(ROOT, "paper_2505_18610_amd", "csrc", "*.hip")) +
+                   glob.glob(os.path.join(ROOT, "paper_2505_18610_amd", "csrc", "*.cpp")) +
+                   [os.path.join(ROOT, "include", "kvq.h")])
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def other_workloads(kq, torch, kvq_synth, skip):
+    """The decode step's launch (kvq_append_decode_attention) on the other workloads of the configuration list: a few
+    distinct resident blocks each (more than a gigabyte, far beyond the last-level cache), trains of back-to-back
+    launches, HIP events around the trains.  Cache values are seeded Gaussian draws made on the device (the launch time
+    does not depend on them; parity at these shapes is the job of the GPU tests).  14B-shaped: three blocks of each bulk
+    width, timed per width; the mean weights the widths as the workload's 48 blocks draw them."""
+    res = {}
+    for name in ("7b", "14b", "32b", "70b"):
+        if name == skip:
+            continue
+        w = kvq_synth.WORKLOADS[name]
+        B, Hkv, Hq, T, P = w.batch, w.n_kv_heads, w.n_q_heads, w.n_tokens, w.page_tokens
+        units = B * Hkv
+        if w.layer_bits is None:
+            layer_tiers = [list(w.tiers)] * {"7b": 4, "32b": 8, "70b": 8}[name]
+        else:
+            layer_tiers = [[(n, b if b_ == 0 else b_) for n, b_ in w.tiers] for b in (2, 2, 2, 4, 4, 4, 8, 8, 8)]
+        L, spare = len(layer_tiers), 64
+        payload = sum(n * units * kq.kvq_bytes_per_token_head(b) for tiers in layer_tiers for n, b in tiers)
+        cfg = kq.KvqConfig(L, B, Hq, Hkv, T + spare, page_tokens=P, policy=kq.KVQ_POLICY_OLDEST_FIRST)
+        arena = torch.empty(kq.kvq_arena_bytes(cfg, int(payload * 1.03) + L * 2 * P * units * 512 + (64 << 20)),
+                            dtype=torch.uint8, device="cuda")
+        cache = kq.KvqCache(cfg, [1 << 60] * L, [2] * L, arena=arena)
+        g = torch.Generator(device="cuda").manual_seed(w.seed)
+        chunk = 8192
+        kbuf = torch.randn((B, Hkv, chunk, 128), device="cuda", generator=g).half()
+        vbuf = torch.randn((B, Hkv, chunk, 128), device="cuda", generator=g).half()
+        for layer, tiers in enumerate(layer_tiers):
+            for n, bits in tiers:
+                for t0 in range(0, n, chunk):
+                    m = min(chunk, n - t0)
+                    cache.kvq_quantize_append(layer, kbuf[:, :, :m].contiguous(), vbuf[:, :, :m].contiguous(), bits)
+        q = torch.randn((B, Hq, 128), device="cuda", generator=g).half()
+        out = torch.empty((B, Hq, 128), dtype=torch.float16, device="cuda")
+        k1, v1 = kbuf[:, :, :1].contiguous(), vbuf[:, :, :1].contiguous()
+        nbytes = [cache.kvq_cache_describe(layer)[1] for layer in range(L)]
+        # groups of equal blocks; a train sweeps the blocks of one group several times between one pair of events
+        groups = {}
+        for layer, tiers in enumerate(layer_tiers):
+            groups.setdefault(tiers[0][1] if w.layer_bits is not None else 0, []).append(layer)
+        sweeps = 24 // max(len(v) for v in groups.values())
+        best = {k: 1e9 for k in groups}
+        for _ in range(400 // L):                # the device reaches its sustained clocks only after some tens of ms of work
+            for layer in range(L):
+                cache.kvq_decode_attention(layer, q, out)
+        for rep in range(4):                     # every launch appends one token to its block (64 spare tokens per block)
+            for key, layers in groups.items():
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                for layer in layers * 2:         # untimed lead-in: the timed launches are queued behind running work
+                    cache.kvq_decode_attention(layer, q, out)
+                e0.record()
+                for _ in range(sweeps):
+                    for layer in layers:
+                        cache.kvq_append_decode_attention(layer, k1, v1, q, out)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep:
+                    best[key] = min(best[key], e0.elapsed_time(e1) / (sweeps * len(layers)))
+        if w.layer_bits is None:
+            ms, bytes_launch = float(best[0]), float(np.mean(nbytes))
+            entry = {}
+        else:
+            counts = {b: w.layer_bits.count(b) for b in (2, 4, 8)}
+            by_bits = {b: (float(best[b]), float(np.mean([nbytes[i] for i in groups[b]]))) for b in (2, 4, 8)}
+            tot = sum(counts.values())
+            ms = sum(counts[b] * by_bits[b][0] for b in counts) / tot
+            bytes_launch = sum(counts[b] * by_bits[b][1] for b in counts) / tot
+            entry = {"by_bulk_width": {f"{b}bit": {"us_per_launch": round(by_bits[b][0] * 1e3, 2),
+                                                   "GBps": round(by_bits[b][1] / by_bits[b][0] / 1e6, 1),
+                                                   "frac": round(by_bits[b][1] / by_bits[b][0] / 1e6 / HBM_PEAK_GBPS, 4),
+                                                   "blocks_of_48": counts[b]} for b in (2, 4, 8)},
+                     "mean": "weighted by the workload's draw of bulk widths over its 48 blocks"}
+        entry.update({"us_per_launch": round(ms * 1e3, 2), "MB_per_launch": round(bytes_launch / 1e6, 1),
+                      "GBps": round(bytes_launch / ms / 1e6, 1), "frac": round(bytes_launch / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                      "units": units, "blocks_resident": L})
+        res[name] = entry
+        cache.close()
+        del arena, cache, kbuf, vbuf
+        torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(w, KV, q_np, seconds_hint=6.0):
+    """The oracle's attention (de-quantize + fp64 attention) on one sequence of one block of the same workload, timed
+    twice: with the BLAS pool limited to one thread, and with the pool as the process finds it.  The oracle's loop is
+    plain numpy: beyond the matrix products it runs on one core whatever the pool size."""
     from oracle import OracleCache, CacheConfig
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
     except Exception:                                   # pragma: no cover
-        threadpool_info = None
+        threadpool_info = threadpool_limits = None
     K, V = KV
     g = w.n_q_heads // w.n_kv_heads
     oc = OracleCache(CacheConfig(1, 1, w.n_q_heads, w.n_kv_heads, page_tokens=w.page_tokens, max_tokens=w.n_tokens),
@@ -428,19 +527,36 @@ def cpu_baseline(w, KV, q_np, seconds_hint=12.0):
     for n, bits in w.tiers_of_layer(0):
         oc.append(0, K[:1, :, t:t + n], V[:1, :, t:t + n], bits)
         t += n
-    reps, t0 = 0, time.time()
-    while True:
-        oc.attention(0, q_np[:1])
-        reps += 1
-        if time.time() - t0 > seconds_hint:
-            break
-    dt = (time.time() - t0) / reps
-    threads = 1
+
+    def run(seconds):
+        reps, t0 = 0, time.time()
+        while True:
+            oc.attention(0, q_np[:1])
+            reps += 1
+            if time.time() - t0 > seconds:
+                break
+        return (time.time() - t0) / reps, reps
+
+    pool = 1
     if threadpool_info is not None:
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    return {"value": round(w.n_tokens / dt, 1), "unit": "KV tokens/s", "cores": int(threads), "kind": "oracle",
+        pool = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    try:
+        nproc = len(os.sched_getaffinity(0))
+    except AttributeError:                              # pragma: no cover
+        nproc = os.cpu_count() or 1
+    dt_all, reps_all = run(seconds_hint)
+    single = None
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            dt_1, reps_1 = run(seconds_hint)
+        single = {"value": round(w.n_tokens / dt_1, 1), "threads": 1, "repetitions": reps_1, "s_each": round(dt_1, 3)}
+    return {"value": round(w.n_tokens / dt_all, 1), "unit": "KV tokens/s", "cores": int(min(pool, nproc)), "kind": "oracle",
+            "nproc": int(nproc), "blas_pool_threads": int(pool),
+            "all_threads": {"value": round(w.n_tokens / dt_all, 1), "threads": int(min(pool, nproc)),
+                            "repetitions": reps_all, "s_each": round(dt_all, 3)},
+            "single_thread": single,
             "sample": f"one sequence of one block ({w.n_kv_heads} KV heads x {w.n_tokens} tokens, {g} query heads each), "
-                      f"numpy fp64 de-quantize + attention, {reps} repetition(s), {dt:.2f} s each"}
+                      f"numpy fp64 de-quantize + attention; value = the all-threads figure"}
 
 
 def main():
@@ -451,6 +567,7 @@ def main():
     ap.add_argument("--workload", default="32b", choices=["7b", "14b", "32b", "70b"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-requant", action="store_true")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the short trains on the other workloads")
     ap.add_argument("--separate-calls", action="store_true",
                     help="step = kvq_quantize_append + kvq_decode_attention (two launches) instead of the fused call")
     ap.add_argument("--fused-merge", type=int, default=None)
@@ -559,12 +676,21 @@ def main():
         bytes_per_launch += sum((t1_ - t0_) * units * kq.kvq_bytes_per_token_head(b) for t0_, t1_, b in segs)
     bytes_per_launch /= L
     achieved = bytes_per_launch / (attn_ms * 1e-3) / 1e9
-    traffic = None
+    # HBM traffic per launch comes from two rocprofv3 --pmc runs of this script (see profiles/); the stored figure is
+    # tied to the sources it was measured with and is reported only while they are unchanged
+    traffic, traffic_note = None, "no counter run stored for these sources"
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    src_hash = library_source_sha16()
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        tj = json.load(open(tpath))
+        if tj.get("library_source_sha16") == src_hash:
+            traffic = tj.get("attention_only_kernel", {}).get("hbm_bytes_per_launch") if args.separate_calls \
+                else tj.get("hbm_bytes_per_launch")
+            traffic_note = f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, sources {src_hash}"
+        else:
+            traffic_note = f"stored counters belong to sources {tj.get('library_source_sha16')}, these are {src_hash}"
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_note,
                 "kernel": "kvq_attention_kernel" if args.separate_calls else "kvq_attention_append_kernel",
                 "avg_launch_ms": round(attn_ms, 5),
                 "min_launch_ms": round(float(np.min(train_ms)), 5), "median_launch_ms": round(float(np.median(train_ms)), 5),
@@ -595,6 +721,15 @@ def main():
     ceiling = measure_read_ceiling(kq, torch, cache)
     roofline["plain_read_kernel_GBps"] = ceiling
     roofline["frac_of_plain_read_kernel"] = round(achieved / ceiling, 4)
+    if not args.no_workloads:
+        cache.close()
+        del cache, arena
+        torch.cuda.empty_cache()
+        wl = other_workloads(kq, torch, kvq_synth, skip=args.workload)
+        wl[args.workload] = {"us_per_launch": round(attn_ms * 1e3, 2), "MB_per_launch": round(bytes_per_launch / 1e6, 1),
+                             "GBps": round(achieved, 1), "frac": round(achieved / HBM_PEAK_GBPS, 4), "units": units,
+                             "blocks_resident": L}
+        result["workloads"] = wl
     if not args.no_requant:
         result["requant"] = measure_requant(kq, torch)
         result["shift_strategies_mse"] = compare_shift_strategies(kq, torch, kvq_synth)
