@@ -145,6 +145,40 @@ __device__ inline void append16_tile(uint8_t* code, const uint16_t* in, int whic
                   (uint32_t)raw[8 * c + 6] | ((uint32_t)raw[8 * c + 7] << 16)};
 }
 
+// A V tile of a 16-bit page whose tokens are all new, written by one wavefront through LDS: the rows are read with
+// 16-byte loads (a wavefront instruction covers one contiguous KiB of the input), parked as [token][channel] in LDS
+// and picked up in the tile layout (lane (j, n): tokens 8j .. 8j+7 of channels 16 nt + n), where the plain path reads
+// the same 4,096 values with two-byte loads.  Rows are rotated by 32 bytes per 8 tokens so that the four lane
+// quarters, which read rows 8 apart, use different banks.  lds: 8 KiB of this wavefront alone, 16-byte aligned.
+__device__ inline void append16_v_tile_lds(uint8_t* code, const uint16_t* in, int tok0, int t_old, int t_new, int lane,
+                                           uint8_t* lds) {
+    const int j = lane >> 4, n = lane & 15;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const int chunk = c * 64 + lane, tl = chunk >> 4, ch8 = chunk & 15;
+        const int tok = tok0 + tl;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (tok < t_new) v = *reinterpret_cast<const u32x4*>(in + (uint64_t)(tok - t_old) * KVQ_D + 8 * ch8);
+        *reinterpret_cast<u32x4*>(lds + tl * 256 + ((ch8 * 16 + 32 * (tl >> 3)) & 255)) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {  // chunk c of the lane's string = channel block nt = c, tokens 8j + 0..7
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int r0 = 8 * j + 2 * e, r1 = r0 + 1;      // same group of 8 rows: same rotation
+            const int col = ((16 * c + n) * 2 + 32 * j) & 255;
+            const uint32_t lo = *reinterpret_cast<const uint16_t*>(lds + r0 * 256 + col);
+            const uint32_t hi = *reinterpret_cast<const uint16_t*>(lds + r1 * 256 + col);
+            w[e] = lo | (hi << 16);
+        }
+        *reinterpret_cast<u32x4*>(code + (c * 64 + lane) * 16) = u32x4{w[0], w[1], w[2], w[3]};
+    }
+}
+
 }  // namespace kvq_dev
 
 #endif

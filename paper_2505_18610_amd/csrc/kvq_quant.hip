@@ -28,12 +28,19 @@ __global__ __launch_bounds__(64) void kvq_append16_kernel(uint8_t* __restrict__ 
     const uint64_t tslot = (uint64_t)unit * tpp + tip;
     uint8_t* code = arena + (uint64_t)pd.code_off256 * 256u + (tslot * 2 + which) * (512u * 16);
     const uint16_t* in = (which ? v_in : k_in) + (uint64_t)unit * n_new * KVQ_D;
+    if (which && tile * KVQ_TILE_TOKENS >= t_old) {  // a V tile made of new tokens only: through LDS (wavefront-uniform)
+        __shared__ __attribute__((aligned(16))) uint8_t lds[32 * 256];
+        kvq_dev::append16_v_tile_lds(code, in, tile * KVQ_TILE_TOKENS, t_old, t_old + n_new, lane, lds);
+        return;
+    }
     kvq_dev::append16_tile(code, in, which, tile * KVQ_TILE_TOKENS, t_old, t_old + n_new, lane, which ? nullptr : rope,
                            (rinv && !which) ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
 }
 
 // Quantizing append (B = 8, 4, 2): same grid and contract as kvq_append_kernel, built on the row-owner core.
-template <int B>
+// PLAIN: keys arrive rotated and the block has no reparameterization (rope and rinv are null): the instantiation
+// carries none of that code, which is the bulk of the general kernel's registers.
+template <int B, bool PLAIN>
 __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ arena,
                                                           const KvqPageDesc* __restrict__ table,
                                                           const uint16_t* __restrict__ k_in,
@@ -66,7 +73,7 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
             u32x4 v = {0u, 0u, 0u, 0u};
             if (isnew) {
                 const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
-                if (which) v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
+                if (PLAIN || which) v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
                 else v = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr,
                                    rinv ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
             }
@@ -201,7 +208,7 @@ __global__ __launch_bounds__(64) void kvq_append_i16_kernel(uint8_t* __restrict_
 // that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by
 // owner lanes exactly like an append.
 template <int B>
-__global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ arena,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4, 4))) void kvq_quant16_kernel(uint8_t* __restrict__ arena,
                                                          const KvqRequantJob* __restrict__ jobs, int tpp,
                                                          uint32_t* __restrict__ flags, int gspan,
                                                          const KvqJobArgs ja) {
@@ -521,9 +528,18 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
     switch (bits + (int16 && bits == 16 ? 1 : 0)) {
         case 17: hipLaunchKernelGGL(kvq_append_i16_kernel, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, gspan, rinv, n_kv_heads, rope); break;
         case 16: hipLaunchKernelGGL(kvq_append16_kernel, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, rinv, n_kv_heads, rope); break;
-        case 8: hipLaunchKernelGGL(kvq_append_q_kernel<8>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
-        case 4: hipLaunchKernelGGL(kvq_append_q_kernel<4>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
-        case 2: hipLaunchKernelGGL(kvq_append_q_kernel<2>, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope); break;
+        case 8:
+            if (!rinv && !rope) hipLaunchKernelGGL((kvq_append_q_kernel<8, true>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
+            else hipLaunchKernelGGL((kvq_append_q_kernel<8, false>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
+            break;
+        case 4:
+            if (!rinv && !rope) hipLaunchKernelGGL((kvq_append_q_kernel<4, true>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
+            else hipLaunchKernelGGL((kvq_append_q_kernel<4, false>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
+            break;
+        case 2:
+            if (!rinv && !rope) hipLaunchKernelGGL((kvq_append_q_kernel<2, true>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
+            else hipLaunchKernelGGL((kvq_append_q_kernel<2, false>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
+            break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
