@@ -15,13 +15,20 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes"]
 
 
-def build(verbose: bool = False) -> str:
+STAMPS_LIB = os.path.join(HERE, "libkvq_stamps.so")
+
+
+def build(verbose: bool = False, phase_stamps: bool = False) -> str:
+    """phase_stamps: build the measurement variant libkvq_stamps.so (attention kernels that record when a workgroup
+    passes each phase, see csrc/kvq_phase_stamps.h) instead of the library; nothing loads it but phase_table.py."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
+    flags = FLAGS + (["-DKVQ_PHASE_STAMPS"] if phase_stamps else [])
+    lib = STAMPS_LIB if phase_stamps else LIB
     for src in SOURCES:
-        obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc, *FLAGS, "-I", os.path.join(HERE, "..", "include"), "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(CSRC, os.path.splitext(src)[0] + (".stamps.o" if phase_stamps else ".o"))
+        cmd = [hipcc, *flags, "-I", os.path.join(HERE, "..", "include"), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -33,12 +40,12 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out.strip():
             print(out)
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, phase_stamps="--phase-stamps" in sys.argv))

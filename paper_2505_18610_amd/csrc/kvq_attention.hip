@@ -47,9 +47,10 @@ __global__ __launch_bounds__(KVQ_ATTN_THREADS) void kvq_merge_kernel(const KvqAt
 
 }  // namespace
 
-#ifdef KVQ_DEBUG_TIMING
-extern "C" int kvq_debug_read(unsigned long long* host) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kvq_dbg), sizeof(unsigned long long) * 1024 * 8);
+#ifdef KVQ_PHASE_STAMPS
+// Measurement build only: copies the stamps of the last launch of the single-cache kernels to the host.
+extern "C" int kvq_phase_stamps_read(unsigned long long* host) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(kvq_phase_stamps), sizeof(unsigned long long) * KVQ_STAMP_WGS * KVQ_STAMP_SLOTS);
 }
 #endif
 

@@ -752,10 +752,10 @@ struct AttnShared {
 };
 
 
-#ifdef KVQ_DEBUG_TIMING
-static __device__ unsigned long long kvq_dbg[1024 * 16];
-#define KVQ_STAMP(k) do { if ((threadIdx.x & 511) == 0) kvq_dbg[(blockIdx.y * gridDim.x + blockIdx.x) % 1024 * 16 + (k)] = wall_clock64(); } while (0)
-#define KVQ_STAMP_ID() do { if ((threadIdx.x & 511) == 0) kvq_dbg[(blockIdx.y * gridDim.x + blockIdx.x) % 1024 * 16 + 7] = ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32) | (unsigned)__builtin_amdgcn_s_getreg(4 | (31 << 11)); } while (0)
+// Phase stamps: hooks of the measurement build (python -m paper_2505_18610_amd.build --phase-stamps), which records
+// when a workgroup passes the points marked below; the library proper compiles them to nothing.
+#ifdef KVQ_PHASE_STAMPS
+#include "kvq_phase_stamps.h"
 #else
 #define KVQ_STAMP(k) do { } while (0)
 #define KVQ_STAMP_ID() do { } while (0)
