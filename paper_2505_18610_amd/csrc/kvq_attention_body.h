@@ -634,7 +634,9 @@ __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds,
         load_string<2 * W>(cur.code, c.lane_off, kw);
         if constexpr (has_meta<B>()) mreg = load_stream16(cur.meta + c.lane_off);
         load_string<2 * W>(cur.code + 512u * W, c.lane_off, vw);
-        if (Q.cls != q_class<B>()) load_q_ops(Q, q_lds, lane, q_class<B>(), c.scale_log2);
+        // the query operands are arranged afresh at the start of every run, also when the last run had the same
+        // arrangement: carried from run to run they would occupy 16 registers across the dispatch in between
+        load_q_ops(Q, q_lds, lane, q_class<B>(), c.scale_log2);
         for (;;) {
             float s[1][2][4];
             uint32_t pop[1][4];
@@ -675,7 +677,7 @@ __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds,
         Stage<B, TPI> sg[N];
         issue_stage<B, TPI>(sg[0], c, c.next);
         advance_begin(c);
-        if (Q.cls != B) load_q_ops(Q, q_lds, lane, B, c.scale_log2);
+        load_q_ops(Q, q_lds, lane, B, c.scale_log2);  // afresh in every run, see above
         advance_end(c);
         int n_live = 1, head = 0;
         // (the run is left by jumps, not by flags: a flag-guarded chain of steps would give the control-flow
