@@ -108,6 +108,7 @@ void kvq_cache_destroy(kvq_cache_t* cache);
 
 /* Quantize-on-append (Sec. 2.2 Eq. 1-2; Sec. 3.1).
  *   k_dev, v_dev: fp16 [batch, n_kv_heads, n_new, head_dim], contiguous; keys already carry RoPE.
+ *   n_new < 2^23 tokens per call (KVQ_E_INVALID beyond; append longer inputs in pieces).
  *   entry_bits: 0 = the policy's entry width (16 while a window is configured or under OLDEST_FIRST, else
  *   the block's current width); 16/8/4/2 = store at exactly that width (state construction).  A width that
  *   differs from the partially filled last page's width is KVQ_E_STATE.

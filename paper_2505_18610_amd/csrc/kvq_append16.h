@@ -73,6 +73,9 @@ __device__ inline u32x4 load_key8(const uint16_t* row, int ch0, const float* rop
 // partially filled tiles stay well defined); otherwise only the new tokens' elements are stored - whole 16-byte
 // chunks for K, single fp16 values for V.  rope: table of the new tokens, fp32 [t_new - t_old][128], or null;
 // rinv_head: the 128 reciprocal reparameterization factors of this KV head, or null (keys only).
+// STREAM: a tile written in full goes out with streaming stores (bulk appends: the tile is read much later; not for a
+// caller that reads the tile back at once).
+template <bool STREAM = false>
 __device__ inline void append16_tile(uint8_t* code, const uint16_t* in, int which, int tok0, int t_old, int t_new,
                                      int lane, const float* rope, const float* rinv_head) {
     const int j = lane >> 4, n = lane & 15;
@@ -137,18 +140,20 @@ __device__ inline void append16_tile(uint8_t* code, const uint16_t* in, int whic
         return;
     }
 #pragma unroll
-    for (int c = 0; c < 8; ++c)
-        *reinterpret_cast<u32x4*>(code + (c * 64 + lane) * 16) =
-            u32x4{(uint32_t)raw[8 * c] | ((uint32_t)raw[8 * c + 1] << 16),
-                  (uint32_t)raw[8 * c + 2] | ((uint32_t)raw[8 * c + 3] << 16),
-                  (uint32_t)raw[8 * c + 4] | ((uint32_t)raw[8 * c + 5] << 16),
-                  (uint32_t)raw[8 * c + 6] | ((uint32_t)raw[8 * c + 7] << 16)};
+    for (int c = 0; c < 8; ++c) {
+        const u32x4 v = {(uint32_t)raw[8 * c] | ((uint32_t)raw[8 * c + 1] << 16),
+                         (uint32_t)raw[8 * c + 2] | ((uint32_t)raw[8 * c + 3] << 16),
+                         (uint32_t)raw[8 * c + 4] | ((uint32_t)raw[8 * c + 5] << 16),
+                         (uint32_t)raw[8 * c + 6] | ((uint32_t)raw[8 * c + 7] << 16)};
+        if (STREAM) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(code + (c * 64 + lane) * 16));
+        else *reinterpret_cast<u32x4*>(code + (c * 64 + lane) * 16) = v;
+    }
 }
 
 // A V tile of a 16-bit page whose tokens are all new, written by one wavefront through LDS: the rows are read with
 // 16-byte loads (a wavefront instruction covers one contiguous KiB of the input), parked as [token][channel] in LDS
 // and picked up in the tile layout (lane (j, n): tokens 8j .. 8j+7 of channels 16 nt + n), where the plain path reads
-// the same 4,096 values with two-byte loads.  Rows are rotated by 32 bytes per 8 tokens so that the four lane
+// the same 4,096 values with two-byte loads; streaming stores, as the tile is read much later.  Rows are rotated by 32 bytes per 8 tokens so that the four lane
 // quarters, which read rows 8 apart, use different banks.  lds: 8 KiB of this wavefront alone, 16-byte aligned.
 __device__ inline void append16_v_tile_lds(uint8_t* code, const uint16_t* in, int tok0, int t_old, int t_new, int lane,
                                            uint8_t* lds) {
@@ -175,7 +180,7 @@ __device__ inline void append16_v_tile_lds(uint8_t* code, const uint16_t* in, in
             const uint32_t hi = *reinterpret_cast<const uint16_t*>(lds + r1 * 256 + col);
             w[e] = lo | (hi << 16);
         }
-        *reinterpret_cast<u32x4*>(code + (c * 64 + lane) * 16) = u32x4{w[0], w[1], w[2], w[3]};
+        __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(code + (c * 64 + lane) * 16));
     }
 }
 

@@ -542,7 +542,7 @@ kvq_status_t plan_append(const kvq_cache_t* c, int32_t layer, int32_t n_new, int
 
 bool append_args_ok(const kvq_cache_t* c, int32_t layer, const void* k_dev, const void* v_dev, int32_t n_new,
                     int32_t entry_bits) {
-    if (!c || layer < 0 || layer >= c->cfg.n_layers || n_new < 0) return false;
+    if (!c || layer < 0 || layer >= c->cfg.n_layers || n_new < 0 || n_new >= KVQ_MAX_APPEND_TOKENS) return false;
     if (entry_bits != 0 && !valid_bits(entry_bits)) return false;
     if (n_new > 0 && !c->dry && (!k_dev || !v_dev)) return false;
     return true;

@@ -56,6 +56,9 @@ struct KvqAttnParams {
 };
 
 // kvq_quant.hip
+// One append call takes fewer than 2^23 tokens per sequence: the kernels address the rows of a unit's input through a
+// buffer descriptor with 32-bit byte offsets (256 bytes per row; offsets up to a few tiles beyond the last row occur).
+#define KVQ_MAX_APPEND_TOKENS (1 << 23)
 hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table, const void* k_in,
                              const void* v_in, int t_old, int n_new, int tiles_per_page, int units,
                              const KvqPageDesc* first_two, int first_page, uint32_t* flags, int group,

@@ -33,8 +33,8 @@ __global__ __launch_bounds__(64) void kvq_append16_kernel(uint8_t* __restrict__ 
         kvq_dev::append16_v_tile_lds(code, in, tile * KVQ_TILE_TOKENS, t_old, t_old + n_new, lane, lds);
         return;
     }
-    kvq_dev::append16_tile(code, in, which, tile * KVQ_TILE_TOKENS, t_old, t_old + n_new, lane, which ? nullptr : rope,
-                           (rinv && !which) ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
+    kvq_dev::append16_tile<true>(code, in, which, tile * KVQ_TILE_TOKENS, t_old, t_old + n_new, lane, which ? nullptr : rope,
+                                 (rinv && !which) ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
 }
 
 // Quantizing append (B = 8, 4, 2): same grid and contract as kvq_append_kernel, built on the row-owner core.
@@ -62,26 +62,46 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
     const int t_new = t_old + n_new, tok0 = tile * KVQ_TILE_TOKENS;
     const uint16_t* in = (which ? v_in : k_in) + (uint64_t)unit * n_new * KVQ_D;
     const int grp = lane & 3;
+    // every load of the tile first (both passes: 8 x 16 bytes per lane in flight), then the arithmetic
+    uint32_t w[2][16];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tok = tok0 + 16 * pass + (lane >> 2);
+        u32x4 v[4];
+        if (PLAIN || which) {
+            // Buffer loads with the unit's n_new rows as the buffer: a lane whose token is not new (before t_old: the
+            // offset wraps to a huge value; at or after t_new: beyond the last row) is out of range and reads zeros,
+            // which is what such a token quantizes -- no branch, no select.  (n_new < 2^23: the offsets cannot wrap
+            // back into the buffer.)
+            const __amdgpu_buffer_rsrc_t rows =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(in), 0, n_new * (KVQ_D * 2), 0x00020000);
+            const uint32_t off = (uint32_t)(tok - t_old) * (uint32_t)(KVQ_D * 2) + 64u * grp;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(rows, (int)(off + 16u * c), 0, 0);
+        } else {
+            const bool isnew = tok >= t_old && tok < t_new;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[c] = u32x4{0u, 0u, 0u, 0u};
+            if (isnew) {
+                const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    v[c] = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr,
+                                     rinv ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            w[pass][4 * c] = v[c].x; w[pass][4 * c + 1] = v[c].y; w[pass][4 * c + 2] = v[c].z; w[pass][4 * c + 3] = v[c].w;
+        }
+    }
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
         const int tl = 16 * pass + (lane >> 2);
         const int tok = tok0 + tl;
-        const bool isnew = tok >= t_old && tok < t_new;
-        uint32_t w[16];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (isnew) {
-                const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
-                if (PLAIN || which) v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
-                else v = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr,
-                                   rinv ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
-            }
-            w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
-        }
         float codes[32];
         uint16_t S, Z;
-        quantize_owner<B>(w, codes, &S, &Z, gspan);  // tokens that are not new quantize zeros: codes 0, S = Z = 0
+        quantize_owner<B>(w[pass], codes, &S, &Z, gspan);  // tokens that are not new quantize zeros: codes 0, S = Z = 0
         note_large_v_scale(flags, which, S);
         scatter_codes(lds, which, tl, grp, codes);
         if (tok >= t_old) store_meta_owner(meta, which, tl, grp, S, Z);
@@ -100,16 +120,23 @@ __global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ 
         for (int i = 0; i < 8; ++i)
             if (tok0 + 8 * j + i < t_old) keep |= 1u << i;
     }
-    if (tok0 < t_old && keep) {
-        uint32_t old[2 * B];
-        load_chunks<B>(code, lane, old);
+    if (tok0 < t_old) {  // (wavefront-uniform) the tile already holds tokens: it is rewritten step by step, plain stores
+        if (keep) {
+            uint32_t old[2 * B];
+            load_chunks<B>(code, lane, old);
 #pragma unroll
-        for (int d = 0; d < 2 * B; ++d) {
-            uint32_t m = which ? v_token_mask<B>(keep, d) : (((keep >> (d / B)) & 1u) ? 0xffffffffu : 0u);
-            str[d] = (old[d] & m) | (str[d] & ~m);
+            for (int d = 0; d < 2 * B; ++d) {
+                uint32_t m = which ? v_token_mask<B>(keep, d) : (((keep >> (d / B)) & 1u) ? 0xffffffffu : 0u);
+                str[d] = (old[d] & m) | (str[d] & ~m);
+            }
         }
+        store_chunks<B>(code, lane, str);
+        asm volatile("" ::: "memory");  // keeps the two kinds of store apart (merged, they would both be plain ones)
+        return;
     }
-    store_chunks<B>(code, lane, str);
+    // a tile made of new tokens only is written once and read much later: streaming stores (with plain stores the
+    // bulk appends run a quarter slower)
+    store_chunks_stream<B>(code, lane, str);
 }
 
 // Append into the integer 16-bit tier: Eq. 1-2 with 2^16 - 1 levels by the same owner lanes; the high and the low
@@ -191,7 +218,12 @@ __global__ __launch_bounds__(64) void kvq_append_i16_kernel(uint8_t* __restrict_
                 str[d] = (old[d] & m) | (str[d] & ~m);
             }
         }
-        store_chunks<8>(dst, lane, str);
+        if (tok0 >= t_old) {
+            store_chunks_stream<8>(dst, lane, str);
+        } else {
+            store_chunks<8>(dst, lane, str);
+            asm volatile("" ::: "memory");  // keeps the two kinds of store apart
+        }
     }
 }
 

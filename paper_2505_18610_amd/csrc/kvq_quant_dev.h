@@ -64,7 +64,11 @@ template <int B>
 __device__ inline void load_chunks_stream(const uint8_t* tile, int lane, uint32_t (&str)[2 * B]) {
 #pragma unroll
     for (int c = 0; c < B / 2; ++c) {
+#ifdef KVQ_TRY_PLAIN_LOADS
+        u32x4 v = *reinterpret_cast<const u32x4*>(tile + (c * 64 + lane) * 16);
+#else
         u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + (c * 64 + lane) * 16));
+#endif
         str[4 * c] = v.x; str[4 * c + 1] = v.y; str[4 * c + 2] = v.z; str[4 * c + 3] = v.w;
     }
 }
@@ -91,6 +95,16 @@ __device__ inline uint32_t pk_max_u(uint32_t a, uint32_t b) {
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b)));
 }
 
+// x - mn for the fp16 value in the low (hi = 0) or high (hi = 1) half of w, in one instruction: x * 1.0 - mn with
+// the single rounding of a fused multiply-add, which is the rounding of the fp32 subtraction (the conversion of
+// x to fp32 is exact), instead of a conversion followed by a subtraction.
+__device__ inline float half_minus(uint32_t w, int hi, float mn) {
+    float r;
+    if (hi) asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(mn));
+    else asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(mn));
+    return r;
+}
+
 #define KVQ_LDS_CODES_K 4096                       // K: [32 tokens][128 channels] code bytes
 #define KVQ_LDS_VGRP (32 * 32 + 16)                // V: per group [32 channels][32 tokens] code bytes, skewed
 #define KVQ_LDS_CODES (4 * KVQ_LDS_VGRP)           // room for either arrangement
@@ -104,9 +118,9 @@ template <int B>
 __device__ inline void quantize_owner(const uint32_t (&w)[16], float (&codes)[32], uint16_t* S, uint16_t* Z,
                                       int gspan) {
     constexpr int levels = (1 << B) - 1;
-    uint32_t mn2 = w[0], mx2 = w[0];
-#pragma unroll
-    for (int k = 1; k < 16; ++k) { mn2 = pk_min_u(mn2, w[k]); mx2 = pk_max_u(mx2, w[k]); }
+    uint32_t mn2 = pk_min_u(w[0], w[1]), mx2 = pk_max_u(w[0], w[1]);  // (no plain copy of a loaded register: the copy
+#pragma unroll                                                        //  would be placed, with a full wait, beside the load)
+    for (int k = 2; k < 16; ++k) { mn2 = pk_min_u(mn2, w[k]); mx2 = pk_max_u(mx2, w[k]); }
     float mn = fminf(h2f((uint16_t)(mn2 & 0xffff)), h2f((uint16_t)(mn2 >> 16)));
     float mx = fmaxf(h2f((uint16_t)(mx2 & 0xffff)), h2f((uint16_t)(mx2 >> 16)));
     if (gspan >= 2) { mn = fminf(mn, __shfl_xor(mn, 1)); mx = fmaxf(mx, __shfl_xor(mx, 1)); }
@@ -132,22 +146,25 @@ __device__ inline void quantize_owner(const uint32_t (&w)[16], float (&codes)[32
         rcp = fmaf(r0, fmaf(-Sf, r0, 1.0f), r0);
     }
     constexpr float near_half = 0.5f - 2.5e-7f * (float)(levels + 1);
+    // No element's quotient exceeds that of the group maximum (x <= mx and every step is monotone), so the clamp to
+    // the top level is decided once per group instead of once per element; a group that needs it (S rounded down
+    // to a subnormal fp16) takes the division path below, which clamps.
+    const bool over = rintf((mx - mn) * rcp) > (float)levels;
     float worst = 0.0f;
 #pragma unroll
     for (int e = 0; e < 32; ++e) {
-        const float x = h2f((uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffff)));
-        const float t = (x - mn) * rcp;
+        const float t = half_minus(w[e >> 1], e & 1, mn) * rcp;
         const float r = rintf(t);
         worst = fmaxf(worst, fabsf(t - r));
-        codes[e] = fminf(r, (float)levels);
+        codes[e] = r;
     }
-    if (__any(worst > near_half)) {
+    if (__any(worst > near_half || over)) {
         asm volatile("" ::: "memory");  // keep this a branch
 #pragma unroll
         for (int e = 0; e < 32; ++e) {
             const float x = h2f((uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffff)));
             const float t = (x - mn) * rcp;
-            if (fabsf(t - rintf(t)) > near_half) codes[e] = (float)code_of(x, mn, Sf, levels);
+            if (over || fabsf(t - rintf(t)) > near_half) codes[e] = (float)code_of(x, mn, Sf, levels);
         }
     }
 }
@@ -245,9 +262,24 @@ struct KvqAppendPages {
     KvqPageDesc d[2];
     int first_page;  // -1: use the table
 };
+// (The offsets are pinned to scalar registers inside each branch: left alone, the two branches are merged into one
+//  load through a selected pointer, which can only be a flat load, and while a flat load is pending every wait for a
+//  global load becomes a wait for all of them.)
 __device__ inline KvqPageDesc append_desc(const KvqPageDesc* table, const KvqAppendPages& ap, int page) {
-    if (ap.first_page < 0) return table[page];
-    return page == ap.first_page ? ap.d[0] : ap.d[1];
+    KvqPageDesc r;
+    r.bits = 0u;
+    r.int16 = 0u;
+    if (ap.first_page < 0) {
+        r.code_off256 = table[page].code_off256;
+        r.meta_off256 = table[page].meta_off256;
+        asm volatile("" : "+s"(r.code_off256), "+s"(r.meta_off256));
+    } else {
+        const bool first = page == ap.first_page;
+        r.code_off256 = first ? ap.d[0].code_off256 : ap.d[1].code_off256;
+        r.meta_off256 = first ? ap.d[0].meta_off256 : ap.d[1].meta_off256;
+        asm volatile("" : "+s"(r.code_off256), "+s"(r.meta_off256));
+    }
+    return r;
 }
 
 // Appends the tokens [t_old, t_new) that fall into one tile of the integer 16-bit tier to its K (which = 0) or V (1)
