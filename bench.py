@@ -126,6 +126,39 @@ def measure_requant(kq, torch):
     return out
 
 
+def measure_bulk_append(kq, torch):
+    """Bulk quantize-on-append of 14B-shaped blocks of 16,384 tokens (64 units) at every entry width; GB/s = (fp16 read
+    + codes and metadata written) / time.  Per width a fresh cache on the same arena: one untimed append, then five
+    blocks queued back to back behind a filler kernel and one event pair.  K and V inputs are 268 MB each."""
+    B, Hkv, T, P, L = 8, 8, 16384, 256, 6
+    units = B * Hkv
+    cfg = kq.KvqConfig(L, B, 40, Hkv, T, page_tokens=P)
+    arena = torch.empty(kq.kvq_arena_bytes(cfg, int(L * T * units * 512 * 1.2)), dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(15)
+    k = torch.randn((B, Hkv, T, 128), device="cuda", generator=g).half()
+    v = torch.randn((B, Hkv, T, 128), device="cuda", generator=g).half()
+    out = {}
+    for bits in (16, 8, 4, 2):
+        cache = kq.KvqCache(cfg, [1 << 60] * L, [2] * L, arena=arena)
+        filler = QueueFiller(torch, cache)
+        cache.kvq_quantize_append(0, k, v, bits)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        filler()
+        e0.record()
+        for layer in range(1, L):
+            cache.kvq_quantize_append(layer, k, v, bits)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / (L - 1)
+        moved = T * units * (512 + kq.kvq_bytes_per_token_head(bits))
+        gbps = moved / ms / 1e6
+        out[f"{bits}bit"] = {"ms": round(ms, 4), "MB_moved": round(moved / 1e6, 1), "GBps": round(gbps, 1),
+                             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+        cache.close()
+    return out
+
+
 def int16_tier(kq, torch, kvq_synth):
     """The integer 16-bit tier (INT16 format of Sec. 4.1.2) beside the raw fp16 tier.
     requant_16to8: Eq. 3 at b = 8 on 14B-shaped blocks of 16,384 tokens (64 units), six blocks behind one event pair as
@@ -732,6 +765,7 @@ def main():
         result["workloads"] = wl
     if not args.no_requant:
         result["requant"] = measure_requant(kq, torch)
+        result["bulk_append"] = measure_bulk_append(kq, torch)
         result["shift_strategies_mse"] = compare_shift_strategies(kq, torch, kvq_synth)
         result["reparam_effect"] = reparam_effect(kq, torch, kvq_synth)
         result["allocation"] = allocation_demo(kq, torch, kvq_synth)
