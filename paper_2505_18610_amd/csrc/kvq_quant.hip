@@ -240,12 +240,17 @@ __global__ __launch_bounds__(64) void kvq_append_i16_kernel(uint8_t* __restrict_
 // that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by
 // owner lanes exactly like an append.
 template <int B>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4, 4))) void kvq_quant16_kernel(uint8_t* __restrict__ arena,
+__global__ __launch_bounds__(64) void kvq_quant16_kernel(uint8_t* __restrict__ arena,
                                                          const KvqRequantJob* __restrict__ jobs, int tpp,
                                                          uint32_t* __restrict__ flags, int gspan,
                                                          const KvqJobArgs ja) {
-    __shared__ __attribute__((aligned(16))) uint8_t raw_lds[32 * 128 * 2];
-    __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
+    // One LDS block: [pad | raw rows 0..15 | raw rows 16..31].  The codes of both passes go to the first KVQ_LDS_CODES bytes,
+    // i.e. the pad and the rows of the first pass, which every lane has read by the time the first codes are written (the
+    // LDS carries out a wavefront's instructions in order); the rows of the second pass are not touched.  8.1 KiB per
+    // wavefront instead of 12.1: the LDS then admits 19 wavefronts per compute unit instead of 13 (16 -> 8: +7 %).
+    __shared__ __attribute__((aligned(16))) uint8_t lds_block[(KVQ_LDS_CODES - 16 * 256) + 32 * 256];
+    uint8_t* const lds = lds_block;
+    uint8_t* const raw_lds = lds_block + (KVQ_LDS_CODES - 16 * 256);
     const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
     const int which = blockIdx.x & 1;
     const int idx = blockIdx.x >> 1;
