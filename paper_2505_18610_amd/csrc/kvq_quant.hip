@@ -37,22 +37,30 @@ __global__ __launch_bounds__(64) void kvq_append16_kernel(uint8_t* __restrict__ 
                                  (rinv && !which) ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
 }
 
-// Quantizing append (B = 8, 4, 2): same grid and contract as kvq_append_kernel, built on the row-owner core.
+// Quantizing append (B = 8, 4, 2), built on the row-owner core: grid.x = ceil(n_strings / KVQ_APPEND_WG_WAVES) workgroups,
+// n_strings = 2 * touched tiles (K and V string of each), grid.y = unit; one wavefront per string.
 // PLAIN: keys arrive rotated and the block has no reparameterization (rope and rinv are null): the instantiation
 // carries none of that code, which is the bulk of the general kernel's registers.
+// Four wavefronts per workgroup, each with a (tile, K | V) string of its own and its own LDS: 1 to 2 % faster on bulk
+// appends than one-wavefront workgroups (a quarter of the workgroups to dispatch); nothing is shared between them.
+#define KVQ_APPEND_WG_WAVES 4
 template <int B, bool PLAIN>
-__global__ __launch_bounds__(64) void kvq_append_q_kernel(uint8_t* __restrict__ arena,
+__global__ __launch_bounds__(64 * KVQ_APPEND_WG_WAVES) void kvq_append_q_kernel(uint8_t* __restrict__ arena,
                                                           const KvqPageDesc* __restrict__ table,
                                                           const uint16_t* __restrict__ k_in,
                                                           const uint16_t* __restrict__ v_in, int t_old,
                                                           int n_new, int tpp, int tile0, KvqAppendPages ap,
                                                           uint32_t* __restrict__ flags, int gspan,
                                                           const float* __restrict__ rinv, int n_kv_heads,
-                                                          const float* __restrict__ rope) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[KVQ_LDS_CODES];
-    const int lane = threadIdx.x, j = lane >> 4, n = lane & 15;
-    const int which = blockIdx.x & 1;
-    const int tile = tile0 + (blockIdx.x >> 1);
+                                                          const float* __restrict__ rope, int n_strings) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[KVQ_APPEND_WG_WAVES][KVQ_LDS_CODES];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint8_t* const lds = lds_all[wave];
+    const int lane = threadIdx.x & 63, j = lane >> 4, n = lane & 15;
+    const int string = blockIdx.x * KVQ_APPEND_WG_WAVES + wave;  // (tile, K | V) of this wavefront
+    if (string >= n_strings) return;
+    const int which = string & 1;
+    const int tile = tile0 + (string >> 1);
     const int unit = blockIdx.y;
     const int page = tile / tpp, tip = tile - page * tpp;
     const KvqPageDesc pd = append_desc(table, ap, page);
@@ -556,6 +564,8 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
     int tile0 = t_old / KVQ_TILE_TOKENS;
     int tile1 = (t_old + n_new + KVQ_TILE_TOKENS - 1) / KVQ_TILE_TOKENS;
     dim3 grid(2 * (tile1 - tile0), units), block(64);
+    const int n_strings = 2 * (tile1 - tile0);
+    const dim3 qgrid((n_strings + KVQ_APPEND_WG_WAVES - 1) / KVQ_APPEND_WG_WAVES, units), qblock(64 * KVQ_APPEND_WG_WAVES);
     const uint16_t* k = static_cast<const uint16_t*>(k_in);
     const uint16_t* v = static_cast<const uint16_t*>(v_in);
     KvqAppendPages ap;
@@ -566,16 +576,16 @@ hipError_t kvq_launch_append(int bits, uint8_t* arena, const KvqPageDesc* table,
         case 17: hipLaunchKernelGGL(kvq_append_i16_kernel, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, gspan, rinv, n_kv_heads, rope); break;
         case 16: hipLaunchKernelGGL(kvq_append16_kernel, grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, rinv, n_kv_heads, rope); break;
         case 8:
-            if (!rinv && !rope) hipLaunchKernelGGL((kvq_append_q_kernel<8, true>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
-            else hipLaunchKernelGGL((kvq_append_q_kernel<8, false>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
+            if (!rinv && !rope) hipLaunchKernelGGL((kvq_append_q_kernel<8, true>), qgrid, qblock, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope, n_strings);
+            else hipLaunchKernelGGL((kvq_append_q_kernel<8, false>), qgrid, qblock, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope, n_strings);
             break;
         case 4:
-            if (!rinv && !rope) hipLaunchKernelGGL((kvq_append_q_kernel<4, true>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
-            else hipLaunchKernelGGL((kvq_append_q_kernel<4, false>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
+            if (!rinv && !rope) hipLaunchKernelGGL((kvq_append_q_kernel<4, true>), qgrid, qblock, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope, n_strings);
+            else hipLaunchKernelGGL((kvq_append_q_kernel<4, false>), qgrid, qblock, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope, n_strings);
             break;
         case 2:
-            if (!rinv && !rope) hipLaunchKernelGGL((kvq_append_q_kernel<2, true>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
-            else hipLaunchKernelGGL((kvq_append_q_kernel<2, false>), grid, block, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope);
+            if (!rinv && !rope) hipLaunchKernelGGL((kvq_append_q_kernel<2, true>), qgrid, qblock, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope, n_strings);
+            else hipLaunchKernelGGL((kvq_append_q_kernel<2, false>), qgrid, qblock, 0, s, arena, table, k, v, t_old, n_new, tiles_per_page, tile0, ap, flags, gspan, rinv, n_kv_heads, rope, n_strings);
             break;
         default: return hipErrorInvalidValue;
     }
