@@ -792,16 +792,18 @@ __device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, f
         mlr[k] = float2v{-INFINITY, 0.f};
         if (e < ns * g) { const int sp = e / g, h = e - sp * g; mlr[k] = load_pair(pml + sp * 32 + 2 * h, AGENT); }
     }
-    float2v v[16][2];
+    // The unit's partial outputs as a buffer of ns splits: 16-byte loads (half the load instructions of 8-byte pairs,
+    // and their issue is what the merge of many splits waits for), no branch -- a split index beyond ns is out of
+    // range and reads zeros, and so does an idle thread, whose offset is put out of range.  AGENT: device-scope
+    // loads (sc1), as the 8-byte atomic loads of the (m, l) pairs are.
+    const __amdgpu_buffer_rsrc_t slab =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(po), 0, ns * 16 * KVQ_D * (int)sizeof(float), 0x00020000);
+    float4v v[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
         const int sp = sgi + k * G;
-        v[k][0] = v[k][1] = float2v{0.f, 0.f};
-        if (active && sp < ns) {
-            const float* src = po + ((size_t)sp * 16 + head) * KVQ_D + 4 * d4;
-            v[k][0] = load_pair(src, AGENT);
-            v[k][1] = load_pair(src + 2, AGENT);
-        }
+        const uint32_t off = active ? (uint32_t)((sp * 16 + head) * KVQ_D + 4 * d4) * 4u : 0xfffffff0u;
+        v[k] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(slab, (int)off, 0, AGENT ? 16 : 0));
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -836,7 +838,7 @@ __device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, f
             const int sp = sgi + k * G;
             if (sp < ns) {
                 const float f = f_lds[sp * 16 + head];
-                acc += float4v{v[k][0][0], v[k][0][1], v[k][1][0], v[k][1][1]} * f;
+                acc += v[k] * f;
             }
         }
         for (int sp = sgi + 16 * G; sp < ns; sp += G) {
