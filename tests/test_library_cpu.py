@@ -64,6 +64,14 @@ def test_invalid_configs_and_arguments():
     assert e.value.status == kq.KVQ_E_STATE
     assert c.kvq_cache_describe(0)[0] == [(0, 40, 8)]
     assert kq.kvq_status_string(kq.KVQ_E_OOM) != kq.kvq_status_string(kq.KVQ_OK)
+    # one append call takes fewer than 2^23 tokens (the kernels address a unit's new rows with 32-bit byte offsets)
+    big = kq.KvqCache(kq.KvqConfig(**{**good, "max_tokens": 1 << 24, "page_tokens": 1024}), [1 << 60], [2], arena=None,
+                      arena_bytes=1 << 40)
+    with pytest.raises(kq.KvqError) as e:
+        big.kvq_quantize_append(0, None, None, n_new=1 << 23, entry_bits=2)
+    assert e.value.status == kq.KVQ_E_INVALID
+    big.kvq_quantize_append(0, None, None, n_new=(1 << 23) - 1, entry_bits=2)
+    assert big.kvq_cache_describe(0)[2] == (1 << 23) - 1
 
 
 def _pair(policy, P, W, sink, budget, fbit, meta=1, Tmax=4096, B=2, H=2, group=32, tier16=0):
