@@ -798,12 +798,17 @@ __device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, f
     // loads (sc1), as the 8-byte atomic loads of the (m, l) pairs are.
     const __amdgpu_buffer_rsrc_t slab =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(po), 0, ns * 16 * KVQ_D * (int)sizeof(float), 0x00020000);
+    // A load instruction costs its issue slots whether or not it is in range, so with few splits per slot group
+    // only the first four are issued.
+    const bool many = ns > 4 * G;
     float4v v[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
         const int sp = sgi + k * G;
         const uint32_t off = active ? (uint32_t)((sp * 16 + head) * KVQ_D + 4 * d4) * 4u : 0xfffffff0u;
-        v[k] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(slab, (int)off, 0, AGENT ? 16 : 0));
+        v[k] = float4v{0.f, 0.f, 0.f, 0.f};
+        if (k < 4 || many)
+            v[k] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(slab, (int)off, 0, AGENT ? 16 : 0));
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
