@@ -16,18 +16,22 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
 
 
 STAMPS_LIB = os.path.join(HERE, "libkvq_stamps.so")
+NOARITH_LIB = os.path.join(HERE, "libkvq_noarith.so")
 
 
-def build(verbose: bool = False, phase_stamps: bool = False) -> str:
+def build(verbose: bool = False, phase_stamps: bool = False, no_arithmetic: bool = False) -> str:
     """phase_stamps: build the measurement variant libkvq_stamps.so (attention kernels that record when a workgroup
-    passes each phase, see csrc/kvq_phase_stamps.h) instead of the library; nothing loads it but phase_table.py."""
+    passes each phase, see csrc/kvq_phase_stamps.h) instead of the library.  no_arithmetic: build libkvq_noarith.so,
+    whose attention kernels load every tile but compute on none (the floor of the launch; results meaningless).
+    Nothing loads either of them but phase_table.py."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
-    flags = FLAGS + (["-DKVQ_PHASE_STAMPS"] if phase_stamps else [])
-    lib = STAMPS_LIB if phase_stamps else LIB
+    flags = FLAGS + (["-DKVQ_PHASE_STAMPS"] if phase_stamps else []) + (["-DKVQ_NO_ARITHMETIC"] if no_arithmetic else [])
+    lib = STAMPS_LIB if phase_stamps else NOARITH_LIB if no_arithmetic else LIB
+    suffix = ".stamps.o" if phase_stamps else ".noarith.o" if no_arithmetic else ".o"
     for src in SOURCES:
-        obj = os.path.join(CSRC, os.path.splitext(src)[0] + (".stamps.o" if phase_stamps else ".o"))
+        obj = os.path.join(CSRC, os.path.splitext(src)[0] + suffix)
         cmd = [hipcc, *flags, "-I", os.path.join(HERE, "..", "include"), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -48,4 +52,4 @@ def build(verbose: bool = False, phase_stamps: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv, phase_stamps="--phase-stamps" in sys.argv))
+    print(build(verbose="-v" in sys.argv, phase_stamps="--phase-stamps" in sys.argv, no_arithmetic="--no-arithmetic" in sys.argv))

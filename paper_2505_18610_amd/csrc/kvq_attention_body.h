@@ -164,6 +164,19 @@ __device__ inline void load_string(const uint8_t* tile, uint32_t lane_off, uint3
     }
 }
 
+// Measurement build without arithmetic (python -m paper_2505_18610_amd.build --no-arithmetic): every load of a tile is
+// issued and waited for as in the library, claims, descriptors, the join and the merge of the splits run as they do,
+// but no tile is computed on.  Its launch time is the floor that the launch structure and memory leave to any
+// arithmetic; its results are meaningless.  Nothing but paper_2505_18610_amd/phase_table.py --floor loads it.
+#ifdef KVQ_NO_ARITHMETIC
+template <int N>
+__device__ inline void keep_loaded(const uint32_t (&w)[N]) {
+#pragma unroll
+    for (int e = 0; e < N; ++e) asm volatile("" :: "v"(w[e]));
+}
+__device__ inline void keep_loaded(const u32x4& v) { asm volatile("" :: "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
+#endif
+
 struct WaveState {
     float4v o[8];   // out^T accumulators: o[nt][i] = channel 16nt + 4j + i of head n (lane = 16j + n)
     float4v zl;     // quarter 0: zero-point sums of V groups 0..3; quarter 1, element 0: softmax denominator
@@ -483,6 +496,15 @@ __device__ inline void wave_lds_sync() {  // orders LDS traffic between the lane
 template <int B, int TPI, bool SAFE>
 __device__ inline void compute_stage(WaveState& st, const QOps& Q, const Stage<B, TPI>& sg, uint8_t* meta_lds,
                                      int n_tokens, float scale_log2, int lane) {
+#ifdef KVQ_NO_ARITHMETIC
+#pragma unroll
+    for (int k = 0; k < TPI; ++k) {
+        keep_loaded(sg.kw[k]);
+        keep_loaded(sg.vw[k]);
+        keep_loaded(sg.meta[k]);
+    }
+    return;
+#endif
     if constexpr (B < 16) {
 #pragma unroll
         for (int k = 0; k < TPI; ++k)
@@ -641,11 +663,17 @@ __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds,
             float s[1][2][4];
             uint32_t pop[1][4];
             const int tok0[1] = {(cur.tile + k) * KVQ_TILE_TOKENS};
+#ifdef KVQ_NO_ARITHMETIC
+            keep_loaded(kw);
+            keep_loaded(mreg);
+            s[0][0][0] = 0.f;
+#else
             if constexpr (has_meta<B>()) {
                 *reinterpret_cast<u32x4*>(meta_lds + lane * 16) = mreg;
                 wave_lds_sync();
             }
             scores_tile<B>(Q, kw, meta_lds, c.scale_log2, lane, s[0]);
+#endif
             const uint8_t *code, *meta;
             bool more;
             if (k + 1 < cur.nt) {  // next tile of the same chunk
@@ -659,6 +687,13 @@ __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds,
                 more = c.next.bits == (uint32_t)W;
                 if (more) { cur = c.next; k = 0; code = cur.code; meta = cur.meta; }
             }
+#ifdef KVQ_NO_ARITHMETIC
+            if (!more) { keep_loaded(vw); return; }
+            load_string<2 * W>(code, c.lane_off, kw);
+            if constexpr (has_meta<B>()) mreg = load_stream16(meta + c.lane_off);
+            keep_loaded(vw);
+            load_string<2 * W>(code + 512u * W, c.lane_off, vw);
+#else
             if (!more) {  // last tile of the run
                 softmax_stage<B, 1>(st, s, tok0, c.n_tokens, lane, pop);
                 accumulate_tile<B, SAFE>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
@@ -671,6 +706,7 @@ __device__ inline void run_chunks(WaveState& st, QOps& Q, const _Float16* q_lds,
             accumulate_tile<B, SAFE>(st, vw, meta_lds, meta_lds + KVQ_WAVE_LDS_CONST, pop[0], lane);
             if constexpr (has_meta<B>()) wave_lds_sync();
             load_string<2 * W>(code + 512u * W, c.lane_off, vw);
+#endif
         }
     } else {
         // narrow tiles: a ring of N register stages of TPI tiles each, N - 1 of them in flight

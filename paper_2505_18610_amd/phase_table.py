@@ -5,6 +5,10 @@
     python paper_2505_18610_amd/phase_table.py --launch-only 14b-2   # 64 launches of the library proper and nothing
                                                                      # else: the program to put behind rocprofv3 --pmc
 
+    python -m paper_2505_18610_amd.build --no-arithmetic       # builds libkvq_noarith.so
+    python -m paper_2505_18610_amd.phase_table --floor 32b 70b 14b-2 14b-4 14b-8 7b
+                                                               # the launch with and without its arithmetic
+
 The measurement build records the device wall clock when thread 0 of every workgroup passes the points listed in
 csrc/kvq_phase_stamps.h.  Launches run in back-to-back trains (as in bench.py); the stamps of the last launch of
 several trains are read and averaged.  Beside them the script times the same trains with the library proper, whose
@@ -158,8 +162,50 @@ def main(names):
         del cache, arena
 
 
+# split counts tried beside the library's own plan (0) in the floor table: 192 workgroups where the plan uses 256
+FLOOR_SPLITS = {"32b": (0, 6), "14b-2": (0, 3)}
+PLANNED_SPLITS = {"32b": 8, "70b": 32, "7b": 3, "14b-2": 4, "14b-4": 3, "14b-8": 3}  # what the library chooses (see main())
+
+
+def floor(names):
+    """The library proper against the build without arithmetic (libkvq_noarith.so: every tile loaded, none computed
+    on; claims, join and merge of the splits as in the library), alternating on one arena; fastest of several trains."""
+    import torch
+    lib_n = os.path.join(HERE, "libkvq_noarith.so")
+    if not os.path.exists(lib_n):
+        raise SystemExit("build the measurement variant first: python -m paper_2505_18610_amd.build --no-arithmetic")
+    kqs = (("library", _binding(os.path.join(HERE, "libkvq.so"), "proper")), ("no arithmetic", _binding(lib_n, "noarith")))
+    L = 8
+    print("| block | workgroups | MB per launch | library (us) | of 8 TB/s | no arithmetic (us) | of 8 TB/s | arithmetic costs (us) |")
+    print("|---|---|---|---|---|---|---|---|")
+    for name in names:
+        tiers, kw = SHAPES[name]
+        units = kw["B"] * kw["Hkv"]
+        arena = None
+        for splits in FLOOR_SPLITS.get(name, (0,)):
+            best = {}
+            for rnd in range(3):
+                for tag, kq in kqs:
+                    cache, arena, q, out = _build_cache(kq, torch, tiers, L=L, arena=arena, **kw)
+                    if splits:
+                        cache.kvq_cache_set_option(kq.KVQ_OPT_SPLITS, splits)
+                    for _ in range(20 if rnd else 60):            # sustained clocks
+                        for layer in range(L):
+                            cache.kvq_decode_attention(layer, q, out)
+                    best[tag] = min(best.get(tag, 1e9), _train_us(torch, cache, q, out, L))
+                    nbytes = cache.kvq_cache_describe(0)[1]
+                    cache.close()
+            a, b = best["library"], best["no arithmetic"]
+            wg = f"{units} x {splits or PLANNED_SPLITS[name]} = {units * (splits or PLANNED_SPLITS[name])}"
+            print(f"| {name} | {wg} | {nbytes / 1e6:.1f} | {a:.2f} | {nbytes / a / 80e3:.1f} % | {b:.2f} | "
+                  f"{nbytes / b / 80e3:.1f} % | {a - b:.2f} |", flush=True)
+        del arena
+
+
 if __name__ == "__main__":
-    if "--launch-only" in sys.argv:
+    if "--floor" in sys.argv:
+        floor([a for a in sys.argv[1:] if a != "--floor"] or ["32b"])
+    elif "--launch-only" in sys.argv:
         launch_only([a for a in sys.argv[1:] if a != "--launch-only"] or ["32b"])
     else:
         main(sys.argv[1:] or ["32b"])
