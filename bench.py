@@ -777,6 +777,9 @@ def main():
     prop = torch.cuda.get_device_properties(0)
     result["device"] = {"name": prop.name, "compute_units": prop.multi_processor_count,
                         "hbm_GiB": round(prop.total_memory / 2 ** 30, 1)}
+    for key, attr in (("max_engine_clock_MHz", "clock_rate"), ("max_memory_clock_MHz", "memory_clock_rate")):
+        if getattr(prop, attr, None):  # nominal maxima the runtime reports (kHz), not a reading under load
+            result["device"][key] = round(getattr(prop, attr) / 1000)
     print(json.dumps(result))
 
 

@@ -64,11 +64,7 @@ template <int B>
 __device__ inline void load_chunks_stream(const uint8_t* tile, int lane, uint32_t (&str)[2 * B]) {
 #pragma unroll
     for (int c = 0; c < B / 2; ++c) {
-#ifdef KVQ_TRY_PLAIN_LOADS
-        u32x4 v = *reinterpret_cast<const u32x4*>(tile + (c * 64 + lane) * 16);
-#else
         u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + (c * 64 + lane) * 16));
-#endif
         str[4 * c] = v.x; str[4 * c + 1] = v.y; str[4 * c + 2] = v.z; str[4 * c + 3] = v.w;
     }
 }
