@@ -841,7 +841,7 @@ __device__ inline void merge_splits(const KvqAttnParams& P, int unit, int tid, f
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
         const int sp = sgi + k * G;
-        const uint32_t off = active ? (uint32_t)((sp * 16 + head) * KVQ_D + 4 * d4) * 4u : 0xfffffff0u;
+        const uint32_t off = active ? (uint32_t)((sp * 16 + head) * KVQ_D + 4 * d4) * 4u : 0x80000000u;
         v[k] = float4v{0.f, 0.f, 0.f, 0.f};
         if (k < 4 || many)
             v[k] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(slab, (int)off, 0, AGENT ? 16 : 0));

@@ -77,13 +77,13 @@ __global__ __launch_bounds__(64 * KVQ_APPEND_WG_WAVES) void kvq_append_q_kernel(
         const int tok = tok0 + 16 * pass + (lane >> 2);
         u32x4 v[4];
         if (PLAIN || which) {
-            // Buffer loads with the unit's n_new rows as the buffer: a lane whose token is not new (before t_old: the
-            // offset wraps to a huge value; at or after t_new: beyond the last row) is out of range and reads zeros,
-            // which is what such a token quantizes -- no branch, no select.  (n_new < 2^23: the offsets cannot wrap
-            // back into the buffer.)
+            // Buffer loads with the unit's n_new rows as the buffer: a lane whose token is not new (before t_old or at
+            // or after t_new) gets an offset beyond the buffer (n_new < 2^23 rows of 256 bytes end below 2^31) and
+            // reads zeros, which is what such a token quantizes -- no branch around the loads.
             const __amdgpu_buffer_rsrc_t rows =
                 __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(in), 0, n_new * (KVQ_D * 2), 0x00020000);
-            const uint32_t off = (uint32_t)(tok - t_old) * (uint32_t)(KVQ_D * 2) + 64u * grp;
+            const uint32_t rel = (uint32_t)(tok - t_old);
+            const uint32_t off = (rel < (uint32_t)n_new ? rel * (uint32_t)(KVQ_D * 2) : 0x80000000u) + 64u * grp;
 #pragma unroll
             for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(rows, (int)(off + 16u * c), 0, 0);
         } else {
