@@ -25,7 +25,8 @@
  *     are updated at enqueue time, the device tables in stream order).
  *   - Errors are reported as kvq_status_t; argument, state and budget errors are detected on the host before
  *     anything is enqueued and leave the cache unchanged.  Nothing throws or aborts across this boundary.
- *     KVQ_E_OOM of an append is found before anything changes as well.  A HIP failure (KVQ_E_HIP) while a call is
+ *     KVQ_E_OOM of an append is found before anything changes as well (the blocks of the new pages and those that
+ *     pages leaving the window are quantized into are taken first).  A HIP failure (KVQ_E_HIP) while a call is
  *     being enqueued can strike after the host tables have been updated; the block is then marked unusable: every
  *     later call on it returns KVQ_E_STATE until kvq_cache_reset empties it (other blocks are unaffected).
  *   - All sequences of one cache have the same length and share one page table per block; sequences of different

@@ -277,14 +277,39 @@ bool alloc_lowerings(kvq_cache* c, std::vector<Lowering>& low) {
     return true;
 }
 
+// Pages of the integer 16-bit tier go down one halving at a time; raw fp16 pages reach any width in one step.
+bool lowers_in_steps(const kvq_cache* c, const std::vector<Lowering>& low) {
+    return !low.empty() && c->int16() && low[0].from == 16 && low[0].to < 8;
+}
+
+// Destination blocks of the first step of run_lowerings, taken ahead of it (so that a caller can find out that the
+// arena is full before it changes anything), and their release when that caller gives up.  A later step of a chain
+// cannot run out of blocks: each step has just freed a larger block per page than the next one takes.
+bool alloc_first_step(kvq_cache* c, std::vector<Lowering>& low) {
+    if (low.empty()) return true;
+    const int to = low[0].to;
+    const bool steps = lowers_in_steps(c, low);
+    if (steps) for (auto& w : low) w.to = 8;
+    const bool ok = alloc_lowerings(c, low);
+    if (steps) for (auto& w : low) w.to = to;
+    return ok;
+}
+void release_first_step(kvq_cache* c, std::vector<Lowering>& low) {
+    const bool steps = lowers_in_steps(c, low);
+    for (auto& w : low) {
+        c->buddy.release(w.new_code, order_of_bits(steps ? 8 : w.to));
+        if (!c->has_meta(w.from)) c->buddy.release(w.new_meta, 0);
+    }
+}
+
 // Enqueue the kernel for lowerings that all share (from, to) -- one halving, or fp16 values to any width -- then
-// commit the host tables.
-kvq_status_t run_lowering_step(kvq_cache* c, int layer, std::vector<Lowering>& low, hipStream_t s) {
+// commit the host tables.  allocated: the destination blocks are in `low` already.
+kvq_status_t run_lowering_step(kvq_cache* c, int layer, std::vector<Lowering>& low, hipStream_t s, bool allocated = false) {
     if (low.empty()) return KVQ_OK;
     Layer& L = c->layers[(size_t)layer];
     const int from = low[0].from, to = low[0].to;
     const bool fresh_meta = !c->has_meta(from);  // raw fp16 pages carry no metadata yet
-    if (!alloc_lowerings(c, low)) return KVQ_E_OOM;
+    if (!allocated && !alloc_lowerings(c, low)) return KVQ_E_OOM;
     if (!c->dry) {
         std::vector<KvqRequantJob> jobs(low.size());
         for (size_t i = 0; i < low.size(); ++i) {
@@ -329,13 +354,19 @@ kvq_status_t run_lowering_step(kvq_cache* c, int layer, std::vector<Lowering>& l
 
 // Lower a set of pages that share (from, to).  Pages of the integer 16-bit tier go down one halving at a time
 // (16 -> 8 -> 4 -> 2 by the configured shift strategy); raw fp16 pages are quantized to the target width directly.
-kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, hipStream_t s) {
+// first_allocated: alloc_first_step has been called on `low`.
+kvq_status_t run_lowerings(kvq_cache* c, int layer, std::vector<Lowering>& low, hipStream_t s, bool first_allocated = false) {
     if (low.empty()) return KVQ_OK;
-    const int from = low[0].from, to = low[0].to;
-    if (!(c->int16() && from == 16 && to < 8)) return run_lowering_step(c, layer, low, s);
+    const int to = low[0].to;
+    if (!lowers_in_steps(c, low)) return run_lowering_step(c, layer, low, s, first_allocated);
     for (int b = 8; b >= to; b /= 2) {
-        for (auto& w : low) { w.from = 2 * b; w.to = b; w.new_code = w.new_meta = 0; }
-        kvq_status_t st = run_lowering_step(c, layer, low, s);
+        const bool have = first_allocated && b == 8;
+        for (auto& w : low) {
+            w.from = 2 * b;
+            w.to = b;
+            if (!have) w.new_code = w.new_meta = 0;
+        }
+        kvq_status_t st = run_lowering_step(c, layer, low, s, have);
         if (st != KVQ_OK) return st;  // the pages stay at the width they reached
     }
     return KVQ_OK;
@@ -573,12 +604,24 @@ kvq_status_t commit_append(kvq_cache_t* c, int32_t layer, const AppendPlan& pl, 
         }
         fresh.push_back(p);
     }
-    kvq_status_t st = ensure_device(c, s);
-    if (st != KVQ_OK) {
+    auto release_fresh = [&]() {
         for (Page& q : fresh) {
             c->buddy.release(q.code_unit, order_of_bits(e));
             if (c->has_meta(e)) c->buddy.release(q.meta_unit, 0);
         }
+    };
+    // pages that leave the window in this call are lowered behind the append: their destination blocks are taken now,
+    // while a full arena can still be reported with nothing changed
+    std::vector<Lowering> low;
+    for (int i : pl.evicted) low.push_back(Lowering{i, 16, pl.bcur});
+    if (!alloc_first_step(c, low)) {
+        release_fresh();
+        return KVQ_E_OOM;
+    }
+    kvq_status_t st = ensure_device(c, s);
+    if (st != KVQ_OK) {
+        release_first_step(c, low);
+        release_fresh();
         return st;
     }
     const int t_old = L.T, T = pl.T;
@@ -588,7 +631,11 @@ kvq_status_t commit_append(kvq_cache_t* c, int32_t layer, const AppendPlan& pl, 
     L.version++;
     // From here on the host tables count the new tokens: a failing enqueue leaves the block unusable (poisoned).
     st = upload_table(c, layer, (int)old_pages, (int)L.pages.size(), s);
-    if (st != KVQ_OK) { L.poisoned = true; return st; }
+    if (st != KVQ_OK) {
+        release_first_step(c, low);
+        L.poisoned = true;
+        return st;
+    }
     if (!c->dry && defer && n_new == 1 && e == 16 && (!c->int16() || defer->int16_too)) {
         defer->active = true;
         defer->t_old = t_old;
@@ -606,14 +653,13 @@ kvq_status_t commit_append(kvq_cache_t* c, int32_t layer, const AppendPlan& pl, 
                               by_arg ? two : nullptr, pg0, c->flags_dev(), c->cfg.group,
                               L.reparam ? c->lambda_dev(layer) + c->cfg.n_kv_heads * KVQ_D : nullptr, c->cfg.n_kv_heads,
                               cos_sin_dev, c->int16(), s) != hipSuccess) {
+            release_first_step(c, low);
             L.poisoned = true;
             return KVQ_E_HIP;
         }
     }
-    if (!pl.evicted.empty()) {
-        std::vector<Lowering> low;
-        for (int i : pl.evicted) low.push_back(Lowering{i, 16, pl.bcur});
-        st = run_lowerings(c, layer, low, s);
+    if (!low.empty()) {
+        st = run_lowerings(c, layer, low, s, true);
         if (st != KVQ_OK) { L.poisoned = true; return st; }  // the plan counted these pages at their new width
     }
     return KVQ_OK;

@@ -31,8 +31,40 @@ int main(int argc, char** argv) {
         const uint64_t ab = kvq_arena_bytes(&cfg, (uint64_t)cfg.n_layers * cfg.batch * cfg.n_kv_heads * (uint64_t)cfg.max_tokens * 600 * (R(0, 3) ? 1 : 0) + (1 << 20) * (uint64_t)R(0, 4));
         kvq_status_t st = kvq_cache_create(&cfg, budget.data(), fbit.data(), nullptr, ab, &c);
         if (st != KVQ_OK) { errs[st]++; continue; }
-        if (R(0, 3) == 0) kvq_cache_set_option(c, KVQ_OPT_TIER16, 1);
+        int int16 = 0;
+        if (R(0, 3) == 0 && kvq_cache_set_option(c, KVQ_OPT_TIER16, 1) == KVQ_OK) int16 = 1;
+        // invariants of the accounting (Sec. 3.1-3.2), checked after every call: the runs of equal width tile
+        // [0, T) in order, widths are 16/8/4/2 and not below the block's Fbit (unless the caller itself put tokens
+        // at a lower width, which explicit entry widths and the lowering of a named run allow), the bytes in use are the runs' tokens times the bytes
+        // of a token at the run's width, and they never exceed the block's budget
+        std::vector<char> below((size_t)cfg.n_layers, 0);
+        auto check = [&](int when) -> bool {
+            for (int l = 0; l < cfg.n_layers; ++l) {
+                kvq_segment_info_t segs[256]; int n = 0; uint64_t used = 0; int T = 0, cur = 0;
+                if (kvq_cache_describe(c, l, segs, 256, &n, &used, &T, &cur) != KVQ_OK) continue;  // poisoned or > 256 runs
+                uint64_t want = 0; int t = 0;
+                for (int i = 0; i < n; ++i) {
+                    const int b = segs[i].bits;
+                    if (segs[i].token_begin != t || segs[i].token_end <= t || (b != 16 && b != 8 && b != 4 && b != 2) ||
+                        (b < fbit[(size_t)l] && !below[(size_t)l])) {
+                        printf("seed %d op %d: bad run %d of block %d: tokens [%d, %d) at %d bits, previous run ended at %d, Fbit %d\n",
+                               seed, when, i, l, segs[i].token_begin, segs[i].token_end, b, t, (int)fbit[(size_t)l]);
+                        return false;
+                    }
+                    want += (uint64_t)(segs[i].token_end - t) * cfg.batch * cfg.n_kv_heads *
+                            kvq_bytes_per_token_head(b, 128, cfg.group, cfg.count_metadata_in_budget, int16);
+                    t = segs[i].token_end;
+                }
+                if (t != T || T > cfg.max_tokens || used != want || used > budget[(size_t)l]) {
+                    printf("seed %d op %d block %d: T %d/%d, bytes %llu, runs give %llu, budget %llu\n", seed, when, l, t, T,
+                           (unsigned long long)used, (unsigned long long)want, (unsigned long long)budget[(size_t)l]);
+                    return false;
+                }
+            }
+            return true;
+        };
         for (int op = 0; op < 400; ++op, ++ops) {
+            if (!check(op)) return 1;
             int layer = R(0, 30) ? R(0, cfg.n_layers - 1) : R(-1, cfg.n_layers);  // sometimes invalid
             int what = R(0, 9);
             if (what <= 5) {
@@ -40,6 +72,7 @@ int main(int argc, char** argv) {
                 int eb = R(0, 4) ? 0 : (R(0, 5) == 5 ? 3 : 2 << R(0, 3));
                 st = kvq_quantize_append(c, layer, nullptr, nullptr, n, eb, nullptr);
                 errs[st]++;
+                if (st == KVQ_OK && eb != 0 && layer >= 0 && layer < cfg.n_layers && eb < fbit[(size_t)layer]) below[(size_t)layer] = 1;
                 if (st == KVQ_E_BUDGET) {
                     int done = -1;
                     st = kvq_progressive_requant(c, layer, -1, n > 0 ? n : 0, nullptr, &done);
@@ -51,10 +84,17 @@ int main(int argc, char** argv) {
                 errs[st]++;
             } else if (what == 7) {
                 int done = -1;
-                st = kvq_progressive_requant(c, layer, R(-1, 6), R(0, 40), nullptr, &done);
+                const int seg = R(-1, 6);
+                st = kvq_progressive_requant(c, layer, seg, R(0, 40), nullptr, &done);
                 errs[st]++;
+                // lowering a named run is the policy-free mechanism: it may go below Fbit, like an explicit entry width
+                if (st == KVQ_OK && seg >= 0 && layer >= 0 && layer < cfg.n_layers) below[(size_t)layer] = 1;
             } else if (what == 8) {
-                if (R(0, 9) == 0) { st = kvq_cache_reset(c, R(-1, cfg.n_layers - 1)); errs[st]++; }
+                if (R(0, 9) == 0) {
+                    const int which = R(-1, cfg.n_layers - 1);
+                    st = kvq_cache_reset(c, which); errs[st]++;
+                    if (st == KVQ_OK) for (int l = 0; l < cfg.n_layers; ++l) if (which < 0 || which == l) below[(size_t)l] = 0;
+                }
                 else { st = kvq_cache_set_option(c, R(0, 9), R(-1, 300)); errs[st]++; }
             } else {
                 float q[4]; st = kvq_decode_attention(c, layer, q, q, 0, 0.f, nullptr); errs[st]++;

@@ -451,3 +451,38 @@ int main() {
     assert r.returncode == 0, r.stderr
     r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
     assert r.returncode == 0 and r.stdout.strip() == "ok", (r.returncode, r.stdout, r.stderr)
+
+
+def test_append_that_finds_the_arena_full_changes_nothing():
+    """KVQ_E_OOM of an append is found before anything changes, also when the blocks that are missing are those of the
+    pages leaving the window in that call (policy PAPER with a window quantizes them behind the append, Sec. 4.1.2):
+    the block is as it was and stays usable (no call on it returns KVQ_E_STATE); the append goes through once a
+    halving has made room."""
+    P, W = 64, 64
+    cfg = kq.KvqConfig(1, 3, 8, 4, 8192, page_tokens=P, window=W, policy=POLICY_PAPER, count_metadata_in_budget=0)
+    hit = 0
+    for payload_pages in range(10, 34):
+        payload = payload_pages * P * 12 * 512 // 2          # arenas that fill up at different points of the sequence
+        gc = kq.KvqCache(cfg, [1 << 60], [2], arena=None, arena_bytes=kq.kvq_arena_bytes(cfg, payload))
+        gc.kvq_quantize_append(0, None, None, n_new=3 * P)
+        gc.kvq_progressive_requant(0)                         # 16 -> 8: pages leaving the window now go to 8 bits
+        for step in range(400):
+            before = gc.kvq_cache_describe(0)
+            try:
+                gc.kvq_quantize_append(0, None, None, n_new=P)
+                continue
+            except kq.KvqError as e:
+                assert e.status == kq.KVQ_E_OOM, e.status
+            hit += 1
+            assert gc.kvq_cache_describe(0) == before
+            if before[3] == 2:
+                break
+            try:                                              # still usable: a halving is carried out ...
+                assert gc.kvq_progressive_requant(0) > 0
+            except kq.KvqError as e:                          # ... unless its own destination blocks do not fit either
+                assert e.status == kq.KVQ_E_OOM, e.status
+                assert gc.kvq_cache_describe(0) == before
+                break
+            gc.kvq_quantize_append(0, None, None, n_new=P)    # and the same append now goes through
+        gc.close()
+    assert hit >= 24
