@@ -486,3 +486,63 @@ def test_append_that_finds_the_arena_full_changes_nothing():
             gc.kvq_quantize_append(0, None, None, n_new=P)    # and the same append now goes through
         gc.close()
     assert hit >= 24
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_bookkeeping_matches_oracle_on_random_call_sequences(seed):
+    """Random configurations and random calls -- appends at the policy's and at explicit widths, halvings under the
+    policy, lowerings of a named run, resets -- on an accounting-only cache and on the oracle's cache: after every call
+    both are in the same state, and a call one of them refuses the other refuses for the same kind of reason."""
+    rng = np.random.default_rng(1000 + seed)
+    P = int(rng.choice([32, 64]))
+    policy = int(rng.choice([POLICY_PAPER, POLICY_OLDEST_FIRST]))
+    W, sink = P * int(rng.integers(0, 3)), P * int(rng.integers(0, 2))
+    fbit = int(rng.choice([2, 4, 8]))
+    tier16 = int(rng.choice([0, TIER16_INT16]))
+    meta = int(rng.integers(0, 2))
+    group = int(rng.choice([32, 64, 128]))
+    Tmax = P * int(rng.integers(6, 20))
+    per16 = bytes_per_token_head(16, 128, group, bool(meta), bool(tier16))
+    budget = int(rng.integers(2 * P, Tmax)) * per16 // int(rng.choice([1, 2, 4]))
+    oc, gc = _pair(policy, P, W, sink, budget, fbit, meta=meta, Tmax=Tmax, B=1, H=1, group=group, tier16=tier16)
+    K, V = kvq_synth.make_kv(seed, 0, 1, 1, 0, Tmax, rope_base=None)
+
+    def both(o_call, g_call):
+        """Runs the call on both sides; returns the kind of outcome, which must agree."""
+        try:
+            o_res, o_kind = o_call(), "ok"
+        except BudgetError:
+            o_res, o_kind = None, kq.KVQ_E_BUDGET
+        except StateError:
+            o_res, o_kind = None, kq.KVQ_E_STATE
+        try:
+            g_res, g_kind = g_call(), "ok"
+        except kq.KvqError as e:
+            g_res, g_kind = None, e.status
+        assert o_kind == g_kind, (o_kind, g_kind)
+        if o_kind == "ok" and o_res is not None:
+            assert o_res == g_res
+        return o_kind
+
+    for step in range(120):
+        T = oc.layers[0].T
+        what = int(rng.integers(0, 10))
+        if what <= 5:
+            n = int(rng.integers(1, 2 * P))
+            eb = 0 if rng.integers(0, 4) else int(rng.choice([16, 8, 4, 2]))
+            if T + n > Tmax:   # the oracle needs the rows it is handed to exist
+                both(lambda: (_ for _ in ()).throw(StateError("max_tokens exceeded")),
+                     lambda: gc.kvq_quantize_append(0, None, None, n_new=n, entry_bits=eb))
+            else:
+                both(lambda: oc.append(0, K[:, :, T:T + n], V[:, :, T:T + n], eb),
+                     lambda: gc.kvq_quantize_append(0, None, None, n_new=n, entry_bits=eb))
+        elif what <= 7:
+            r = int(rng.integers(0, P))
+            both(lambda: oc.requant(0, reserve_tokens=r), lambda: gc.kvq_progressive_requant(0, reserve_tokens=r))
+        elif what == 8:
+            sg = int(rng.integers(0, 5))
+            both(lambda: oc.requant(0, segment=sg), lambda: gc.kvq_progressive_requant(0, segment=sg))
+        elif rng.integers(0, 4) == 0:
+            oc, _ = _pair(policy, P, W, sink, budget, fbit, meta=meta, Tmax=Tmax, B=1, H=1, group=group, tier16=tier16)
+            gc.kvq_cache_reset(0)
+        _same_state(oc, gc)
