@@ -513,7 +513,7 @@ def test_ranges_longer_than_the_descriptor_window():
     B, H, P, n_pages = 1, 1, 96, 300
     T = P * n_pages - 17
     K, V = kvq_synth.make_kv(160, 0, B, H, 0, T)
-    oc, gc = make_pair(1, B, 4 * H, H, P * n_pages, P)
+    oc, gc = make_pair(1, B, 4 * H, H, P * n_pages, P, policy=POLICY_OLDEST_FIRST)  # new tokens enter at 16 bits
     t = 0
     for n, bits in ((P * 90, 2), (P * 60, 4), (P * 100, 8), (T - P * 250, 16)):
         append_both(oc, gc, 0, K[:, :, t:t + n], V[:, :, t:t + n], bits)
@@ -524,6 +524,20 @@ def test_ranges_longer_than_the_descriptor_window():
         for n in (1, 2, 3, 0):
             gc.kvq_cache_set_option(kq.KVQ_OPT_SPLITS, n)
             check_attention(oc, gc, 0, q)
+    # decode steps on the same cache: the launch appends its token, whose tile is in the last of the windows
+    K2, V2 = kvq_synth.make_kv(161, 0, B, H, T, T + 6)
+    out = torch.empty((B, 4 * H, 128), dtype=torch.float32, device="cuda")
+    for i, (det, n) in enumerate(((0, 1), (1, 1), (0, 2), (1, 2), (0, 3), (0, 0))):
+        gc.kvq_cache_set_option(kq.KVQ_OPT_DETERMINISTIC, det)
+        gc.kvq_cache_set_option(kq.KVQ_OPT_SPLITS, n)
+        k1, v1 = K2[:, :, i:i + 1], V2[:, :, i:i + 1]
+        q = kvq_synth.make_q(161, 0, B, 4 * H, T + i)
+        oc.append(0, k1, v1)
+        gc.kvq_append_decode_attention(0, dev(k1), dev(v1), dev(q), out)
+        torch.cuda.synchronize()
+        mx, rl = attention_errors(out.cpu().numpy(), oc.attention(0, q))
+        assert mx <= MAX_ABS and rl <= REL_L2, (det, n, mx, rl)
+    assert_same_cache(oc, gc, 0)
 
 
 def test_softmax_scale_and_multi_layer():
