@@ -446,6 +446,28 @@ def measure_read_ceiling(kq, torch, cache):
     return round(best, 1)
 
 
+def read_clock_state():
+    """Clock levels and power policy of the first GPU as the kernel driver exposes them (sysfs; the level marked
+    current is the one at the moment of reading, right behind the timed steps).  Empty where sysfs has no such files."""
+    import glob
+    state = {}
+    for card in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        for key, name in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk"), ("performance_level", "power_dpm_force_performance_level")):
+            try:
+                text = open(os.path.join(card, name)).read().strip()
+            except OSError:
+                continue
+            if key == "performance_level":
+                state[key] = text
+            else:
+                lines = [l.strip() for l in text.splitlines() if l.strip()]
+                state[key + "_levels"] = [l.split(":", 1)[1].replace("*", "").strip() for l in lines if ":" in l]
+                state[key + "_current"] = next((l.split(":", 1)[1].replace("*", "").strip() for l in lines if l.endswith("*")), None)
+        if state:
+            break
+    return state
+
+
 def library_source_sha16():
     """Hash of the library's sources (kernels, host code, public header): ties stored counter results to the code."""
     import glob
@@ -663,6 +685,7 @@ def main():
     t_issue = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    clocks = read_clock_state()  # outside the timed region, right behind it
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     _, _, T_end, _ = cache.kvq_cache_describe(0)
     T_mid = T_end - args.steps / 2.0
@@ -777,9 +800,7 @@ def main():
     prop = torch.cuda.get_device_properties(0)
     result["device"] = {"name": prop.name, "compute_units": prop.multi_processor_count,
                         "hbm_GiB": round(prop.total_memory / 2 ** 30, 1)}
-    for key, attr in (("max_engine_clock_MHz", "clock_rate"), ("max_memory_clock_MHz", "memory_clock_rate")):
-        if getattr(prop, attr, None):  # nominal maxima the runtime reports (kHz), not a reading under load
-            result["device"][key] = round(getattr(prop, attr) / 1000)
+    result["device"]["clocks"] = clocks
     print(json.dumps(result))
 
 
