@@ -171,26 +171,45 @@ __global__ __launch_bounds__(64) void kvq_append_i16_kernel(uint8_t* __restrict_
     const int t_new = t_old + n_new, tok0 = tile * KVQ_TILE_TOKENS;
     const uint16_t* in = (which ? v_in : k_in) + (uint64_t)unit * n_new * KVQ_D;
     const int grp = lane & 3;
+    // every load of the tile first, as in kvq_append_q_kernel: rows that need neither rotation nor reparameterization
+    // come through range-checked buffer loads (a token that is not new reads zeros)
+    const bool plain = which || (!rope && !rinv);  // wavefront-uniform
+    uint32_t w[2][16];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tok = tok0 + 16 * pass + (lane >> 2);
+        u32x4 v[4];
+        if (plain) {
+            const __amdgpu_buffer_rsrc_t rows =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(in), 0, n_new * (KVQ_D * 2), 0x00020000);
+            const uint32_t rel = (uint32_t)(tok - t_old);
+            const uint32_t off = (rel < (uint32_t)n_new ? rel * (uint32_t)(KVQ_D * 2) : 0x80000000u) + 64u * grp;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[c] = __builtin_amdgcn_raw_buffer_load_b128(rows, (int)(off + 16u * c), 0, 0);
+        } else {
+            const bool isnew = tok >= t_old && tok < t_new;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[c] = u32x4{0u, 0u, 0u, 0u};
+            if (isnew) {
+                const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    v[c] = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr,
+                                     rinv ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            w[pass][4 * c] = v[c].x; w[pass][4 * c + 1] = v[c].y; w[pass][4 * c + 2] = v[c].z; w[pass][4 * c + 3] = v[c].w;
+        }
+    }
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
         const int tl = 16 * pass + (lane >> 2);
         const int tok = tok0 + tl;
-        const bool isnew = tok >= t_old && tok < t_new;
-        uint32_t w[16];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (isnew) {
-                const uint16_t* row = in + (uint64_t)(tok - t_old) * KVQ_D;
-                if (which) v = *reinterpret_cast<const u32x4*>(row + 32 * grp + 8 * c);
-                else v = load_key8(row, 32 * grp + 8 * c, rope ? rope + (uint64_t)(tok - t_old) * KVQ_D : nullptr,
-                                   rinv ? rinv + (unit % n_kv_heads) * KVQ_D : nullptr);
-            }
-            w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
-        }
         float codes[32], lo[32];
         uint16_t S, Z;
-        quantize_owner<16>(w, codes, &S, &Z, gspan);
+        quantize_owner<16>(w[pass], codes, &S, &Z, gspan);
 #pragma unroll
         for (int e = 0; e < 32; ++e) {  // exact: integers below 2^16
             const float hi = floorf(codes[e] * 0.00390625f);
@@ -235,14 +254,6 @@ __global__ __launch_bounds__(64) void kvq_append_i16_kernel(uint8_t* __restrict_
     }
 }
 
-// ------------------------------------------------------------------------------------- fp16 page -> b bits
-// grid.x = 2 * n_jobs * tiles_per_page, grid.y = unit, 64 threads.  Direct quantization (Eq. 1-2) of a page
-// that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by
-// owner lanes exactly like an append.
-// ------------------------------------------------------------------------------------- fp16 page -> b bits
-// grid.x = 2 * n_jobs * tiles_per_page, grid.y = unit, 64 threads.  Direct quantization (Eq. 1-2) of a page
-// that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by
-// owner lanes exactly like an append.
 // ------------------------------------------------------------------------------------- fp16 page -> b bits
 // grid.x = 2 * n_jobs * tiles_per_page, grid.y = unit, 64 threads.  Direct quantization (Eq. 1-2) of a page
 // that still holds raw fp16 values: the tile is first laid out [token][channel] in LDS, then quantized by
